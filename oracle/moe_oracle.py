@@ -1,0 +1,281 @@
+"""CPU oracle for the W4A16 mixture-of-experts layer (TEST INFRASTRUCTURE).
+
+Plain, slow, obviously-correct NumPy: explicit nibble unpack, exact
+dequantisation, float64 matmuls, explicit rounding to the 16-bit storage type
+at the four tensors the staged interface materialises (H, act, Y, out), and a
+float64 weighted combine.  Nothing here is blocked, fused or reordered, and
+nothing is shared with the HIP path.  Only tests, the smoke check and the
+benchmark's cpu_baseline leg may import this module; the product path must
+never route through it.
+
+Operator definition.  The paper's mixed-type MoE evaluation (Section VII-B,
+"Mixed-type MoE", Table III) fixes only the operand set A (fp16 activations),
+B (int4 weights), scale and zp, and the FP16xINT4 semantics of Section II-C /
+Fig. 4(b) (weights are cast to the activation type and contracted on the
+matrix units).  The remaining choices follow the benchmark statement:
+
+* int4 packing: eight unsigned nibbles per 32-bit word, element 8j+i of a row
+  sits in bits [4i, 4i+4) of word j (sequential order, little-endian
+  significance).
+* group-wise asymmetric quantisation along the reduction (last) dimension:
+  W[n, k] = (q[n, k] - z[n, k // g]) * s[n, k // g].
+* W1 [E, 2N, K]: rows [0, N) are the gate projection (goes through SiLU),
+  rows [N, 2N) the up projection.  W2 [E, K, N] is the down projection.
+* slot s = t * topk + j is routed to expert topk_ids[t, j]; ids outside
+  [0, E) are ignored (not bucketed, contribute zero to the output).
+
+Every floating tensor is handled in "value space": float64 arrays whose values
+are exactly representable in the 16-bit type.  `decode_bits` / `encode_bits`
+move between value space and raw uint16 patterns.
+
+Parity pins (tests/test_oracle_*.py): exact rational brute force on tiny
+shapes, pack/unpack round trip and the 0x76543210 vector, all-zero nibbles
+=> -z*s, one-hot routing => dense GEMM chain, E=1 => dense MLP, top-k weights
+sum to one, token permutation equivariance (bit-identical), W2-scale doubling
+doubles the output, combine linearity, rounding against NumPy's fp16 cast,
+PyTorch's bf16 cast and hand-derived tie cases.  The paper prints no worked
+numeric example for this operator, so there is no paper-valued fixture.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+_FORMATS = {
+    # name: (significand bits incl. hidden one, min normal exponent, max finite value)
+    "f16": (11, -14, 65504.0),
+    "bf16": (8, -126, float.fromhex("0x1.fep127")),
+}
+
+
+# --------------------------------------------------------------------------
+# 16-bit storage formats
+# --------------------------------------------------------------------------
+def rnd(x, dt: str) -> np.ndarray:
+    """IEEE round-to-nearest-even of float64 values to fp16 / bf16, returned as
+    float64 (value space).  Rounds once, straight from float64."""
+    sig, emin, vmax = _FORMATS[dt]
+    x = np.asarray(x, dtype=np.float64)
+    a = np.abs(x)
+    _, e = np.frexp(a)                      # a = m * 2**e, m in [0.5, 1)
+    # spacing of representable numbers around a: 2**(e - sig), floored at the subnormal spacing
+    qexp = np.maximum(e - sig, emin - (sig - 1))
+    q = np.ldexp(1.0, qexp)
+    r = np.rint(a / q) * q                  # rint = ties to even; a / q is exact (power of two)
+    # overflow: at or beyond (largest finite + half an ulp of the top binade) rounds to inf
+    half_ulp_top = np.ldexp(1.0, int(np.frexp(vmax)[1]) - sig - 1)
+    r = np.where(a >= vmax + half_ulp_top, np.inf, r)
+    r = np.where(np.isnan(x), np.nan, r)
+    return np.copysign(r, x)
+
+
+def decode_bits(bits, dt: str) -> np.ndarray:
+    """uint16 bit patterns -> float64 values."""
+    b = np.ascontiguousarray(bits, dtype=np.uint16)
+    if dt == "f16":
+        return b.view(np.float16).astype(np.float64)
+    if dt == "bf16":
+        return (b.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+    raise ValueError(dt)
+
+
+def encode_bits(values, dt: str) -> np.ndarray:
+    """float64 values already representable in dt -> uint16 bit patterns."""
+    v = rnd(values, dt)
+    if dt == "f16":
+        return v.astype(np.float16).view(np.uint16)
+    if dt == "bf16":
+        return (v.astype(np.float32).view(np.uint32) >> np.uint32(16)).astype(np.uint16)
+    raise ValueError(dt)
+
+
+# --------------------------------------------------------------------------
+# int4 packing and dequantisation
+# --------------------------------------------------------------------------
+def unpack_int4(words) -> np.ndarray:
+    """[..., W] 32-bit words -> [..., 8W] uint8 nibbles; element 8j+i = bits [4i,4i+4) of word j."""
+    w = np.ascontiguousarray(words).view(np.uint32)
+    out = np.empty(w.shape + (8,), dtype=np.uint8)
+    for i in range(8):
+        out[..., i] = (w >> np.uint32(4 * i)) & np.uint32(0xF)
+    return out.reshape(w.shape[:-1] + (w.shape[-1] * 8,))
+
+
+def pack_int4(q) -> np.ndarray:
+    """Inverse of unpack_int4: [..., 8W] values 0..15 -> [..., W] int32 words."""
+    q = np.asarray(q)
+    assert q.shape[-1] % 8 == 0 and q.min(initial=0) >= 0 and q.max(initial=0) <= 15
+    q8 = q.reshape(q.shape[:-1] + (q.shape[-1] // 8, 8)).astype(np.uint32)
+    w = np.zeros(q8.shape[:-1], dtype=np.uint32)
+    for i in range(8):
+        w |= q8[..., i] << np.uint32(4 * i)
+    return w.view(np.int32)
+
+
+def dequant(qweight, scales, zeros, group: int) -> np.ndarray:
+    """W[..., n, k] = (q - z[..., n, k//g]) * s[..., n, k//g] in float64 (exact:
+    |q - z| <= 15 and the scale has at most 11 significant bits).
+
+    qweight [..., rows, red/8] words, scales [..., rows, red/g] float64 values,
+    zeros [..., rows, red/g] integers 0..15."""
+    q = unpack_int4(qweight).astype(np.int64)
+    z = np.repeat(np.asarray(zeros).astype(np.int64), group, axis=-1)
+    s = np.repeat(np.asarray(scales, dtype=np.float64), group, axis=-1)
+    assert q.shape == z.shape == s.shape, (q.shape, z.shape, s.shape)
+    return (q - z).astype(np.float64) * s
+
+
+# --------------------------------------------------------------------------
+# routing weights (input preparation; kept here to pin the generator's router)
+# --------------------------------------------------------------------------
+def route_topk(logits, topk: int):
+    """Top-k experts per token (descending logit, ties to the lower index) and the
+    full softmax renormalised over the selected experts, in float64."""
+    logits = np.asarray(logits, dtype=np.float64)
+    T, E = logits.shape
+    ids = np.empty((T, topk), dtype=np.int32)
+    w = np.empty((T, topk), dtype=np.float64)
+    for t in range(T):
+        full = np.exp(logits[t] - logits[t].max())
+        full /= full.sum()
+        order = sorted(range(E), key=lambda e: (-logits[t, e], e))[:topk]
+        ids[t] = order
+        w[t] = full[order] / full[order].sum()
+    return ids, w
+
+
+# --------------------------------------------------------------------------
+# step 1: expert bucketing
+# --------------------------------------------------------------------------
+def align_capacity(T: int, topk: int, E: int, block_m: int) -> int:
+    S = T * topk
+    worst = S + min(E, S) * (block_m - 1)
+    return -(-worst // block_m) * block_m
+
+
+def align_by_expert(topk_ids, E: int, block_m: int) -> dict:
+    """Stable counting sort of the T*topk slots by expert, each non-empty expert
+    padded to a multiple of block_m.  All outputs int32.
+
+    expert_counts[e]   number of slots routed to e (unpadded)
+    expert_offsets     exclusive prefix sum of the padded counts, length E+1
+    sorted_slot_ids    [capacity]; segment e holds its slots in ascending slot
+                       order, then the sentinel S; everything past num_padded is S
+    block_expert_ids   [capacity/block_m]; expert owning each block, -1 past the end
+    num_padded         expert_offsets[E]
+    """
+    ids = np.asarray(topk_ids, dtype=np.int64).reshape(-1)
+    S = ids.size
+    T_topk_cap = -(-(S + min(E, S) * (block_m - 1)) // block_m) * block_m
+    counts = np.zeros(E, dtype=np.int64)
+    for e in range(E):
+        counts[e] = int(np.count_nonzero(ids == e))
+    padded = -(-counts // block_m) * block_m
+    offsets = np.concatenate([[0], np.cumsum(padded)])
+    sorted_ids = np.full(T_topk_cap, S, dtype=np.int64)
+    block_e = np.full(T_topk_cap // block_m, -1, dtype=np.int64)
+    for e in range(E):
+        slots = np.nonzero(ids == e)[0]           # ascending slot id
+        sorted_ids[offsets[e]:offsets[e] + slots.size] = slots
+        block_e[offsets[e] // block_m: offsets[e + 1] // block_m] = e
+    return {
+        "expert_counts": counts.astype(np.int32),
+        "expert_offsets": offsets.astype(np.int32),
+        "sorted_slot_ids": sorted_ids.astype(np.int32),
+        "block_expert_ids": block_e.astype(np.int32),
+        "num_padded": np.array([offsets[-1]], dtype=np.int32),
+    }
+
+
+# --------------------------------------------------------------------------
+# steps 2 and 4: grouped W4A16 GEMM
+# --------------------------------------------------------------------------
+def grouped_gemm(A, row_div: int, qweight, scales, zeros, slot_expert, group: int,
+                 dt=None, fill=np.nan) -> np.ndarray:
+    """C[s, n] = sum_k A[s // row_div, k] * W[e_s, n, k],  e_s = slot_expert[s].
+
+    A [rows, K_in] float64 values; qweight [E, N_out, K_in/8]; scales float64
+    values [E, N_out, K_in/g]; zeros [E, N_out, K_in/g].  Accumulates in
+    float64 and rounds once to dt (dt=None keeps float64).  Rows of slots whose
+    expert id is outside [0, E) are left at `fill` (the HIP entry point leaves
+    such rows untouched)."""
+    A = np.asarray(A, dtype=np.float64)
+    slot_expert = np.asarray(slot_expert).reshape(-1)
+    E, N_out = qweight.shape[0], qweight.shape[1]
+    S = slot_expert.size
+    C = np.full((S, N_out), fill, dtype=np.float64)
+    for e in range(E):
+        slots = np.nonzero(slot_expert == e)[0]
+        if slots.size == 0:
+            continue
+        W = dequant(qweight[e], scales[e], zeros[e], group)       # [N_out, K_in]
+        C[slots] = A[slots // row_div] @ W.T
+    if dt is not None:
+        C = np.where(np.isnan(C), C, rnd(C, dt))
+    return C
+
+
+def gemm_entry(A, row_div: int, qweight, scales, zeros, slot_expert, group: int,
+               s: int, n: int) -> float:
+    """One output element of grouped_gemm, unrounded, by the definition (used to
+    sample outputs at sizes where the full product is too slow)."""
+    e = int(np.asarray(slot_expert).reshape(-1)[s])
+    W = dequant(qweight[e, n:n + 1], np.asarray(scales)[e, n:n + 1], zeros[e, n:n + 1], group)[0]
+    return float(np.dot(np.asarray(A, dtype=np.float64)[s // row_div], W))
+
+
+# --------------------------------------------------------------------------
+# step 3: SiLU-and-multiply, step 5: combine
+# --------------------------------------------------------------------------
+def silu_mul(H, dt=None) -> np.ndarray:
+    """act[s, n] = silu(H[s, n]) * H[s, N + n], silu(x) = x / (1 + exp(-x))."""
+    H = np.asarray(H, dtype=np.float64)
+    N = H.shape[1] // 2
+    g, u = H[:, :N], H[:, N:]
+    with np.errstate(over="ignore"):
+        act = g / (1.0 + np.exp(-g)) * u
+    return rnd(act, dt) if dt is not None else act
+
+
+def combine(Y, topk_weights, dt=None, slot_valid=None) -> np.ndarray:
+    """out[t, c] = sum_j w[t, j] * Y[t*topk + j, c], summed in j order in float64.
+    Slots flagged invalid contribute zero."""
+    w = np.asarray(topk_weights, dtype=np.float64)
+    T, topk = w.shape
+    Y = np.asarray(Y, dtype=np.float64).reshape(T, topk, -1)
+    out = np.zeros((T, Y.shape[2]), dtype=np.float64)
+    for j in range(topk):
+        term = w[:, j:j + 1] * Y[:, j, :]
+        if slot_valid is not None:
+            ok = np.asarray(slot_valid).reshape(T, topk)[:, j:j + 1]
+            term = np.where(ok, term, 0.0)
+        out += term
+    return rnd(out, dt) if dt is not None else out
+
+
+# --------------------------------------------------------------------------
+# whole layer
+# --------------------------------------------------------------------------
+def layer(X, topk_ids, topk_weights, qw1, s1, z1, qw2, s2, z2, group: int, dt: str,
+          round_intermediates: bool = True, tokens=None, return_intermediates: bool = False):
+    """The full layer for all tokens, or for the subset `tokens` (each token's
+    output depends on no other token, so the restriction is the definition
+    applied to fewer rows).  X, s1, s2 are float64 values; output float64 values
+    rounded to dt."""
+    X = np.asarray(X, dtype=np.float64)
+    ids = np.asarray(topk_ids)
+    w = np.asarray(topk_weights)
+    if tokens is not None:
+        tokens = np.asarray(tokens, dtype=np.int64)
+        X, ids, w = X[tokens], ids[tokens], w[tokens]
+    T, topk = ids.shape
+    E = qw1.shape[0]
+    mid = dt if round_intermediates else None
+    slot_expert = ids.reshape(-1)
+    valid = (slot_expert >= 0) & (slot_expert < E)
+    H = grouped_gemm(X, topk, qw1, s1, z1, slot_expert, group, mid, fill=0.0)
+    act = silu_mul(H, mid)
+    Y = grouped_gemm(act, 1, qw2, s2, z2, slot_expert, group, mid, fill=0.0)
+    out = combine(Y, w, dt, slot_valid=valid)
+    if return_intermediates:
+        return out, {"H": H, "act": act, "Y": Y}
+    return out
