@@ -1,0 +1,160 @@
+/*
+ * moe_w4a16.h -- C ABI of the MI355X (gfx950) W4A16 mixture-of-experts layer.
+ *
+ * The operator is the FP16xINT4 "mixed-type MoE" layer of the paper's
+ * evaluation (Section VII-B "Mixed-type MoE", Fig. 10, Table III): fp16/bf16
+ * activations A, int4 weights B with per-group scale and zero-point tensors,
+ * weights cast to the activation type in registers and contracted on the
+ * matrix units (Section II-C, Fig. 4(b)), all experts served by one launch.
+ *
+ * Conventions shared by every entry point
+ *   - Plain C, no exceptions.  Every function that can fail returns a
+ *     moe_status; moe_last_error() gives a thread-local message for the last
+ *     non-OK status returned on the calling thread.
+ *   - EVERY pointer argument is a DEVICE pointer owned by the caller (for
+ *     example a PyTorch allocation).  The library never allocates, frees or
+ *     keeps them, never synchronises with the host, and enqueues work only on
+ *     `stream` (a hipStream_t passed as void*; NULL = the default stream).
+ *   - Row-major tensors, innermost dimension contiguous, no strides.
+ *   - dt selects the 16-bit activation/scale/output type (moe_dtype).
+ *   - Shapes are validated on the host before any launch; data-dependent
+ *     problems (an expert id outside [0, E)) cannot be reported synchronously:
+ *     such slots are ignored (not bucketed, contribute zero to the output).
+ *   - T == 0 is a successful no-op.
+ *
+ * Quantised weight format (per expert e, output row n, reduction index k)
+ *   qweight [E, N_out, K_in/8] int32: element k = 8j+i of a row is the unsigned
+ *           nibble in bits [4i, 4i+4) of word j.
+ *   scales  [E, N_out, K_in/g] dt, zeros [E, N_out, K_in/g] uint8 in 0..15:
+ *           W[e,n,k] = (q - zeros[e,n,k/g]) * scales[e,n,k/g].
+ *   Requirements: g % 32 == 0, K_in % g == 0, N_out % 16 == 0,
+ *   K_in / g <= 512 (group tables are staged in LDS).
+ */
+#ifndef MOE_W4A16_H
+#define MOE_W4A16_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  MOE_OK = 0,
+  MOE_INVALID_ARGUMENT = 1,
+  MOE_UNSUPPORTED_SHAPE = 2,
+  MOE_WORKSPACE_TOO_SMALL = 3,
+  MOE_HIP_ERROR = 4
+} moe_status;
+
+typedef enum { MOE_F16 = 0, MOE_BF16 = 1 } moe_dtype;
+
+/* Message for the last non-OK status returned on this thread ("" if none). */
+const char* moe_last_error(void);
+
+/*
+ * Number of int32 rows sorted_slot_ids must hold:
+ * roundup(S + min(E, S) * (block_m - 1), block_m) with S = T * topk.
+ * Returns 0 for invalid arguments.
+ */
+size_t moe_align_capacity(int T, int topk, int E, int block_m);
+
+/*
+ * Expert bucketing: stable counting sort of the S = T*topk routed slots
+ * (slot s = t*topk + j goes to expert topk_ids[s]) with every non-empty
+ * expert padded to a multiple of block_m.  The paper treats the MoE layer as
+ * one kernel over all experts (Section VII-B); this is the indexing that
+ * makes a single grouped launch possible.  Integer outputs, fully
+ * deterministic:
+ *   expert_counts    [E]        slots per expert, unpadded
+ *   expert_offsets   [E+1]      exclusive prefix sum of the padded counts
+ *   sorted_slot_ids  [capacity] segment e = its slots in ascending slot order,
+ *                               then the sentinel S; all of [num_padded,
+ *                               capacity) is S
+ *   block_expert_ids [capacity/block_m] owning expert per block, -1 past the end
+ *   num_padded       [1]        = expert_offsets[E]
+ * block_m in {16, 32, 64, 128, 256}; 1 <= E <= 1024.
+ */
+int moe_align_by_expert(const int32_t* topk_ids, int T, int topk, int E, int block_m,
+                        int32_t* expert_counts, int32_t* expert_offsets,
+                        int32_t* sorted_slot_ids, int32_t* block_expert_ids,
+                        int32_t* num_padded, void* stream);
+
+/*
+ * Grouped W4A16 GEMM (Section II-C / Fig. 4(b) dataflow, Table III operands):
+ *   C[s, n] = sum_k A[s / row_div, k] * W[e_s, n, k]     for every bucketed slot s,
+ * e_s being the expert whose segment of sorted_slot_ids contains s.
+ * fp32 accumulation, one round-to-nearest-even to dt.
+ *   A   [rows_A, K_in] dt; rows_A >= ceil(num_slots / row_div).
+ *       row_div = topk for the gate/up projection (A = token activations),
+ *       1 for the down projection (A is already per slot).
+ *   C   [num_slots, N_out] dt, written at row = slot id.  Rows of slots that
+ *       were not bucketed are left untouched.
+ *   sorted_slot_ids / block_expert_ids / num_padded: as produced by
+ *       moe_align_by_expert with the same block_m and num_slots = T*topk.
+ */
+int moe_w4a16_grouped_gemm(const void* A, int row_div,
+                           const int32_t* qweight, const void* scales, const uint8_t* zeros,
+                           const int32_t* sorted_slot_ids, const int32_t* block_expert_ids,
+                           const int32_t* num_padded,
+                           int num_slots, int E, int N_out, int K_in, int group_size, int block_m,
+                           moe_dtype dt, void* C, void* stream);
+
+/*
+ * act[s, n] = silu(H[s, n]) * H[s, N + n],  silu(x) = x / (1 + exp(-x)).
+ * H [S, 2N] dt (columns [0,N) gate, [N,2N) up), act [S, N] dt; fp32 math.
+ * The gated activation between the two projections of each expert.
+ */
+int moe_silu_mul(const void* H, void* act, int S, int N, moe_dtype dt, void* stream);
+
+/*
+ * out[t, c] = sum_{j<topk} topk_weights[t, j] * Y[t*topk + j, c]
+ * Y [T*topk, K] dt, topk_weights [T, topk] float32, out [T, K] dt;
+ * fp32 accumulation in j order, one rounding.
+ */
+int moe_combine(const void* Y, const float* topk_weights, void* out,
+                int T, int topk, int K, moe_dtype dt, void* stream);
+
+/* Bytes of workspace moe_w4a16_layer needs for these sizes (0 if invalid). */
+size_t moe_w4a16_layer_workspace_bytes(int T, int K, int N, int E, int topk, moe_dtype dt);
+
+/*
+ * The whole layer on one stream (the unit the paper times in Fig. 10):
+ * bucketing -> grouped GEMM with W1 [E, 2N, K] (rows [0,N) gate, [N,2N) up)
+ * fused with SiLU-and-multiply -> grouped GEMM with W2 [E, K, N] -> weighted
+ * combine.  X [T, K] dt, topk_ids [T, topk] int32, topk_weights [T, topk]
+ * float32, out [T, K] dt.  `workspace` is caller-owned device memory of at
+ * least moe_w4a16_layer_workspace_bytes(...) bytes, 256-byte aligned; its
+ * contents are scratch.  Slots with an expert id outside [0, E) contribute
+ * zero.
+ */
+int moe_w4a16_layer(const void* X, const int32_t* topk_ids, const float* topk_weights,
+                    const int32_t* qw1, const void* s1, const uint8_t* z1,
+                    const int32_t* qw2, const void* s2, const uint8_t* z2,
+                    void* out, int T, int K, int N, int E, int topk, int group_size,
+                    moe_dtype dt, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Measurement hooks (not part of the operator).
+ *
+ * moe_set_stage_events: while set (n == 5), moe_w4a16_layer records the given
+ * hipEvent_t handles on its stream: events[0] before bucketing, [1] before the
+ * first grouped GEMM, [2] before the second, [3] before the combine, [4] after
+ * it.  Pass (NULL, 0) to clear.  Thread-local.
+ *
+ * moe_set_tile_override: force the grouped GEMM tile (tokens per tile =
+ * 16*mt, output features per workgroup = 64*nt) instead of the built-in
+ * heuristic; (0, 0) restores it.  Unsupported combinations make the GEMM
+ * return MOE_UNSUPPORTED_SHAPE.  Thread-local.
+ *
+ * moe_layer_block_m: the bucketing block size the layer picks for these sizes.
+ */
+int moe_set_stage_events(void* const* events, int n);
+int moe_set_tile_override(int mt, int nt);
+int moe_layer_block_m(int T, int E, int topk);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOE_W4A16_H */

@@ -117,11 +117,15 @@ def dequant(qweight, scales, zeros, group: int) -> np.ndarray:
 
     qweight [..., rows, red/8] words, scales [..., rows, red/g] float64 values,
     zeros [..., rows, red/g] integers 0..15."""
-    q = unpack_int4(qweight).astype(np.int64)
-    z = np.repeat(np.asarray(zeros).astype(np.int64), group, axis=-1)
-    s = np.repeat(np.asarray(scales, dtype=np.float64), group, axis=-1)
-    assert q.shape == z.shape == s.shape, (q.shape, z.shape, s.shape)
-    return (q - z).astype(np.float64) * s
+    q = unpack_int4(qweight)
+    zeros = np.asarray(zeros)
+    scales = np.asarray(scales, dtype=np.float64)
+    G = zeros.shape[-1]
+    assert q.shape[-1] == G * group and scales.shape == zeros.shape, (q.shape, zeros.shape, scales.shape)
+    qg = q.reshape(q.shape[:-1] + (G, group)).astype(np.int16)
+    d = qg - zeros.astype(np.int16)[..., None]                  # integer q - z, |d| <= 15
+    W = d.astype(np.float64) * scales[..., None]
+    return W.reshape(q.shape)
 
 
 # --------------------------------------------------------------------------

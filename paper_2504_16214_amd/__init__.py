@@ -1,0 +1,12 @@
+"""MI355X-native W4A16 mixture-of-experts layer: hand-written HIP kernels (gfx950) behind a
+small C ABI (include/moe_w4a16.h), with a thin Python binding of the same names.
+
+PyTorch is used for device memory and streams only; every step of the layer runs in the HIP
+library.  There is no CPU fallback: if the library has not been built the binding raises.
+"""
+from .binding import (  # noqa: F401
+    MOE_F16, MOE_BF16, MoEError, library_path, load_library,
+    moe_align_capacity, moe_align_by_expert, moe_w4a16_grouped_gemm, moe_silu_mul, moe_combine,
+    moe_w4a16_layer_workspace_bytes, moe_w4a16_layer, moe_layer_block_m,
+    moe_set_tile_override, moe_set_stage_events, moe_last_error,
+)

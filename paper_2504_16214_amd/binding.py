@@ -1,0 +1,166 @@
+"""ctypes binding of libmoe_w4a16.so.  Argument marshalling only: torch tensors supply device
+pointers and the current HIP stream; all arithmetic happens in the library's kernels."""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch  # imported before the library so it binds to the HIP runtime torch already loaded
+
+MOE_F16, MOE_BF16 = 0, 1
+_STATUS = {1: "INVALID_ARGUMENT", 2: "UNSUPPORTED_SHAPE", 3: "WORKSPACE_TOO_SMALL", 4: "HIP_ERROR"}
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB: Optional[ctypes.CDLL] = None
+
+EXPORTS = [
+    "moe_last_error", "moe_align_capacity", "moe_align_by_expert", "moe_w4a16_grouped_gemm",
+    "moe_silu_mul", "moe_combine", "moe_w4a16_layer_workspace_bytes", "moe_w4a16_layer",
+    "moe_set_stage_events", "moe_set_tile_override", "moe_layer_block_m",
+]
+
+
+class MoEError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"{_STATUS.get(status, status)}: {message}")
+        self.status = status
+
+
+def library_path() -> str:
+    return os.path.join(_HERE, "libmoe_w4a16.so")
+
+
+def load_library() -> ctypes.CDLL:
+    """Load the in-tree HIP library; fail loudly if it has not been built."""
+    global _LIB
+    if _LIB is not None:
+        return _LIB
+    path = library_path()
+    if not os.path.exists(path):
+        raise RuntimeError(f"{path} is missing: build it with `python -m paper_2504_16214_amd.build` "
+                           "(there is no fallback path)")
+    lib = ctypes.CDLL(path)
+    vp, i32, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
+    lib.moe_last_error.restype = ctypes.c_char_p
+    lib.moe_last_error.argtypes = []
+    lib.moe_align_capacity.restype = sz
+    lib.moe_align_capacity.argtypes = [i32] * 4
+    lib.moe_align_by_expert.restype = i32
+    lib.moe_align_by_expert.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp]
+    lib.moe_w4a16_grouped_gemm.restype = i32
+    lib.moe_w4a16_grouped_gemm.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, vp, vp]
+    lib.moe_silu_mul.restype = i32
+    lib.moe_silu_mul.argtypes = [vp, vp, i32, i32, i32, vp]
+    lib.moe_combine.restype = i32
+    lib.moe_combine.argtypes = [vp, vp, vp, i32, i32, i32, i32, vp]
+    lib.moe_w4a16_layer_workspace_bytes.restype = sz
+    lib.moe_w4a16_layer_workspace_bytes.argtypes = [i32] * 6
+    lib.moe_w4a16_layer.restype = i32
+    lib.moe_w4a16_layer.argtypes = [vp] * 10 + [i32] * 7 + [vp, sz, vp]
+    lib.moe_set_stage_events.restype = i32
+    lib.moe_set_stage_events.argtypes = [ctypes.POINTER(vp), i32]
+    lib.moe_set_tile_override.restype = i32
+    lib.moe_set_tile_override.argtypes = [i32, i32]
+    lib.moe_layer_block_m.restype = i32
+    lib.moe_layer_block_m.argtypes = [i32, i32, i32]
+    _LIB = lib
+    return lib
+
+
+def _check(status: int) -> None:
+    if status != 0:
+        raise MoEError(status, load_library().moe_last_error().decode())
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError("device tensor expected")
+    if not t.is_contiguous():
+        raise ValueError("contiguous tensor expected")
+    return t.data_ptr()
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+
+
+def _dt(t: torch.Tensor) -> int:
+    if t.dtype == torch.float16:
+        return MOE_F16
+    if t.dtype == torch.bfloat16:
+        return MOE_BF16
+    raise ValueError(f"fp16 or bf16 tensor expected, got {t.dtype}")
+
+
+def moe_last_error() -> str:
+    return load_library().moe_last_error().decode()
+
+
+def moe_align_capacity(T: int, topk: int, E: int, block_m: int) -> int:
+    return int(load_library().moe_align_capacity(T, topk, E, block_m))
+
+
+def moe_layer_block_m(T: int, E: int, topk: int) -> int:
+    return int(load_library().moe_layer_block_m(T, E, topk))
+
+
+def moe_align_by_expert(topk_ids, E, block_m, expert_counts, expert_offsets, sorted_slot_ids,
+                        block_expert_ids, num_padded, stream=None) -> None:
+    """topk_ids [T, topk] int32; outputs are preallocated int32 device tensors."""
+    T, topk = topk_ids.shape
+    _check(load_library().moe_align_by_expert(_ptr(topk_ids), T, topk, E, block_m, _ptr(expert_counts),
+                                              _ptr(expert_offsets), _ptr(sorted_slot_ids),
+                                              _ptr(block_expert_ids), _ptr(num_padded), _stream(stream)))
+
+
+def moe_w4a16_grouped_gemm(A, row_div, qweight, scales, zeros, sorted_slot_ids, block_expert_ids,
+                           num_padded, num_slots, group_size, block_m, C, stream=None) -> None:
+    E, N_out, kw = qweight.shape
+    _check(load_library().moe_w4a16_grouped_gemm(
+        _ptr(A), row_div, _ptr(qweight), _ptr(scales), _ptr(zeros), _ptr(sorted_slot_ids),
+        _ptr(block_expert_ids), _ptr(num_padded), num_slots, E, N_out, kw * 8, group_size, block_m,
+        _dt(A), _ptr(C), _stream(stream)))
+
+
+def moe_silu_mul(H, act, stream=None) -> None:
+    S, N2 = H.shape
+    _check(load_library().moe_silu_mul(_ptr(H), _ptr(act), S, N2 // 2, _dt(H), _stream(stream)))
+
+
+def moe_combine(Y, topk_weights, out, stream=None) -> None:
+    T, topk = topk_weights.shape
+    _check(load_library().moe_combine(_ptr(Y), _ptr(topk_weights), _ptr(out), T, topk, Y.shape[1], _dt(Y),
+                                      _stream(stream)))
+
+
+def moe_w4a16_layer_workspace_bytes(T, K, N, E, topk, dt) -> int:
+    return int(load_library().moe_w4a16_layer_workspace_bytes(T, K, N, E, topk, dt))
+
+
+def moe_w4a16_layer(X, topk_ids, topk_weights, qw1, s1, z1, qw2, s2, z2, out, group_size, workspace,
+                    stream=None) -> None:
+    T, K = X.shape
+    E, N2, _ = qw1.shape
+    topk = topk_ids.shape[1]
+    _check(load_library().moe_w4a16_layer(
+        _ptr(X), _ptr(topk_ids), _ptr(topk_weights), _ptr(qw1), _ptr(s1), _ptr(z1), _ptr(qw2), _ptr(s2),
+        _ptr(z2), _ptr(out), T, K, N2 // 2, E, topk, group_size, _dt(X), _ptr(workspace),
+        workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+def moe_set_tile_override(mt: int, nt: int) -> None:
+    _check(load_library().moe_set_tile_override(mt, nt))
+
+
+def moe_set_stage_events(events) -> None:
+    """events: sequence of 5 raw hipEvent_t handles (ints), or None to clear."""
+    lib = load_library()
+    if not events:
+        _check(lib.moe_set_stage_events(None, 0))
+        return
+    arr = (ctypes.c_void_p * len(events))(*events)
+    _check(lib.moe_set_stage_events(arr, len(events)))

@@ -1,0 +1,337 @@
+// Host side of the C ABI declared in include/moe_w4a16.h: argument validation, tile choice,
+// workspace carving and kernel launches.  No allocation, no synchronisation, caller's stream.
+#include <hip/hip_runtime.h>
+#include <stdarg.h>
+#include <stdint.h>
+#include <stdio.h>
+
+#include "../../include/moe_w4a16.h"
+#include "gemm_kernel.hpp"
+
+namespace moe {
+
+int launch_align(const int32_t*, int, int, int, int, int32_t*, int32_t*, int32_t*, int32_t*, int32_t*,
+                 hipStream_t);
+int launch_silu_mul(const void*, void*, long long, int, int, hipStream_t);
+int launch_combine(const void*, const float*, const int32_t*, int, void*, long long, int, int, int,
+                   hipStream_t);
+
+// ---- table of compiled GEMM variants ------------------------------------------------------
+#define MOE_DECL(DT, MT, NT, KS, KW, F) \
+  extern template int launch_w4a16_gemm<DT, MT, NT, KS, KW, F>(const GemmParams&, int, hipStream_t);
+#define MOE_ALL_DT_KW(M, MT, NT, KS, F) \
+  M(0, MT, NT, KS, 1, F) M(0, MT, NT, KS, 2, F) M(0, MT, NT, KS, 4, F) \
+  M(1, MT, NT, KS, 1, F) M(1, MT, NT, KS, 2, F) M(1, MT, NT, KS, 4, F)
+#define MOE_TILE(MT, NT, KS) MOE_ALL_DT_KW(MOE_DECL, MT, NT, KS, 0)
+#define MOE_TILE_FUSE(MT, NT, KS) MOE_ALL_DT_KW(MOE_DECL, MT, NT, KS, 1)
+#include "gemm_variants.def"
+
+typedef int (*GemmLaunchFn)(const GemmParams&, int, hipStream_t);
+struct GemmVariant { int dt, mt, nt, ks, kw, fuse; GemmLaunchFn fn; };
+#define MOE_ENTRY(DT, MT, NT, KS, KW, F) {DT, MT, NT, KS, KW, F, &launch_w4a16_gemm<DT, MT, NT, KS, KW, F>},
+static const GemmVariant kVariants[] = {
+#define MOE_TILE(MT, NT, KS) MOE_ALL_DT_KW(MOE_ENTRY, MT, NT, KS, 0)
+#define MOE_TILE_FUSE(MT, NT, KS) MOE_ALL_DT_KW(MOE_ENTRY, MT, NT, KS, 1)
+#include "gemm_variants.def"
+};
+
+static const GemmVariant* find_variant(int dt, int mt, int nt, int kw, int fuse) {
+  for (const GemmVariant& v : kVariants)
+    if (v.dt == dt && v.mt == mt && v.nt == nt && v.kw == kw && v.fuse == fuse) return &v;
+  return nullptr;
+}
+
+// ---- thread-local state -----------------------------------------------------------------
+static thread_local char g_err[512] = "";
+static thread_local void* g_events[5] = {nullptr, nullptr, nullptr, nullptr, nullptr};
+static thread_local int g_nevents = 0;
+static thread_local int g_force_mt = 0, g_force_nt = 0;
+
+static int fail(int status, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return status;
+}
+static int hip_fail(int err, const char* what) {
+  return fail(MOE_HIP_ERROR, "%s: %s", what, hipGetErrorString((hipError_t)err));
+}
+
+static bool valid_block_m(int b) { return b == 16 || b == 32 || b == 64 || b == 128 || b == 256; }
+static size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+static size_t align_capacity(long long S, int E, int block_m) {
+  const long long worst = S + (S < E ? S : E) * (long long)(block_m - 1);
+  return (size_t)((worst + block_m - 1) / block_m * block_m);
+}
+constexpr size_t kLdsLimit = 160 * 1024;
+constexpr int kMaxGroups = 512;
+
+static size_t gemm_lds_bytes(int mt, int nt, int ks, int G) {
+  const size_t M_T = 16 * mt, NW = 16 * nt;
+  return 2 * M_T * (ks * 2 + 16) + 4 * NW * (ks / 2 + 16) + (size_t)G * 64 * nt * 4 + M_T * 4;
+}
+
+// Tile choice.  Tokens per tile follow the bucketing block; the feature width per workgroup is
+// as wide as LDS allows while still giving every CU a couple of workgroups (256 CUs).
+static int choose_tile(int num_slots, int E, int feat, int G, int block_m, int fuse, int& mt, int& nt,
+                       int& ks) {
+  mt = block_m / 16;
+  if (mt > 8) mt = 8;
+  if (g_force_mt > 0) {
+    if ((block_m / 16) % g_force_mt != 0) return -1;
+    mt = g_force_mt;
+  }
+  ks = mt >= 4 ? 128 : 256;
+  const int min_nt = (fuse || mt >= 4) ? 2 : 1;
+  if (g_force_nt > 0) {
+    nt = g_force_nt;
+    return (nt >= min_nt && (nt == 1 || nt == 2 || nt == 4) && gemm_lds_bytes(mt, nt, ks, G) <= kLdsLimit) ? 0 : -1;
+  }
+  const long long est_blocks = (num_slots + 16 * mt - 1) / (16 * mt) + (num_slots < E ? num_slots : E) / 2;
+  nt = mt >= 4 ? 4 : 2;
+  for (;;) {
+    const int fpw = fuse ? 32 * nt : 64 * nt;
+    const long long wgs = est_blocks * ((feat + fpw - 1) / fpw);
+    const bool fits = gemm_lds_bytes(mt, nt, ks, G) <= kLdsLimit;
+    if (fits && (wgs >= 512 || nt == min_nt)) return 0;
+    if (nt == min_nt) return -1;
+    nt >>= 1;
+  }
+}
+
+struct GemmArgs {
+  const void* A; int row_div;
+  const int32_t* qweight; const void* scales; const uint8_t* zeros;
+  const int32_t* sorted_slot_ids; const int32_t* block_expert_ids; const int32_t* num_padded;
+  int num_slots, E, N_out, K_in, group, block_m, dt;
+  void* C; int ldc; int fuse_half_n;
+};
+
+static int run_gemm(const GemmArgs& a, hipStream_t stream) {
+  if (a.dt != MOE_F16 && a.dt != MOE_BF16) return fail(MOE_INVALID_ARGUMENT, "dt must be MOE_F16 or MOE_BF16");
+  if (a.num_slots < 0 || a.E < 1 || a.row_div < 1 || a.N_out < 1 || a.K_in < 1 || a.group < 1)
+    return fail(MOE_INVALID_ARGUMENT, "sizes must be positive (num_slots >= 0)");
+  if (!valid_block_m(a.block_m)) return fail(MOE_INVALID_ARGUMENT, "block_m must be 16, 32, 64, 128 or 256");
+  if (a.group % 32 != 0) return fail(MOE_UNSUPPORTED_SHAPE, "group_size %d is not a multiple of 32", a.group);
+  if (a.K_in % a.group != 0) return fail(MOE_UNSUPPORTED_SHAPE, "K_in %d is not a multiple of group_size %d", a.K_in, a.group);
+  if (a.N_out % 16 != 0) return fail(MOE_UNSUPPORTED_SHAPE, "N_out %d is not a multiple of 16", a.N_out);
+  const int G = a.K_in / a.group;
+  if (G > kMaxGroups) return fail(MOE_UNSUPPORTED_SHAPE, "K_in/group_size = %d exceeds %d", G, kMaxGroups);
+  if (a.num_slots == 0) return MOE_OK;
+  if (!a.A || !a.qweight || !a.scales || !a.zeros || !a.sorted_slot_ids || !a.block_expert_ids ||
+      !a.num_padded || !a.C)
+    return fail(MOE_INVALID_ARGUMENT, "null pointer argument");
+  if (((uintptr_t)a.A | (uintptr_t)a.qweight) % 16 != 0)
+    return fail(MOE_INVALID_ARGUMENT, "A and qweight must be 16-byte aligned");
+  if (((uintptr_t)a.C | (uintptr_t)a.scales) % 2 != 0)
+    return fail(MOE_INVALID_ARGUMENT, "C and scales must be 2-byte aligned");
+
+  const int fuse = a.fuse_half_n > 0 ? 1 : 0;
+  const int feat = fuse ? a.fuse_half_n : a.N_out;
+  const int kw = a.group % 128 == 0 ? 4 : (a.group % 64 == 0 ? 2 : 1);
+  int mt, nt, ks;
+  if (choose_tile(a.num_slots, a.E, feat, G, a.block_m, fuse, mt, nt, ks) != 0)
+    return fail(MOE_UNSUPPORTED_SHAPE, "no GEMM tile fits (K_in/group_size = %d, block_m = %d, override %d/%d)",
+                G, a.block_m, g_force_mt, g_force_nt);
+  const GemmVariant* v = find_variant(a.dt, mt, nt, kw, fuse);
+  if (!v) return fail(MOE_UNSUPPORTED_SHAPE, "GEMM variant mt=%d nt=%d kw=%d fuse=%d is not compiled", mt, nt, kw, fuse);
+
+  GemmParams p;
+  p.A = a.A; p.row_div = a.row_div;
+  p.qweight = a.qweight; p.scales = a.scales; p.zeros = a.zeros;
+  p.sorted_slot_ids = a.sorted_slot_ids; p.block_expert_ids = a.block_expert_ids; p.num_padded = a.num_padded;
+  p.num_slots = a.num_slots; p.E = a.E; p.N_out = a.N_out; p.K_in = a.K_in; p.group = a.group;
+  p.block_m = a.block_m; p.C = a.C; p.ldc = a.ldc;
+  const int fpw = fuse ? 32 * nt : 64 * nt;
+  p.n_tiles = (feat + fpw - 1) / fpw;
+  p.G = G;
+  p.cpg = a.group / (32 * kw);
+  p.half_n = a.fuse_half_n;
+  p.sz_vec = (G % 8 == 0 && (uintptr_t)a.scales % 16 == 0 && (uintptr_t)a.zeros % 8 == 0) ? 1 : 0;
+  const size_t cap = align_capacity(a.num_slots, a.E, a.block_m);
+  const long long grid = (long long)(cap / (16 * mt)) * p.n_tiles;
+  if (grid > 0x7fffffffLL) return fail(MOE_UNSUPPORTED_SHAPE, "grid too large");
+  const int err = v->fn(p, (int)grid, stream);
+  if (err != 0) return hip_fail(err, "grouped GEMM launch");
+  return MOE_OK;
+}
+
+static int pick_block_m(long long S, int E) {
+  const long long avg = S / (E > 0 ? E : 1);
+  if (avg <= 8) return 16;
+  if (avg <= 24) return 32;
+  if (avg <= 64) return 64;
+  return 128;
+}
+
+struct Workspace {
+  size_t counts, offsets, num_padded, sorted, blocks, act, Y, total;
+};
+static Workspace carve(long long T, int K, int N, int E, int topk) {
+  const long long S = T * topk;
+  Workspace w;
+  size_t o = 0;
+  w.counts = o;      o += round_up((size_t)E * 4, 256);
+  w.offsets = o;     o += round_up((size_t)(E + 1) * 4, 256);
+  w.num_padded = o;  o += 256;
+  w.sorted = o;      o += round_up(align_capacity(S, E, 128) * 4, 256);
+  w.blocks = o;      o += round_up((align_capacity(S, E, 16) / 16 + 1) * 4, 256);
+  w.act = o;         o += round_up((size_t)S * N * 2, 256);
+  w.Y = o;           o += round_up((size_t)S * K * 2, 256);
+  w.total = o;
+  return w;
+}
+
+}  // namespace moe
+
+using namespace moe;
+
+extern "C" {
+
+const char* moe_last_error(void) { return g_err; }
+
+size_t moe_align_capacity(int T, int topk, int E, int block_m) {
+  if (T < 0 || topk < 1 || E < 1 || !valid_block_m(block_m)) return 0;
+  return align_capacity((long long)T * topk, E, block_m);
+}
+
+int moe_align_by_expert(const int32_t* topk_ids, int T, int topk, int E, int block_m,
+                        int32_t* expert_counts, int32_t* expert_offsets, int32_t* sorted_slot_ids,
+                        int32_t* block_expert_ids, int32_t* num_padded, void* stream) {
+  if (T < 0 || topk < 1 || E < 1) return fail(MOE_INVALID_ARGUMENT, "need T >= 0, topk >= 1, E >= 1");
+  if (!valid_block_m(block_m)) return fail(MOE_INVALID_ARGUMENT, "block_m must be 16, 32, 64, 128 or 256");
+  if (E > 1024) return fail(MOE_UNSUPPORTED_SHAPE, "E = %d exceeds 1024", E);
+  const long long S = (long long)T * topk;
+  if (S > 0x7fffffffLL / 2) return fail(MOE_UNSUPPORTED_SHAPE, "T*topk too large");
+  if (!expert_counts || !expert_offsets || !num_padded || (S > 0 && (!topk_ids || !sorted_slot_ids || !block_expert_ids)))
+    return fail(MOE_INVALID_ARGUMENT, "null pointer argument");
+  const size_t cap = align_capacity(S, E, block_m);
+  const int err = launch_align(topk_ids, (int)S, E, block_m, (int)cap, expert_counts, expert_offsets,
+                               sorted_slot_ids, block_expert_ids, num_padded, (hipStream_t)stream);
+  if (err != 0) return hip_fail(err, "align launch");
+  return MOE_OK;
+}
+
+int moe_w4a16_grouped_gemm(const void* A, int row_div, const int32_t* qweight, const void* scales,
+                           const uint8_t* zeros, const int32_t* sorted_slot_ids,
+                           const int32_t* block_expert_ids, const int32_t* num_padded, int num_slots,
+                           int E, int N_out, int K_in, int group_size, int block_m, moe_dtype dt,
+                           void* C, void* stream) {
+  GemmArgs a{A, row_div, qweight, scales, zeros, sorted_slot_ids, block_expert_ids, num_padded,
+             num_slots, E, N_out, K_in, group_size, block_m, (int)dt, C, N_out, 0};
+  return run_gemm(a, (hipStream_t)stream);
+}
+
+int moe_silu_mul(const void* H, void* act, int S, int N, moe_dtype dt, void* stream) {
+  if (S < 0 || N < 1) return fail(MOE_INVALID_ARGUMENT, "need S >= 0 and N >= 1");
+  if (dt != MOE_F16 && dt != MOE_BF16) return fail(MOE_INVALID_ARGUMENT, "dt must be MOE_F16 or MOE_BF16");
+  if (S == 0) return MOE_OK;
+  if (!H || !act) return fail(MOE_INVALID_ARGUMENT, "null pointer argument");
+  if (N % 8 == 0 && ((uintptr_t)H | (uintptr_t)act) % 16 != 0)
+    return fail(MOE_INVALID_ARGUMENT, "H and act must be 16-byte aligned");
+  const int err = launch_silu_mul(H, act, S, N, (int)dt, (hipStream_t)stream);
+  if (err != 0) return hip_fail(err, "silu_mul launch");
+  return MOE_OK;
+}
+
+int moe_combine(const void* Y, const float* topk_weights, void* out, int T, int topk, int K, moe_dtype dt,
+                void* stream) {
+  if (T < 0 || topk < 1 || K < 1) return fail(MOE_INVALID_ARGUMENT, "need T >= 0, topk >= 1, K >= 1");
+  if (dt != MOE_F16 && dt != MOE_BF16) return fail(MOE_INVALID_ARGUMENT, "dt must be MOE_F16 or MOE_BF16");
+  if (T == 0) return MOE_OK;
+  if (!Y || !topk_weights || !out) return fail(MOE_INVALID_ARGUMENT, "null pointer argument");
+  if (K % 8 == 0 && ((uintptr_t)Y | (uintptr_t)out) % 16 != 0)
+    return fail(MOE_INVALID_ARGUMENT, "Y and out must be 16-byte aligned");
+  const int err = launch_combine(Y, topk_weights, nullptr, 0, out, T, topk, K, (int)dt, (hipStream_t)stream);
+  if (err != 0) return hip_fail(err, "combine launch");
+  return MOE_OK;
+}
+
+size_t moe_w4a16_layer_workspace_bytes(int T, int K, int N, int E, int topk, moe_dtype dt) {
+  (void)dt;
+  if (T < 0 || K < 1 || N < 1 || E < 1 || topk < 1) return 0;
+  return carve(T, K, N, E, topk).total;
+}
+
+int moe_layer_block_m(int T, int E, int topk) {
+  if (T < 0 || E < 1 || topk < 1) return 0;
+  return pick_block_m((long long)T * topk, E);
+}
+
+int moe_w4a16_layer(const void* X, const int32_t* topk_ids, const float* topk_weights,
+                    const int32_t* qw1, const void* s1, const uint8_t* z1,
+                    const int32_t* qw2, const void* s2, const uint8_t* z2,
+                    void* out, int T, int K, int N, int E, int topk, int group_size, moe_dtype dt,
+                    void* workspace, size_t workspace_bytes, void* stream_v) {
+  hipStream_t stream = (hipStream_t)stream_v;
+  if (T < 0 || K < 1 || N < 1 || E < 1 || topk < 1 || group_size < 1)
+    return fail(MOE_INVALID_ARGUMENT, "need T >= 0 and positive K, N, E, topk, group_size");
+  if (dt != MOE_F16 && dt != MOE_BF16) return fail(MOE_INVALID_ARGUMENT, "dt must be MOE_F16 or MOE_BF16");
+  if (E > 1024) return fail(MOE_UNSUPPORTED_SHAPE, "E = %d exceeds 1024", E);
+  if (group_size % 32 != 0 || K % group_size != 0 || N % group_size != 0)
+    return fail(MOE_UNSUPPORTED_SHAPE, "group_size %d must be a multiple of 32 dividing K=%d and N=%d", group_size, K, N);
+  if (K % 16 != 0 || N % 16 != 0) return fail(MOE_UNSUPPORTED_SHAPE, "K and N must be multiples of 16");
+  if (K / group_size > kMaxGroups || N / group_size > kMaxGroups)
+    return fail(MOE_UNSUPPORTED_SHAPE, "more than %d quantisation groups per row", kMaxGroups);
+  if (T == 0) return MOE_OK;
+  if (!X || !topk_ids || !topk_weights || !qw1 || !s1 || !z1 || !qw2 || !s2 || !z2 || !out || !workspace)
+    return fail(MOE_INVALID_ARGUMENT, "null pointer argument");
+  if (((uintptr_t)workspace % 256) != 0) return fail(MOE_INVALID_ARGUMENT, "workspace must be 256-byte aligned");
+  if (((uintptr_t)out % 16) != 0) return fail(MOE_INVALID_ARGUMENT, "out must be 16-byte aligned");
+  const Workspace w = carve(T, K, N, E, topk);
+  if (workspace_bytes < w.total)
+    return fail(MOE_WORKSPACE_TOO_SMALL, "workspace has %zu bytes, %zu needed", workspace_bytes, w.total);
+  const long long S = (long long)T * topk;
+  if (S > 0x7fffffffLL / 2) return fail(MOE_UNSUPPORTED_SHAPE, "T*topk too large");
+
+  unsigned char* base = (unsigned char*)workspace;
+  int32_t* counts = (int32_t*)(base + w.counts);
+  int32_t* offsets = (int32_t*)(base + w.offsets);
+  int32_t* num_padded = (int32_t*)(base + w.num_padded);
+  int32_t* sorted = (int32_t*)(base + w.sorted);
+  int32_t* blocks = (int32_t*)(base + w.blocks);
+  void* act = base + w.act;
+  void* Y = base + w.Y;
+  const int block_m = pick_block_m(S, E);
+  const bool ev = g_nevents == 5;
+
+  if (ev) (void)hipEventRecord((hipEvent_t)g_events[0], stream);
+  int err = launch_align(topk_ids, (int)S, E, block_m, (int)align_capacity(S, E, block_m), counts, offsets,
+                         sorted, blocks, num_padded, stream);
+  if (err != 0) return hip_fail(err, "align launch");
+
+  if (ev) (void)hipEventRecord((hipEvent_t)g_events[1], stream);
+  GemmArgs g1{X, topk, qw1, s1, z1, sorted, blocks, num_padded, (int)S, E, 2 * N, K, group_size, block_m,
+              (int)dt, act, N, N};
+  int st = run_gemm(g1, stream);
+  if (st != MOE_OK) return st;
+
+  if (ev) (void)hipEventRecord((hipEvent_t)g_events[2], stream);
+  GemmArgs g2{act, 1, qw2, s2, z2, sorted, blocks, num_padded, (int)S, E, K, N, group_size, block_m,
+              (int)dt, Y, K, 0};
+  st = run_gemm(g2, stream);
+  if (st != MOE_OK) return st;
+
+  if (ev) (void)hipEventRecord((hipEvent_t)g_events[3], stream);
+  err = launch_combine(Y, topk_weights, topk_ids, E, out, T, topk, K, (int)dt, stream);
+  if (err != 0) return hip_fail(err, "combine launch");
+  if (ev) (void)hipEventRecord((hipEvent_t)g_events[4], stream);
+  return MOE_OK;
+}
+
+int moe_set_stage_events(void* const* events, int n) {
+  if (n == 0 || events == nullptr) { g_nevents = 0; return MOE_OK; }
+  if (n != 5) return fail(MOE_INVALID_ARGUMENT, "expected 5 events");
+  for (int i = 0; i < 5; ++i) g_events[i] = events[i];
+  g_nevents = 5;
+  return MOE_OK;
+}
+
+int moe_set_tile_override(int mt, int nt) {
+  if (mt < 0 || nt < 0) return fail(MOE_INVALID_ARGUMENT, "negative tile override");
+  g_force_mt = mt; g_force_nt = nt;
+  return MOE_OK;
+}
+
+}  // extern "C"

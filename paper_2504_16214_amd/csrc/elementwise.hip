@@ -1,0 +1,118 @@
+// SiLU-and-multiply between the two expert projections and the top-k weighted combine.
+// Both are pure streaming kernels: 128-bit loads/stores, fp32 math, one rounding.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "gemm_kernel.hpp"   // 16-bit conversions and silu_f32 only
+
+namespace moe {
+
+template <int DT>
+__global__ void __launch_bounds__(256)
+silu_mul_kernel(const uint16_t* __restrict__ H, uint16_t* __restrict__ act, long long S, int N) {
+  // one thread = 8 consecutive columns when N % 8 == 0, else one column
+  const bool vec = (N & 7) == 0;
+  const long long per_row = vec ? (N >> 3) : N;
+  const long long total = S * per_row;
+  for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < total; i += (long long)gridDim.x * 256) {
+    const long long s = i / per_row;
+    const int c = (int)(i - s * per_row);
+    const uint16_t* hrow = H + s * 2 * (long long)N;
+    uint16_t* arow = act + s * (long long)N;
+    if (vec) {
+      const uint4 g = *reinterpret_cast<const uint4*>(hrow + c * 8);
+      const uint4 u = *reinterpret_cast<const uint4*>(hrow + N + c * 8);
+      const uint32_t gw[4] = {g.x, g.y, g.z, g.w}, uw[4] = {u.x, u.y, u.z, u.w};
+      uint32_t o[4];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const float g0 = from_bits16<DT>((uint16_t)gw[k]), g1 = from_bits16<DT>((uint16_t)(gw[k] >> 16));
+        const float u0 = from_bits16<DT>((uint16_t)uw[k]), u1 = from_bits16<DT>((uint16_t)(uw[k] >> 16));
+        o[k] = (uint32_t)to_bits16<DT>(silu_f32(g0) * u0) | ((uint32_t)to_bits16<DT>(silu_f32(g1) * u1) << 16);
+      }
+      *reinterpret_cast<uint4*>(arow + c * 8) = make_uint4(o[0], o[1], o[2], o[3]);
+    } else {
+      arow[c] = to_bits16<DT>(silu_f32(from_bits16<DT>(hrow[c])) * from_bits16<DT>(hrow[N + c]));
+    }
+  }
+}
+
+// ids == nullptr: every slot contributes.  Otherwise slots whose expert id lies outside
+// [0, E) contribute zero (their Y rows were never written).
+template <int DT>
+__global__ void __launch_bounds__(256)
+combine_kernel(const uint16_t* __restrict__ Y, const float* __restrict__ w, const int32_t* __restrict__ ids,
+               int E, uint16_t* __restrict__ out, long long T, int topk, int K) {
+  const bool vec = (K & 7) == 0;
+  const long long per_row = vec ? (K >> 3) : K;
+  const long long total = T * per_row;
+  for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < total; i += (long long)gridDim.x * 256) {
+    const long long t = i / per_row;
+    const int c = (int)(i - t * per_row);
+    if (vec) {
+      float acc[8];
+#pragma unroll
+      for (int k = 0; k < 8; ++k) acc[k] = 0.f;
+      for (int j = 0; j < topk; ++j) {
+        const long long slot = t * topk + j;
+        if (ids) { const int e = ids[slot]; if (e < 0 || e >= E) continue; }
+        const float wj = w[slot];
+        const uint4 y = *reinterpret_cast<const uint4*>(Y + slot * (long long)K + c * 8);
+        const uint32_t yw[4] = {y.x, y.y, y.z, y.w};
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          acc[2 * k] = __builtin_fmaf(wj, from_bits16<DT>((uint16_t)yw[k]), acc[2 * k]);
+          acc[2 * k + 1] = __builtin_fmaf(wj, from_bits16<DT>((uint16_t)(yw[k] >> 16)), acc[2 * k + 1]);
+        }
+      }
+      uint32_t o[4];
+#pragma unroll
+      for (int k = 0; k < 4; ++k)
+        o[k] = (uint32_t)to_bits16<DT>(acc[2 * k]) | ((uint32_t)to_bits16<DT>(acc[2 * k + 1]) << 16);
+      *reinterpret_cast<uint4*>(out + t * (long long)K + c * 8) = make_uint4(o[0], o[1], o[2], o[3]);
+    } else {
+      float acc = 0.f;
+      for (int j = 0; j < topk; ++j) {
+        const long long slot = t * topk + j;
+        if (ids) { const int e = ids[slot]; if (e < 0 || e >= E) continue; }
+        acc = __builtin_fmaf(w[slot], from_bits16<DT>(Y[slot * (long long)K + c]), acc);
+      }
+      out[t * (long long)K + c] = to_bits16<DT>(acc);
+    }
+  }
+}
+
+static int grid_for(long long work_items) {
+  long long blocks = (work_items + 255) / 256;
+  const long long cap = 256LL * 32;      // 256 CUs, grid-stride beyond that
+  if (blocks > cap) blocks = cap;
+  if (blocks < 1) blocks = 1;
+  return (int)blocks;
+}
+
+int launch_silu_mul(const void* H, void* act, long long S, int N, int dt, hipStream_t stream) {
+  const long long items = S * (((N & 7) == 0) ? (N >> 3) : N);
+  if (items == 0) return 0;
+  if (dt == kF16)
+    hipLaunchKernelGGL(silu_mul_kernel<kF16>, dim3(grid_for(items)), dim3(256), 0, stream,
+                       (const uint16_t*)H, (uint16_t*)act, S, N);
+  else
+    hipLaunchKernelGGL(silu_mul_kernel<kBF16>, dim3(grid_for(items)), dim3(256), 0, stream,
+                       (const uint16_t*)H, (uint16_t*)act, S, N);
+  return (int)hipGetLastError();
+}
+
+int launch_combine(const void* Y, const float* w, const int32_t* ids, int E, void* out, long long T,
+                   int topk, int K, int dt, hipStream_t stream) {
+  const long long items = T * (((K & 7) == 0) ? (K >> 3) : K);
+  if (items == 0) return 0;
+  if (dt == kF16)
+    hipLaunchKernelGGL(combine_kernel<kF16>, dim3(grid_for(items)), dim3(256), 0, stream,
+                       (const uint16_t*)Y, w, ids, E, (uint16_t*)out, T, topk, K);
+  else
+    hipLaunchKernelGGL(combine_kernel<kBF16>, dim3(grid_for(items)), dim3(256), 0, stream,
+                       (const uint16_t*)Y, w, ids, E, (uint16_t*)out, T, topk, K);
+  return (int)hipGetLastError();
+}
+
+}  // namespace moe

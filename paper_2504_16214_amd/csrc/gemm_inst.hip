@@ -1,0 +1,35 @@
+// Explicit instantiations of the grouped W4A16 GEMM for one (dtype, KW) pair.
+// Compiled several times with -DMOE_DT={0,1} -DMOE_KW={1,2,4} so the variants build in parallel.
+#include "gemm_kernel.hpp"
+
+#ifndef MOE_DT
+#error "compile with -DMOE_DT=0|1"
+#endif
+#ifndef MOE_KW
+#error "compile with -DMOE_KW=1|2|4"
+#endif
+
+namespace moe {
+
+template <int DT, int MT, int NT, int KS, int KW, int FUSE>
+int launch_w4a16_gemm(const GemmParams& p, int grid, hipStream_t stream) {
+  auto kern = w4a16_gemm_kernel<DT, MT, NT, KS, KW, FUSE>;
+  const size_t lds = TileGeom<MT, NT, KS>::lds_bytes(p.G);
+  static size_t lds_allowed = 64 * 1024;   // raise the dynamic LDS limit once per size class
+  if (lds > lds_allowed) {
+    hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (err != hipSuccess) return (int)err;
+    lds_allowed = lds;
+  }
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, stream, p);
+  return (int)hipGetLastError();
+}
+
+#define MOE_TILE(MT, NT, KS) \
+  template int launch_w4a16_gemm<MOE_DT, MT, NT, KS, MOE_KW, 0>(const GemmParams&, int, hipStream_t);
+#define MOE_TILE_FUSE(MT, NT, KS) \
+  template int launch_w4a16_gemm<MOE_DT, MT, NT, KS, MOE_KW, 1>(const GemmParams&, int, hipStream_t);
+#include "gemm_variants.def"
+
+}  // namespace moe

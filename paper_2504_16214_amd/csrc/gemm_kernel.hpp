@@ -1,0 +1,435 @@
+// Grouped W4A16 GEMM for gfx950 (MI355X): C[s, :] = A[s / row_div, :] . dequant(W[expert(s)])^T
+//
+// Dataflow (the efficient one of the paper's Fig. 4(b), Section II-C, re-cut for CDNA4):
+//   packed int4 weights  : global --128-bit coalesced loads--> VGPR --> wave-private LDS tile
+//                          --ds_read (one lane = one MFMA operand column)--> VGPR
+//                          --in-register nibble unpack, (q - z) * s--> MFMA B operand
+//   activations          : global --128-bit loads--> VGPR --> shared LDS tile (padded rows)
+//                          --ds_read_b128--> MFMA A operand
+//   scales / zero points : staged once per workgroup into LDS, one 32-bit entry per (group, row)
+// Weights never travel register -> LDS -> register after the cast; every hop of A, B, scale
+// and zp is a wide vector access (Table III).
+//
+// Work decomposition.  A workgroup (256 threads = 4 wavefronts of 64) owns a tile of
+// M_T = 16*MT bucketed slots of one expert and N_T = 64*NT output features.  Wave w owns
+// features [w*16*NT, (w+1)*16*NT) of the tile for all M_T slots, so each packed weight is
+// unpacked exactly once per workgroup and the wave's weight tile in LDS is private to it
+// (no barrier on the weight path).  The activation tile is shared by the four waves.
+//
+// MFMA mapping (v_mfma_f32_16x16x32_{f16,bf16}): tokens on the M side, output features on
+// the N side.  Lane l holds for A: row l%16, k-slots 8*(l/16)..+7; for B: column l%16, same
+// k-slots; for the 16x16 result: rows 4*(l/16)..+3, column l%16.
+//
+// Reduction-index permutation.  Summation order over k is free, so one chunk-step of
+// CK = 32*KW reduction indices feeds KW MFMAs like this: lane (n, j) reads KW consecutive
+// packed words (8*KW k's starting at CK*u + 8*KW*j); word i goes to MFMA i.  MFMA i thus
+// contracts k = CK*u + 8*KW*j + 8*i + e (j = 0..3, e = 0..7); the A operand is read at the
+// same k's.  Inside a word the nibble pairs come out as (e, e+4), so the A tile is stored in
+// LDS with each run of 8 elements reordered to 0,4,1,5,2,6,3,7.  KW is chosen so that one
+// chunk-step never straddles a quantisation group (group % CK == 0).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace moe {
+
+struct GemmParams {
+  const void* A;
+  int row_div;
+  const int32_t* qweight;
+  const void* scales;
+  const uint8_t* zeros;
+  const int32_t* sorted_slot_ids;
+  const int32_t* block_expert_ids;
+  const int32_t* num_padded;
+  int num_slots, E, N_out, K_in, group, block_m;
+  void* C;
+  int ldc;
+  int n_tiles;    // workgroups along the feature dimension
+  int G;          // K_in / group
+  int cpg;        // chunk-steps per quantisation group = group / (32*KW)
+  int half_n;     // fused SiLU-and-multiply: N (weight rows [0,N) gate, [N,2N) up); else 0
+  int sz_vec;     // 1 if scale rows are 16-byte aligned (G % 8 == 0 and aligned base pointers)
+};
+
+typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float floatx4_t __attribute__((ext_vector_type(4)));
+typedef float floatx2_t __attribute__((ext_vector_type(2)));
+
+constexpr int kF16 = 0, kBF16 = 1;
+
+template <int DT>
+__device__ __forceinline__ floatx4_t mfma16x16x32(const uint4& a, const uint4& b, floatx4_t c) {
+  if constexpr (DT == kF16) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, a),
+                                                  __builtin_bit_cast(half8_t, b), c, 0, 0, 0);
+  } else {
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a),
+                                                   __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
+  }
+}
+
+// Per (group, feature row) dequantisation constants, decoded from the 32-bit LDS entry.
+//   f16 : entry = (0x6400 | z) << 16 | scale_bits      -> s2 = (s, s), zc2 = (1024+z, 1024+z)
+//   bf16: entry = scale_bits << 16 | z                 -> s (fp32), nzs = -(128+z)*s (exact)
+template <int DT>
+struct DeqCtx;
+template <>
+struct DeqCtx<kF16> {
+  half2_t s2, zc2;
+  __device__ __forceinline__ explicit DeqCtx(uint32_t e) {
+    s2 = __builtin_bit_cast(half2_t, (e & 0xffffu) * 0x10001u);
+    zc2 = __builtin_bit_cast(half2_t, (e >> 16) * 0x10001u);
+  }
+};
+template <>
+struct DeqCtx<kBF16> {
+  float s, nzs;
+  __device__ __forceinline__ explicit DeqCtx(uint32_t e) {
+    s = __builtin_bit_cast(float, e & 0xffff0000u);
+    nzs = -(128.0f + (float)(e & 0xffu)) * s;
+  }
+};
+
+template <int DT>
+__device__ __forceinline__ uint32_t pack_sz_entry(uint16_t scale_bits, uint8_t z) {
+  if constexpr (DT == kF16) return ((0x6400u | (uint32_t)z) << 16) | (uint32_t)scale_bits;
+  else return ((uint32_t)scale_bits << 16) | (uint32_t)z;
+}
+
+// One packed word (8 nibbles) -> 8 dequantised 16-bit values in the order 0,4,1,5,2,6,3,7.
+// f16 : OR the nibble into the mantissa of 1024.0 (exact 1024+q), subtract 1024+z (exact
+//       integer q-z), multiply by the scale (one rounding).
+// bf16: OR into 128.0 (exact 128+q), widen to fp32 by shifting, fma with the scale and the
+//       exact -(128+z)*s (result (q-z)*s exact in fp32), round once to bf16.
+template <int DT>
+__device__ __forceinline__ uint4 dequant_word(uint32_t w, const DeqCtx<DT>& c) {
+  uint32_t r[4];
+  if constexpr (DT == kF16) {
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+      uint32_t t = ((w >> (4 * p)) & 0x000F000Fu) | 0x64006400u;
+      half2_t h = (__builtin_bit_cast(half2_t, t) - c.zc2) * c.s2;
+      r[p] = __builtin_bit_cast(uint32_t, h);
+    }
+  } else {
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+      uint32_t t = ((w >> (4 * p)) & 0x000F000Fu) | 0x43004300u;
+      float lo = __builtin_bit_cast(float, t << 16);
+      float hi = __builtin_bit_cast(float, t & 0xffff0000u);
+      floatx2_t f = {__builtin_fmaf(lo, c.s, c.nzs), __builtin_fmaf(hi, c.s, c.nzs)};
+      r[p] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2_t));
+    }
+  }
+  return make_uint4(r[0], r[1], r[2], r[3]);
+}
+
+template <int DT>
+__device__ __forceinline__ uint16_t to_bits16(float v) {
+  if constexpr (DT == kF16) return __builtin_bit_cast(uint16_t, (_Float16)v);
+  else return __builtin_bit_cast(uint16_t, (__bf16)v);
+}
+template <int DT>
+__device__ __forceinline__ float from_bits16(uint16_t b) {
+  if constexpr (DT == kF16) return (float)__builtin_bit_cast(_Float16, b);
+  else return __builtin_bit_cast(float, (uint32_t)b << 16);
+}
+
+__device__ __forceinline__ float silu_f32(float x) { return x / (1.0f + __expf(-x)); }
+
+// 8 consecutive 16-bit elements x0..x7 -> order x0,x4,x1,x5,x2,x6,x3,x7
+__device__ __forceinline__ uint4 interleave8(const uint4& a) {
+  uint4 o;
+  o.x = __builtin_amdgcn_perm(a.z, a.x, 0x05040100u);  // (x0, x4)
+  o.y = __builtin_amdgcn_perm(a.z, a.x, 0x07060302u);  // (x1, x5)
+  o.z = __builtin_amdgcn_perm(a.w, a.y, 0x05040100u);  // (x2, x6)
+  o.w = __builtin_amdgcn_perm(a.w, a.y, 0x07060302u);  // (x3, x7)
+  return o;
+}
+
+// Workgroups are dealt round-robin to the 8 XCDs (each with its own L2).  Map the hardware
+// block id to a logical tile index so that every XCD walks a contiguous range of tiles:
+// tiles that share an activation tile (same slot block, neighbouring feature tiles) or the
+// same expert's weights (neighbouring slot blocks) then meet in one L2.
+__device__ __forceinline__ int xcd_contiguous_index(int pid, int nwg) {
+  const int xcd = pid & 7, idx = pid >> 3;
+  const int per = nwg >> 3, rem = nwg & 7;
+  return xcd < rem ? xcd * (per + 1) + idx : rem * (per + 1) + (xcd - rem) * per + idx;
+}
+
+template <int KW>
+struct WordVec;
+template <>
+struct WordVec<1> { uint32_t w[1]; };
+template <>
+struct WordVec<2> { uint32_t w[2]; };
+template <>
+struct WordVec<4> { uint32_t w[4]; };
+
+template <int KW>
+__device__ __forceinline__ WordVec<KW> lds_read_words(const unsigned char* p) {
+  WordVec<KW> v;
+  if constexpr (KW == 4) {
+    uint4 t = *reinterpret_cast<const uint4*>(p);
+    v.w[0] = t.x; v.w[1] = t.y; v.w[2] = t.z; v.w[3] = t.w;
+  } else if constexpr (KW == 2) {
+    uint2 t = *reinterpret_cast<const uint2*>(p);
+    v.w[0] = t.x; v.w[1] = t.y;
+  } else {
+    v.w[0] = *reinterpret_cast<const uint32_t*>(p);
+  }
+  return v;
+}
+
+template <int MT, int NT, int KS>
+struct TileGeom {
+  static constexpr int M_T = 16 * MT;        // slots per workgroup tile
+  static constexpr int NW = 16 * NT;         // features per wave
+  static constexpr int N_T = 4 * NW;         // features per workgroup
+  static constexpr int XP = KS * 2 + 16;     // LDS bytes per activation row (padded)
+  static constexpr int WP = KS / 2 + 16;     // LDS bytes per packed weight row (padded)
+  static constexpr int CPR = KS / 8;         // 16-byte chunks per activation row
+  static constexpr int RPP = 256 / CPR;      // activation rows per cooperative pass
+  static constexpr int XPASS = M_T / RPP;    // passes per stage
+  static constexpr int LPR = KS / 32;        // lanes covering one weight row (16 B each)
+  static constexpr int RPI = 64 / LPR;       // weight rows per wave load instruction
+  static constexpr int WPASS = NW / RPI;     // weight load instructions per stage per wave
+  static_assert(XPASS >= 1 && WPASS >= 1, "tile too small for the load mapping");
+  static size_t lds_bytes(int G) {
+    return (size_t)2 * M_T * XP + (size_t)4 * NW * WP + (size_t)G * N_T * 4 + (size_t)M_T * 4;
+  }
+};
+
+// Local feature index of a workgroup tile -> weight row / output column.
+//   plain : feature f = tile*N_T + lf, weight row = output column = f.
+//   fused SiLU-and-multiply: wave-local sub-tiles alternate gate, up; the pair (2p, 2p+1)
+//   covers act columns c..c+15 with weight rows c (gate) and N + c (up).
+template <int NT, int FUSE>
+__device__ __forceinline__ void feature_of(int n_tile, int wave, int sub, int n, const GemmParams& p,
+                                           int& wrow, int& ocol, bool& valid) {
+  constexpr int NW = 16 * NT, N_T = 4 * NW;
+  if constexpr (FUSE == 0) {
+    const int f = n_tile * N_T + wave * NW + sub * 16 + n;
+    wrow = f; ocol = f; valid = f < p.N_out;
+  } else {
+    const int c = n_tile * (N_T / 2) + wave * (NW / 2) + (sub >> 1) * 16 + n;
+    wrow = (sub & 1) * p.half_n + c; ocol = c; valid = c < p.half_n;
+  }
+}
+
+template <int DT, int MT, int NT, int KS, int KW, int FUSE>
+__global__ void __launch_bounds__(256) w4a16_gemm_kernel(const GemmParams p) {
+  using G_ = TileGeom<MT, NT, KS>;
+  constexpr int M_T = G_::M_T, NW = G_::NW, N_T = G_::N_T, XP = G_::XP, WP = G_::WP;
+  constexpr int CPR = G_::CPR, RPP = G_::RPP, XPASS = G_::XPASS;
+  constexpr int LPR = G_::LPR, RPI = G_::RPI, WPASS = G_::WPASS;
+  constexpr int CK = 32 * KW, UCH = KS / CK;
+  static_assert(FUSE == 0 || NT % 2 == 0, "fused SiLU needs gate/up sub-tile pairs");
+
+  extern __shared__ __align__(16) unsigned char smem[];
+  unsigned char* xs = smem;                                        // [2][M_T][XP]
+  unsigned char* ws_all = xs + 2 * M_T * XP;                       // [4][NW][WP]
+  uint32_t* sz = reinterpret_cast<uint32_t*>(ws_all + 4 * NW * WP);  // [G][N_T]
+  int* slot_s = reinterpret_cast<int*>(sz + p.G * N_T);            // [M_T]
+
+  const int L = xcd_contiguous_index(blockIdx.x, gridDim.x);
+  const int n_tile = L % p.n_tiles;
+  const int row0 = (L / p.n_tiles) * M_T;
+  if (row0 >= *p.num_padded) return;
+  const int e = p.block_expert_ids[row0 / p.block_m];
+  if (e < 0 || e >= p.E) return;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int ln = lane & 15, lj = lane >> 4;
+  unsigned char* wsw = ws_all + wave * NW * WP;
+  const int K_in = p.K_in, kwords = K_in >> 3;
+
+  // ---- per-thread global pointers -------------------------------------------------
+  const uint16_t* A16 = reinterpret_cast<const uint16_t*>(p.A);
+  const uint16_t* xptr[XPASS];
+  bool xok[XPASS];
+  const int xr_row = tid / CPR, xr_chunk = tid % CPR;
+#pragma unroll
+  for (int ps = 0; ps < XPASS; ++ps) {
+    const int slot = p.sorted_slot_ids[row0 + ps * RPP + xr_row];
+    xok[ps] = slot >= 0 && slot < p.num_slots;
+    const int arow = xok[ps] ? slot / p.row_div : 0;
+    xptr[ps] = A16 + (size_t)arow * K_in + xr_chunk * 8;
+  }
+  const uint32_t* qw = reinterpret_cast<const uint32_t*>(p.qweight);
+  const uint32_t* wptr[WPASS];
+  bool wok[WPASS];
+  const int wl_row = lane / LPR, wl_chunk = lane % LPR;
+#pragma unroll
+  for (int q = 0; q < WPASS; ++q) {
+    const int rw = q * RPI + wl_row;
+    int wrow, ocol;
+    feature_of<NT, FUSE>(n_tile, wave, rw >> 4, rw & 15, p, wrow, ocol, wok[q]);
+    if (!wok[q]) wrow = 0;
+    wptr[q] = qw + ((size_t)e * p.N_out + wrow) * kwords + wl_chunk * 4;
+  }
+
+  uint4 xr[2][XPASS], wr[2][WPASS];
+  auto load_stage = [&](int st, uint4(&xv)[XPASS], uint4(&wv)[WPASS]) {
+    const int k0 = st * KS;
+#pragma unroll
+    for (int q = 0; q < WPASS; ++q) {
+      wv[q] = make_uint4(0, 0, 0, 0);
+      if (wok[q] && k0 + wl_chunk * 32 + 32 <= K_in)
+        wv[q] = *reinterpret_cast<const uint4*>(wptr[q] + (k0 >> 3));
+    }
+#pragma unroll
+    for (int ps = 0; ps < XPASS; ++ps) {
+      xv[ps] = make_uint4(0, 0, 0, 0);
+      if (xok[ps] && k0 + xr_chunk * 8 + 8 <= K_in)
+        xv[ps] = *reinterpret_cast<const uint4*>(xptr[ps] + k0);
+    }
+  };
+  auto store_stage = [&](const uint4(&xv)[XPASS], const uint4(&wv)[WPASS], unsigned char* xbuf) {
+#pragma unroll
+    for (int q = 0; q < WPASS; ++q)
+      *reinterpret_cast<uint4*>(wsw + (q * RPI + wl_row) * WP + wl_chunk * 16) = wv[q];
+#pragma unroll
+    for (int ps = 0; ps < XPASS; ++ps)
+      *reinterpret_cast<uint4*>(xbuf + (ps * RPP + xr_row) * XP + xr_chunk * 16) = interleave8(xv[ps]);
+  };
+
+  const int nst = (K_in + KS - 1) / KS;
+  load_stage(0, xr[0], wr[0]);
+  if (nst > 1) load_stage(1, xr[1], wr[1]);
+
+  // ---- stage scales / zero points of this tile's rows into LDS ---------------------
+  if (tid < M_T) slot_s[tid] = p.sorted_slot_ids[row0 + tid];
+  {
+    const uint16_t* sc = reinterpret_cast<const uint16_t*>(p.scales);
+    const int G = p.G, G8 = (G + 7) >> 3;
+    for (int idx = tid; idx < N_T * G8; idx += 256) {
+      const int lf = idx % N_T, gb = (idx / N_T) * 8;
+      int wrow, ocol;
+      bool ok;
+      feature_of<NT, FUSE>(n_tile, lf / NW, (lf % NW) >> 4, lf & 15, p, wrow, ocol, ok);
+      uint16_t sv[8];
+      uint8_t zv[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) { sv[i] = 0; zv[i] = 0; }
+      if (ok) {
+        const size_t base = ((size_t)e * p.N_out + wrow) * G + gb;
+        if (p.sz_vec) {
+          const uint4 s4 = *reinterpret_cast<const uint4*>(sc + base);
+          const uint2 z2 = *reinterpret_cast<const uint2*>(p.zeros + base);
+          const uint32_t sw[4] = {s4.x, s4.y, s4.z, s4.w};
+          const uint32_t zw[2] = {z2.x, z2.y};
+#pragma unroll
+          for (int i = 0; i < 8; ++i) {
+            sv[i] = (uint16_t)(sw[i >> 1] >> (16 * (i & 1)));
+            zv[i] = (uint8_t)(zw[i >> 2] >> (8 * (i & 3)));
+          }
+        } else {
+#pragma unroll
+          for (int i = 0; i < 8; ++i)
+            if (gb + i < G) { sv[i] = sc[base + i]; zv[i] = p.zeros[base + i]; }
+        }
+      }
+#pragma unroll
+      for (int i = 0; i < 8; ++i)
+        if (gb + i < G) sz[(gb + i) * N_T + lf] = pack_sz_entry<DT>(sv[i], zv[i]);
+    }
+  }
+
+  floatx4_t acc[MT][NT];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+    for (int s = 0; s < NT; ++s) acc[mt][s] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+
+  auto compute_stage = [&](int st, const unsigned char* xbuf) {
+    const int left = (K_in - st * KS) / CK;
+    const int nu = left < UCH ? left : UCH;
+#pragma unroll
+    for (int u = 0; u < UCH; ++u) {
+      if (u >= nu) break;
+      const int cc = st * UCH + u;
+      const int gi = p.cpg == 1 ? cc : cc / p.cpg;
+      WordVec<KW> wv[NT];
+      uint32_t ent[NT];
+#pragma unroll
+      for (int s = 0; s < NT; ++s) {
+        ent[s] = sz[gi * N_T + wave * NW + s * 16 + ln];
+        wv[s] = lds_read_words<KW>(wsw + (s * 16 + ln) * WP + 16 * KW * u + 4 * KW * lj);
+      }
+#pragma unroll
+      for (int i = 0; i < KW; ++i) {
+        uint4 b[NT];
+#pragma unroll
+        for (int s = 0; s < NT; ++s) b[s] = dequant_word<DT>(wv[s].w[i], DeqCtx<DT>(ent[s]));
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+          const uint4 a = *reinterpret_cast<const uint4*>(
+              xbuf + (mt * 16 + ln) * XP + 2 * (CK * u + 8 * KW * lj + 8 * i));
+#pragma unroll
+          for (int s = 0; s < NT; ++s) acc[mt][s] = mfma16x16x32<DT>(a, b[s], acc[mt][s]);
+        }
+      }
+    }
+  };
+
+  store_stage(xr[0], wr[0], xs);
+  __syncthreads();
+
+  // Two stages per trip so the register prefetch buffers are indexed statically:
+  // while stage st is computed from LDS, stage st+1 sits in registers and st+2 is in flight.
+  for (int st = 0; st < nst; st += 2) {
+    if (st + 2 < nst) load_stage(st + 2, xr[0], wr[0]);
+    compute_stage(st, xs);
+    if (st + 1 < nst) store_stage(xr[1], wr[1], xs + M_T * XP);
+    __syncthreads();
+    if (st + 1 < nst) {
+      if (st + 3 < nst) load_stage(st + 3, xr[1], wr[1]);
+      compute_stage(st + 1, xs + M_T * XP);
+      if (st + 2 < nst) store_stage(xr[0], wr[0], xs);
+      __syncthreads();
+    }
+  }
+
+  // ---- epilogue: one rounding to the 16-bit type, rows addressed by slot id ---------
+  uint16_t* C16 = reinterpret_cast<uint16_t*>(p.C);
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int slot = slot_s[mt * 16 + lj * 4 + i];
+      if (slot < 0 || slot >= p.num_slots) continue;
+      uint16_t* crow = C16 + (size_t)slot * p.ldc;
+      if constexpr (FUSE == 0) {
+#pragma unroll
+        for (int s = 0; s < NT; ++s) {
+          int wrow, ocol; bool ok;
+          feature_of<NT, FUSE>(n_tile, wave, s, ln, p, wrow, ocol, ok);
+          if (ok) crow[ocol] = to_bits16<DT>(acc[mt][s][i]);
+        }
+      } else {
+#pragma unroll
+        for (int s = 0; s < NT; s += 2) {
+          int wrow, ocol; bool ok;
+          feature_of<NT, FUSE>(n_tile, wave, s, ln, p, wrow, ocol, ok);
+          if (ok) {
+            // round gate/up to the storage type first so the fused path equals the staged one
+            const float g = from_bits16<DT>(to_bits16<DT>(acc[mt][s][i]));
+            const float u = from_bits16<DT>(to_bits16<DT>(acc[mt][s + 1][i]));
+            crow[ocol] = to_bits16<DT>(silu_f32(g) * u);
+          }
+        }
+      }
+    }
+  }
+}
+
+// Host-side launcher, one per instantiation.  Returns hipError_t as int.
+template <int DT, int MT, int NT, int KS, int KW, int FUSE>
+int launch_w4a16_gemm(const GemmParams& p, int grid, hipStream_t stream);
+
+}  // namespace moe
