@@ -1,0 +1,191 @@
+#!/usr/bin/env python3
+"""Benchmark of the W4A16 MoE layer on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config NAME]
+
+One step = one call of moe_w4a16_layer (bucketing, gate/up GEMM + SiLU-and-multiply, down
+GEMM, combine) on a seeded synthetic workload that is resident in HBM before the timed region.
+Prints ONE JSON line.  `value` is the layer's algorithmic HBM throughput in GB/s (weights of
+the active experts + activations in + result out, divided by the step time); TFLOP/s and both
+roofline fractions are included as extra keys.  The `roofline` object covers the dominant
+kernel (the gate/up grouped GEMM), timed inside the same steps with HIP events recorded by
+the library on the stream it launches on.  `cpu_baseline` times the CPU oracle on a bounded
+sample of the same workload on this machine's host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_PEAK_TFLOPS = 2500.0      # dense fp16/bf16 MFMA, published
+
+
+def algorithmic_bytes(cfg, topk_ids):
+    """Minimum HBM traffic of one layer call (weights are int4: counted as 4 bits)."""
+    E_act = int(np.unique(topk_ids[(topk_ids >= 0) & (topk_ids < cfg.E)]).size)
+    K, N, g, T, S = cfg.K, cfg.N, cfg.group, cfg.T, cfg.S
+    w1 = 2 * N * K // 2 + 2 * N * (K // g) * 3          # packed nibbles + (2-byte scale, 1-byte zero)
+    w2 = K * N // 2 + K * (N // g) * 3
+    io = 2 * T * K + 2 * T * K + 8 * S                   # X in, out, ids + routing weights
+    gemm1 = E_act * w1 + 2 * T * K + 2 * S * N + 4 * S   # dominant kernel: weights, X, act out, slot table
+    return E_act, E_act * (w1 + w2) + io, gemm1
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", default="deepseek_decode")
+    ap.add_argument("--tile", default="", help="mt,nt override of the GEMM tile (tuning)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2504_16214_amd as M
+    from moe_workloads import CONFIGS, make_inputs
+
+    cfg = CONFIGS[args.config]
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    t0 = time.time()
+    inp = make_inputs(cfg)
+    print(f"[bench] generated {cfg.name} in {time.time() - t0:.1f}s", file=sys.stderr, flush=True)
+    tdt = torch.float16 if cfg.dtype == "f16" else torch.bfloat16
+    mdt = M.MOE_F16 if cfg.dtype == "f16" else M.MOE_BF16
+
+    def dev16(bits):
+        return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda().view(tdt)
+
+    X, s1, s2 = dev16(inp.x_bits), dev16(inp.s1_bits), dev16(inp.s2_bits)
+    ids = torch.from_numpy(inp.topk_ids).cuda()
+    w = torch.from_numpy(inp.topk_weights).cuda()
+    qw1, z1 = torch.from_numpy(inp.qw1).cuda(), torch.from_numpy(inp.z1).cuda()
+    qw2, z2 = torch.from_numpy(inp.qw2).cuda(), torch.from_numpy(inp.z2).cuda()
+    out = torch.empty((cfg.T, cfg.K), dtype=tdt, device="cuda")
+    ws = torch.empty(M.moe_w4a16_layer_workspace_bytes(cfg.T, cfg.K, cfg.N, cfg.E, cfg.topk, mdt),
+                     dtype=torch.uint8, device="cuda")
+    if args.tile:
+        mt, nt = (int(v) for v in args.tile.split(","))
+        M.moe_set_tile_override(mt, nt)
+
+    def step():
+        M.moe_w4a16_layer(X, ids, w, qw1, s1, z1, qw2, s2, z2, out, cfg.group, ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    # per-step stage events, created (and first recorded) before the timed region
+    K_steps = args.steps
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(K_steps)]
+    for row in evs:
+        for e in row:
+            e.record()
+    torch.cuda.synchronize()
+
+    t_start = time.perf_counter()
+    for i in range(K_steps):
+        M.moe_set_stage_events([e.cuda_event for e in evs[i]])
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t_start
+    M.moe_set_stage_events(None)
+
+    ms_per_step = elapsed * 1e3 / K_steps
+    stage_ms = np.array([[row[j].elapsed_time(row[j + 1]) for j in range(4)] for row in evs])
+    stage_avg = stage_ms.mean(axis=0)
+    E_act, layer_bytes, gemm1_bytes = algorithmic_bytes(cfg, inp.topk_ids)
+    flops = 6.0 * cfg.K * cfg.N * cfg.S
+    gbs = layer_bytes / (ms_per_step * 1e-3) / 1e9
+    tflops = flops / (ms_per_step * 1e-3) / 1e12
+    g1_gbs = gemm1_bytes / (stage_avg[1] * 1e-3) / 1e9
+    g1_tflops = (4.0 * cfg.K * cfg.N * cfg.S) / (stage_avg[1] * 1e-3) / 1e12
+    hbm_bound = (flops / layer_bytes) < (MFMA_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9))
+
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get(cfg.name, {}).get("gemm1_bytes_per_launch")
+        except Exception:
+            traffic = None
+    if hbm_bound:
+        roofline = {"bound": "hbm", "achieved": round(g1_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": round(g1_gbs / HBM_PEAK_GBS, 4), "traffic": traffic}
+    else:
+        roofline = {"bound": "mfma", "achieved": round(g1_tflops, 1), "peak": MFMA_PEAK_TFLOPS,
+                    "unit": "TFLOP/s", "frac": round(g1_tflops / MFMA_PEAK_TFLOPS, 4), "traffic": traffic}
+    roofline["kernel"] = "w4a16_gemm_kernel (gate/up projection + SiLU-and-multiply)"
+    roofline["kernel_ms"] = round(float(stage_avg[1]), 4)
+
+    result = {
+        "metric": "W4A16 MoE layer TFLOP/s + HBM GB/s (% of MI355X roofline), 1 GPU",
+        "value": round(gbs, 1), "unit": "GB/s",
+        "n_gpus": 1, "steps": K_steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: T={cfg.T} K={cfg.K} N={cfg.N} E={cfg.E} top{cfg.topk} "
+                               f"g={cfg.group} {cfg.dtype}, seed {cfg.seed}",
+                   "active_experts": E_act, "algorithmic_bytes": layer_bytes, "flop": flops,
+                   "block_m": M.moe_layer_block_m(cfg.T, cfg.E, cfg.topk), "tile_override": args.tile or None},
+        "tflops": round(tflops, 2), "hbm_frac": round(gbs / HBM_PEAK_GBS, 4),
+        "mfma_frac": round(tflops / MFMA_PEAK_TFLOPS, 4),
+        "stage_ms": {"align": round(float(stage_avg[0]), 4), "gemm1_silu": round(float(stage_avg[1]), 4),
+                     "gemm2": round(float(stage_avg[2]), 4), "combine": round(float(stage_avg[3]), 4)},
+        "roofline": roofline,
+    }
+
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(cfg, inp)
+    print(json.dumps(result), flush=True)
+
+
+def cpu_baseline(cfg, inp):
+    """The CPU oracle as it stands, on a bounded sample: token 0 with as many of its routed
+    experts as keep the run to roughly 10-30 s; throughput in the metric's unit (algorithmic
+    weight bytes of the experts it touched per second)."""
+    from oracle import moe_oracle as O
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    per_expert = 3.0 * cfg.K * cfg.N            # weights unpacked per expert (W1 + W2)
+    n_exp = int(max(1, min(cfg.topk, 1.2e8 // per_expert if per_expert < 1.2e8 else 1)))
+    n_tok = 1
+    if per_expert * cfg.topk < 3e7:             # small experts: take more tokens
+        n_tok = int(min(cfg.T, max(1, 1.2e8 // (per_expert * cfg.topk))))
+        n_exp = cfg.topk
+    ids = inp.topk_ids[:n_tok].copy()
+    ids[:, n_exp:] = -1                          # ignored slots: not computed
+    X = O.decode_bits(inp.x_bits[:n_tok], cfg.dtype)
+    s1 = O.decode_bits(inp.s1_bits, cfg.dtype)
+    s2 = O.decode_bits(inp.s2_bits, cfg.dtype)
+    t0 = time.perf_counter()
+    O.layer(X, ids, inp.topk_weights[:n_tok], inp.qw1, s1, inp.z1, inp.qw2, s2, inp.z2, cfg.group, cfg.dtype)
+    dt = time.perf_counter() - t0
+    touched = int(np.unique(ids[ids >= 0]).size)
+    g = cfg.group
+    wbytes = touched * (1.5 * cfg.K * cfg.N + 3 * cfg.K * cfg.N // g * 3)
+    return {"value": round(wbytes / dt / 1e9, 4), "unit": "GB/s", "cores": int(threads), "kind": "oracle",
+            "seconds": round(dt, 2),
+            "sample": f"{n_tok} token(s) x {n_exp} routed expert(s) of {cfg.name} ({touched} experts touched), "
+                      f"NumPy fp64 oracle, whole-layer definition"}
+
+
+if __name__ == "__main__":
+    main()

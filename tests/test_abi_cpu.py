@@ -1,0 +1,101 @@
+"""CPU-only checks of the C ABI: the in-tree library loads, exports every function the
+header declares, and its host logic (capacity, workspace sizing, block choice, argument
+validation that happens before any launch) behaves as documented.  No kernel is launched."""
+from __future__ import annotations
+
+import ctypes
+import os
+import re
+
+import pytest
+
+from oracle import moe_oracle as O
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "moe_w4a16.h")
+
+
+@pytest.fixture(scope="module")
+def binding():
+    import paper_2504_16214_amd.binding as b
+    if not os.path.exists(b.library_path()):
+        from paper_2504_16214_amd.build import build
+        build(verbose=False)
+    b.load_library()
+    return b
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(moe_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_declares_the_five_entry_points():
+    names = declared_functions()
+    for n in ("moe_align_by_expert", "moe_w4a16_grouped_gemm", "moe_silu_mul", "moe_combine", "moe_w4a16_layer"):
+        assert n in names
+
+
+def test_library_exports_every_declared_symbol(binding):
+    lib = ctypes.CDLL(binding.library_path())
+    for name in declared_functions():
+        assert hasattr(lib, name), f"{name} declared in the header but not exported"
+    assert sorted(binding.EXPORTS) == declared_functions()
+
+
+@pytest.mark.parametrize("T,topk,E,bm", [(16, 2, 8, 16), (128, 8, 256, 16), (4096, 8, 256, 128), (1, 1, 1, 256),
+                                         (0, 2, 4, 16), (3, 2, 1000, 64)])
+def test_capacity_matches_oracle(binding, T, topk, E, bm):
+    assert binding.moe_align_capacity(T, topk, E, bm) == O.align_capacity(T, topk, E, bm)
+
+
+def test_capacity_rejects_bad_block(binding):
+    assert binding.moe_align_capacity(4, 2, 8, 24) == 0
+
+
+def test_workspace_covers_tables_and_intermediates(binding):
+    T, K, N, E, topk = 128, 7168, 2048, 256, 8
+    need = binding.moe_w4a16_layer_workspace_bytes(T, K, N, E, topk, 0)
+    S = T * topk
+    assert need >= S * N * 2 + S * K * 2 + O.align_capacity(T, topk, E, 128) * 4
+    assert need < 2 * (S * N * 2 + S * K * 2) + (1 << 22)
+    assert binding.moe_w4a16_layer_workspace_bytes(-1, K, N, E, topk, 0) == 0
+
+
+def test_layer_block_choice_tracks_rows_per_expert(binding):
+    assert binding.moe_layer_block_m(128, 256, 8) == 16      # about 4 rows per expert
+    assert binding.moe_layer_block_m(64, 8, 2) == 32         # 16 rows per expert
+    assert binding.moe_layer_block_m(4096, 256, 8) == 128    # 128 rows per expert
+
+
+def test_validation_before_launch_returns_status(binding):
+    lib = binding.load_library()
+    assert lib.moe_silu_mul(None, None, -1, 8, 0, None) == 1
+    assert b"S >= 0" in lib.moe_last_error()
+    assert lib.moe_combine(None, None, None, 4, 0, 8, 0, None) == 1
+    assert lib.moe_align_by_expert(None, 4, 2, 2000, 16, None, None, None, None, None, None) == 2
+    assert lib.moe_align_by_expert(None, 4, 2, 8, 17, None, None, None, None, None, None) == 1
+    # grouped GEMM: shape checks come before any pointer is touched
+    args = [None, 1, None, None, None, None, None, None]
+    assert lib.moe_w4a16_grouped_gemm(*args, 8, 4, 64, 256, 48, 16, 0, None, None) == 2      # group % 32
+    assert lib.moe_w4a16_grouped_gemm(*args, 8, 4, 64, 200, 64, 16, 0, None, None) == 2      # K_in % group
+    assert lib.moe_w4a16_grouped_gemm(*args, 8, 4, 60, 256, 64, 16, 0, None, None) == 2      # N_out % 16
+    assert lib.moe_w4a16_grouped_gemm(*args, 8, 4, 64, 256, 64, 16, 5, None, None) == 1      # dtype
+    assert lib.moe_w4a16_grouped_gemm(*args, 8, 4, 64, 256, 64, 16, 0, None, None) == 1      # null pointers
+    assert lib.moe_w4a16_grouped_gemm(*args, 0, 4, 64, 256, 64, 16, 0, None, None) == 0      # no slots: no-op
+    assert lib.moe_w4a16_layer(*([None] * 10), 0, 256, 128, 4, 2, 128, 0, None, 0, None) == 0  # T == 0
+    assert lib.moe_w4a16_layer(*([None] * 10), 4, 256, 128, 4, 2, 128, 0, None, 0, None) == 1  # null pointers
+    assert lib.moe_set_stage_events(None, 0) == 0
+    assert lib.moe_set_tile_override(0, 0) == 0
+
+
+def test_product_path_does_not_import_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2504_16214_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".hpp", ".h", ".def")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in text.lower().replace("no cpu fallback", ""), f
+    assert "oracle" not in open(os.path.join(ROOT, "moe_workloads", "__init__.py")).read().replace(
+        "CPU oracle and the HIP path alike", "")
