@@ -2,8 +2,8 @@
 
 Plain, slow, obviously-correct NumPy: explicit nibble unpack, exact
 dequantisation, float64 matmuls, explicit rounding to the 16-bit storage type
-at the four tensors the staged interface materialises (H, act, Y, out), and a
-float64 weighted combine.  Nothing here is blocked, fused or reordered, and
+at the tensors the staged interface materialises (H, act, Y, out; the whole-layer
+form keeps Y unrounded, see `layer`), and a float64 weighted combine.  Nothing here is blocked, fused or reordered, and
 nothing is shared with the HIP path.  Only tests, the smoke check and the
 benchmark's cpu_baseline leg may import this module; the product path must
 never route through it.
@@ -264,7 +264,19 @@ def layer(X, topk_ids, topk_weights, qw1, s1, z1, qw2, s2, z2, group: int, dt: s
     """The full layer for all tokens, or for the subset `tokens` (each token's
     output depends on no other token, so the restriction is the definition
     applied to fewer rows).  X, s1, s2 are float64 values; output float64 values
-    rounded to dt."""
+    rounded to dt.
+
+    Rounding points of the whole layer: H and act are rounded to dt (they are
+    the 16-bit operands the second mixed-type GEMM consumes: A is fp16/bf16 by
+    the operator's definition, Table III), the result `out` is rounded to dt.
+    The down projection Y is NOT rounded inside the layer: it goes into the
+    weighted combine at full precision and the sum is rounded once.  (The paper
+    does not state rounding points.  Rounding Y first would put a 16-bit ulp of
+    |Y| ~ 64..128, i.e. 0.03..0.06, times the routing weight into `out`, which
+    is larger than the 2e-2 absolute acceptance bound whenever two correct
+    implementations round a near-tie differently; the staged grouped_gemm entry
+    point still rounds its own output.)  round_intermediates=False also keeps H
+    and act in float64."""
     X = np.asarray(X, dtype=np.float64)
     ids = np.asarray(topk_ids)
     w = np.asarray(topk_weights)
@@ -278,7 +290,7 @@ def layer(X, topk_ids, topk_weights, qw1, s1, z1, qw2, s2, z2, group: int, dt: s
     valid = (slot_expert >= 0) & (slot_expert < E)
     H = grouped_gemm(X, topk, qw1, s1, z1, slot_expert, group, mid, fill=0.0)
     act = silu_mul(H, mid)
-    Y = grouped_gemm(act, 1, qw2, s2, z2, slot_expert, group, mid, fill=0.0)
+    Y = grouped_gemm(act, 1, qw2, s2, z2, slot_expert, group, None, fill=0.0)
     out = combine(Y, w, dt, slot_valid=valid)
     if return_intermediates:
         return out, {"H": H, "act": act, "Y": Y}

@@ -13,7 +13,7 @@ namespace moe {
 int launch_align(const int32_t*, int, int, int, int, int32_t*, int32_t*, int32_t*, int32_t*, int32_t*,
                  hipStream_t);
 int launch_silu_mul(const void*, void*, long long, int, int, hipStream_t);
-int launch_combine(const void*, const float*, const int32_t*, int, void*, long long, int, int, int,
+int launch_combine(const void*, int, const float*, const int32_t*, int, void*, long long, int, int, int,
                    hipStream_t);
 
 // ---- table of compiled GEMM variants ------------------------------------------------------
@@ -105,7 +105,7 @@ struct GemmArgs {
   const int32_t* qweight; const void* scales; const uint8_t* zeros;
   const int32_t* sorted_slot_ids; const int32_t* block_expert_ids; const int32_t* num_padded;
   int num_slots, E, N_out, K_in, group, block_m, dt;
-  void* C; int ldc; int fuse_half_n;
+  void* C; int ldc; int fuse_half_n; int out_f32;
 };
 
 static int run_gemm(const GemmArgs& a, hipStream_t stream) {
@@ -148,6 +148,7 @@ static int run_gemm(const GemmArgs& a, hipStream_t stream) {
   p.G = G;
   p.cpg = a.group / (32 * kw);
   p.half_n = a.fuse_half_n;
+  p.out_f32 = a.out_f32;
   p.sz_vec = (G % 8 == 0 && (uintptr_t)a.scales % 16 == 0 && (uintptr_t)a.zeros % 8 == 0) ? 1 : 0;
   const size_t cap = align_capacity(a.num_slots, a.E, a.block_m);
   const long long grid = (long long)(cap / (16 * mt)) * p.n_tiles;
@@ -178,7 +179,7 @@ static Workspace carve(long long T, int K, int N, int E, int topk) {
   w.sorted = o;      o += round_up(align_capacity(S, E, 128) * 4, 256);
   w.blocks = o;      o += round_up((align_capacity(S, E, 16) / 16 + 1) * 4, 256);
   w.act = o;         o += round_up((size_t)S * N * 2, 256);
-  w.Y = o;           o += round_up((size_t)S * K * 2, 256);
+  w.Y = o;           o += round_up((size_t)S * K * 4, 256);   // float32: combined unrounded
   w.total = o;
   return w;
 }
@@ -219,7 +220,7 @@ int moe_w4a16_grouped_gemm(const void* A, int row_div, const int32_t* qweight, c
                            int E, int N_out, int K_in, int group_size, int block_m, moe_dtype dt,
                            void* C, void* stream) {
   GemmArgs a{A, row_div, qweight, scales, zeros, sorted_slot_ids, block_expert_ids, num_padded,
-             num_slots, E, N_out, K_in, group_size, block_m, (int)dt, C, N_out, 0};
+             num_slots, E, N_out, K_in, group_size, block_m, (int)dt, C, N_out, 0, 0};
   return run_gemm(a, (hipStream_t)stream);
 }
 
@@ -243,7 +244,7 @@ int moe_combine(const void* Y, const float* topk_weights, void* out, int T, int 
   if (!Y || !topk_weights || !out) return fail(MOE_INVALID_ARGUMENT, "null pointer argument");
   if (K % 8 == 0 && ((uintptr_t)Y | (uintptr_t)out) % 16 != 0)
     return fail(MOE_INVALID_ARGUMENT, "Y and out must be 16-byte aligned");
-  const int err = launch_combine(Y, topk_weights, nullptr, 0, out, T, topk, K, (int)dt, (hipStream_t)stream);
+  const int err = launch_combine(Y, 0, topk_weights, nullptr, 0, out, T, topk, K, (int)dt, (hipStream_t)stream);
   if (err != 0) return hip_fail(err, "combine launch");
   return MOE_OK;
 }
@@ -303,18 +304,18 @@ int moe_w4a16_layer(const void* X, const int32_t* topk_ids, const float* topk_we
 
   if (ev) (void)hipEventRecord((hipEvent_t)g_events[1], stream);
   GemmArgs g1{X, topk, qw1, s1, z1, sorted, blocks, num_padded, (int)S, E, 2 * N, K, group_size, block_m,
-              (int)dt, act, N, N};
+              (int)dt, act, N, N, 0};
   int st = run_gemm(g1, stream);
   if (st != MOE_OK) return st;
 
   if (ev) (void)hipEventRecord((hipEvent_t)g_events[2], stream);
   GemmArgs g2{act, 1, qw2, s2, z2, sorted, blocks, num_padded, (int)S, E, K, N, group_size, block_m,
-              (int)dt, Y, K, 0};
+              (int)dt, Y, K, 0, 1};
   st = run_gemm(g2, stream);
   if (st != MOE_OK) return st;
 
   if (ev) (void)hipEventRecord((hipEvent_t)g_events[3], stream);
-  err = launch_combine(Y, topk_weights, topk_ids, E, out, T, topk, K, (int)dt, stream);
+  err = launch_combine(Y, 1, topk_weights, topk_ids, E, out, T, topk, K, (int)dt, stream);
   if (err != 0) return hip_fail(err, "combine launch");
   if (ev) (void)hipEventRecord((hipEvent_t)g_events[4], stream);
   return MOE_OK;

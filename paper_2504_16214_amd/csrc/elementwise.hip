@@ -39,10 +39,13 @@ silu_mul_kernel(const uint16_t* __restrict__ H, uint16_t* __restrict__ act, long
 
 // ids == nullptr: every slot contributes.  Otherwise slots whose expert id lies outside
 // [0, E) contribute zero (their Y rows were never written).
-template <int DT>
+// YF32 = 1: Y holds float32 (the fused layer keeps the down projection unrounded until here).
+template <int DT, int YF32>
 __global__ void __launch_bounds__(256)
-combine_kernel(const uint16_t* __restrict__ Y, const float* __restrict__ w, const int32_t* __restrict__ ids,
+combine_kernel(const void* __restrict__ Yv, const float* __restrict__ w, const int32_t* __restrict__ ids,
                int E, uint16_t* __restrict__ out, long long T, int topk, int K) {
+  const uint16_t* Y = reinterpret_cast<const uint16_t*>(Yv);
+  const float* Yf = reinterpret_cast<const float*>(Yv);
   const bool vec = (K & 7) == 0;
   const long long per_row = vec ? (K >> 3) : K;
   const long long total = T * per_row;
@@ -57,12 +60,20 @@ combine_kernel(const uint16_t* __restrict__ Y, const float* __restrict__ w, cons
         const long long slot = t * topk + j;
         if (ids) { const int e = ids[slot]; if (e < 0 || e >= E) continue; }
         const float wj = w[slot];
-        const uint4 y = *reinterpret_cast<const uint4*>(Y + slot * (long long)K + c * 8);
-        const uint32_t yw[4] = {y.x, y.y, y.z, y.w};
+        if constexpr (YF32) {
+          const float4 y0 = *reinterpret_cast<const float4*>(Yf + slot * (long long)K + c * 8);
+          const float4 y1 = *reinterpret_cast<const float4*>(Yf + slot * (long long)K + c * 8 + 4);
+          const float yv[8] = {y0.x, y0.y, y0.z, y0.w, y1.x, y1.y, y1.z, y1.w};
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
-          acc[2 * k] = __builtin_fmaf(wj, from_bits16<DT>((uint16_t)yw[k]), acc[2 * k]);
-          acc[2 * k + 1] = __builtin_fmaf(wj, from_bits16<DT>((uint16_t)(yw[k] >> 16)), acc[2 * k + 1]);
+          for (int k = 0; k < 8; ++k) acc[k] = __builtin_fmaf(wj, yv[k], acc[k]);
+        } else {
+          const uint4 y = *reinterpret_cast<const uint4*>(Y + slot * (long long)K + c * 8);
+          const uint32_t yw[4] = {y.x, y.y, y.z, y.w};
+#pragma unroll
+          for (int k = 0; k < 4; ++k) {
+            acc[2 * k] = __builtin_fmaf(wj, from_bits16<DT>((uint16_t)yw[k]), acc[2 * k]);
+            acc[2 * k + 1] = __builtin_fmaf(wj, from_bits16<DT>((uint16_t)(yw[k] >> 16)), acc[2 * k + 1]);
+          }
         }
       }
       uint32_t o[4];
@@ -75,7 +86,8 @@ combine_kernel(const uint16_t* __restrict__ Y, const float* __restrict__ w, cons
       for (int j = 0; j < topk; ++j) {
         const long long slot = t * topk + j;
         if (ids) { const int e = ids[slot]; if (e < 0 || e >= E) continue; }
-        acc = __builtin_fmaf(w[slot], from_bits16<DT>(Y[slot * (long long)K + c]), acc);
+        const float yv = YF32 ? Yf[slot * (long long)K + c] : from_bits16<DT>(Y[slot * (long long)K + c]);
+        acc = __builtin_fmaf(w[slot], yv, acc);
       }
       out[t * (long long)K + c] = to_bits16<DT>(acc);
     }
@@ -102,16 +114,16 @@ int launch_silu_mul(const void* H, void* act, long long S, int N, int dt, hipStr
   return (int)hipGetLastError();
 }
 
-int launch_combine(const void* Y, const float* w, const int32_t* ids, int E, void* out, long long T,
-                   int topk, int K, int dt, hipStream_t stream) {
+int launch_combine(const void* Y, int y_f32, const float* w, const int32_t* ids, int E, void* out,
+                   long long T, int topk, int K, int dt, hipStream_t stream) {
   const long long items = T * (((K & 7) == 0) ? (K >> 3) : K);
   if (items == 0) return 0;
-  if (dt == kF16)
-    hipLaunchKernelGGL(combine_kernel<kF16>, dim3(grid_for(items)), dim3(256), 0, stream,
-                       (const uint16_t*)Y, w, ids, E, (uint16_t*)out, T, topk, K);
-  else
-    hipLaunchKernelGGL(combine_kernel<kBF16>, dim3(grid_for(items)), dim3(256), 0, stream,
-                       (const uint16_t*)Y, w, ids, E, (uint16_t*)out, T, topk, K);
+  const dim3 grid(grid_for(items)), block(256);
+#define MOE_LAUNCH_COMBINE(DT, F) \
+  hipLaunchKernelGGL((combine_kernel<DT, F>), grid, block, 0, stream, Y, w, ids, E, (uint16_t*)out, T, topk, K)
+  if (dt == kF16) { if (y_f32) MOE_LAUNCH_COMBINE(kF16, 1); else MOE_LAUNCH_COMBINE(kF16, 0); }
+  else { if (y_f32) MOE_LAUNCH_COMBINE(kBF16, 1); else MOE_LAUNCH_COMBINE(kBF16, 0); }
+#undef MOE_LAUNCH_COMBINE
   return (int)hipGetLastError();
 }
 

@@ -3,7 +3,8 @@
 // Dataflow (the efficient one of the paper's Fig. 4(b), Section II-C, re-cut for CDNA4):
 //   packed int4 weights  : global --128-bit coalesced loads--> VGPR --> wave-private LDS tile
 //                          --ds_read (one lane = one MFMA operand column)--> VGPR
-//                          --in-register nibble unpack, (q - z) * s--> MFMA B operand
+//                          --in-register nibble unpack to the exact integers q - z--> MFMA B operand
+//                          (the group scale multiplies the fp32 partial sum of each chunk-step)
 //   activations          : global --128-bit loads--> VGPR --> shared LDS tile (padded rows)
 //                          --ds_read_b128--> MFMA A operand
 //   scales / zero points : staged once per workgroup into LDS, one 32-bit entry per (group, row)
@@ -50,6 +51,7 @@ struct GemmParams {
   int cpg;        // chunk-steps per quantisation group = group / (32*KW)
   int half_n;     // fused SiLU-and-multiply: N (weight rows [0,N) gate, [N,2N) up); else 0
   int sz_vec;     // 1 if scale rows are 16-byte aligned (G % 8 == 0 and aligned base pointers)
+  int out_f32;    // 1: C is float32 (the layer's down projection feeds the combine unrounded)
 };
 
 typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
@@ -58,11 +60,14 @@ typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 typedef float floatx4_t __attribute__((ext_vector_type(4)));
 typedef float floatx2_t __attribute__((ext_vector_type(2)));
+// native 128-bit / 64-bit register vectors (not HIP's struct-based u32x4: these stay in VGPRs)
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kF16 = 0, kBF16 = 1;
 
 template <int DT>
-__device__ __forceinline__ floatx4_t mfma16x16x32(const uint4& a, const uint4& b, floatx4_t c) {
+__device__ __forceinline__ floatx4_t mfma16x16x32(const u32x4& a, const u32x4& b, floatx4_t c) {
   if constexpr (DT == kF16) {
     return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, a),
                                                   __builtin_bit_cast(half8_t, b), c, 0, 0, 0);
@@ -73,24 +78,28 @@ __device__ __forceinline__ floatx4_t mfma16x16x32(const uint4& a, const uint4& b
 }
 
 // Per (group, feature row) dequantisation constants, decoded from the 32-bit LDS entry.
-//   f16 : entry = (0x6400 | z) << 16 | scale_bits      -> s2 = (s, s), zc2 = (1024+z, 1024+z)
-//   bf16: entry = scale_bits << 16 | z                 -> s (fp32), nzs = -(128+z)*s (exact)
+//   f16 : entry = (0x6400 | z) << 16 | scale_bits   -> zc2 = (1024+z, 1024+z) as packed f16
+//   bf16: entry = scale_bits << 16 | z              -> zc = 128+z as fp32
+// The scale itself is applied in fp32 to the partial sum of each chunk-step (which never
+// straddles a quantisation group), so the MFMA consumes the exact integers q - z and the only
+// roundings on the contraction path are those of the fp32 accumulation.
 template <int DT>
 struct DeqCtx;
 template <>
 struct DeqCtx<kF16> {
-  half2_t s2, zc2;
+  half2_t zc2;
+  float s;
   __device__ __forceinline__ explicit DeqCtx(uint32_t e) {
-    s2 = __builtin_bit_cast(half2_t, (e & 0xffffu) * 0x10001u);
     zc2 = __builtin_bit_cast(half2_t, (e >> 16) * 0x10001u);
+    s = (float)__builtin_bit_cast(_Float16, (uint16_t)(e & 0xffffu));
   }
 };
 template <>
 struct DeqCtx<kBF16> {
-  float s, nzs;
+  float zc, s;
   __device__ __forceinline__ explicit DeqCtx(uint32_t e) {
     s = __builtin_bit_cast(float, e & 0xffff0000u);
-    nzs = -(128.0f + (float)(e & 0xffu)) * s;
+    zc = 128.0f + (float)(e & 0xffu);
   }
 };
 
@@ -100,19 +109,20 @@ __device__ __forceinline__ uint32_t pack_sz_entry(uint16_t scale_bits, uint8_t z
   else return ((uint32_t)scale_bits << 16) | (uint32_t)z;
 }
 
-// One packed word (8 nibbles) -> 8 dequantised 16-bit values in the order 0,4,1,5,2,6,3,7.
-// f16 : OR the nibble into the mantissa of 1024.0 (exact 1024+q), subtract 1024+z (exact
-//       integer q-z), multiply by the scale (one rounding).
-// bf16: OR into 128.0 (exact 128+q), widen to fp32 by shifting, fma with the scale and the
-//       exact -(128+z)*s (result (q-z)*s exact in fp32), round once to bf16.
+// One packed word (8 nibbles) -> the 8 exact integers q - z as 16-bit floats, in the order
+// 0,4,1,5,2,6,3,7.
+// f16 : OR the nibble pair into the mantissas of (1024.0, 1024.0) -> exact 1024+q, then one
+//       packed subtract of 1024+z.
+// bf16: OR into (128.0, 128.0) -> exact 128+q; widen each half to fp32 by shifting, subtract
+//       128+z, convert back (exact: |q-z| <= 15).
 template <int DT>
-__device__ __forceinline__ uint4 dequant_word(uint32_t w, const DeqCtx<DT>& c) {
+__device__ __forceinline__ u32x4 dequant_word(uint32_t w, const DeqCtx<DT>& c) {
   uint32_t r[4];
   if constexpr (DT == kF16) {
 #pragma unroll
     for (int p = 0; p < 4; ++p) {
       uint32_t t = ((w >> (4 * p)) & 0x000F000Fu) | 0x64006400u;
-      half2_t h = (__builtin_bit_cast(half2_t, t) - c.zc2) * c.s2;
+      half2_t h = __builtin_bit_cast(half2_t, t) - c.zc2;
       r[p] = __builtin_bit_cast(uint32_t, h);
     }
   } else {
@@ -121,11 +131,11 @@ __device__ __forceinline__ uint4 dequant_word(uint32_t w, const DeqCtx<DT>& c) {
       uint32_t t = ((w >> (4 * p)) & 0x000F000Fu) | 0x43004300u;
       float lo = __builtin_bit_cast(float, t << 16);
       float hi = __builtin_bit_cast(float, t & 0xffff0000u);
-      floatx2_t f = {__builtin_fmaf(lo, c.s, c.nzs), __builtin_fmaf(hi, c.s, c.nzs)};
+      floatx2_t f = {lo - c.zc, hi - c.zc};
       r[p] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2_t));
     }
   }
-  return make_uint4(r[0], r[1], r[2], r[3]);
+  return u32x4{r[0], r[1], r[2], r[3]};
 }
 
 template <int DT>
@@ -142,8 +152,8 @@ __device__ __forceinline__ float from_bits16(uint16_t b) {
 __device__ __forceinline__ float silu_f32(float x) { return x / (1.0f + __expf(-x)); }
 
 // 8 consecutive 16-bit elements x0..x7 -> order x0,x4,x1,x5,x2,x6,x3,x7
-__device__ __forceinline__ uint4 interleave8(const uint4& a) {
-  uint4 o;
+__device__ __forceinline__ u32x4 interleave8(const u32x4& a) {
+  u32x4 o;
   o.x = __builtin_amdgcn_perm(a.z, a.x, 0x05040100u);  // (x0, x4)
   o.y = __builtin_amdgcn_perm(a.z, a.x, 0x07060302u);  // (x1, x5)
   o.z = __builtin_amdgcn_perm(a.w, a.y, 0x05040100u);  // (x2, x6)
@@ -174,10 +184,10 @@ template <int KW>
 __device__ __forceinline__ WordVec<KW> lds_read_words(const unsigned char* p) {
   WordVec<KW> v;
   if constexpr (KW == 4) {
-    uint4 t = *reinterpret_cast<const uint4*>(p);
+    u32x4 t = *reinterpret_cast<const u32x4*>(p);
     v.w[0] = t.x; v.w[1] = t.y; v.w[2] = t.z; v.w[3] = t.w;
   } else if constexpr (KW == 2) {
-    uint2 t = *reinterpret_cast<const uint2*>(p);
+    u32x2 t = *reinterpret_cast<const u32x2*>(p);
     v.w[0] = t.x; v.w[1] = t.y;
   } else {
     v.w[0] = *reinterpret_cast<const uint32_t*>(p);
@@ -249,58 +259,68 @@ __global__ void __launch_bounds__(256) w4a16_gemm_kernel(const GemmParams p) {
   const int K_in = p.K_in, kwords = K_in >> 3;
 
   // ---- per-thread global pointers -------------------------------------------------
+  // Loads are never predicated: padding rows, feature rows past N_out and reduction chunks
+  // past K_in are redirected to a valid address.  What they fetch only ever reaches output
+  // rows / columns that are not stored, or chunk-steps that are not executed.
   const uint16_t* A16 = reinterpret_cast<const uint16_t*>(p.A);
   const uint16_t* xptr[XPASS];
-  bool xok[XPASS];
   const int xr_row = tid / CPR, xr_chunk = tid % CPR;
 #pragma unroll
   for (int ps = 0; ps < XPASS; ++ps) {
     const int slot = p.sorted_slot_ids[row0 + ps * RPP + xr_row];
-    xok[ps] = slot >= 0 && slot < p.num_slots;
-    const int arow = xok[ps] ? slot / p.row_div : 0;
-    xptr[ps] = A16 + (size_t)arow * K_in + xr_chunk * 8;
+    const int arow = (slot >= 0 && slot < p.num_slots) ? slot / p.row_div : 0;
+    xptr[ps] = A16 + (size_t)arow * K_in;
   }
   const uint32_t* qw = reinterpret_cast<const uint32_t*>(p.qweight);
   const uint32_t* wptr[WPASS];
-  bool wok[WPASS];
   const int wl_row = lane / LPR, wl_chunk = lane % LPR;
 #pragma unroll
   for (int q = 0; q < WPASS; ++q) {
     const int rw = q * RPI + wl_row;
     int wrow, ocol;
-    feature_of<NT, FUSE>(n_tile, wave, rw >> 4, rw & 15, p, wrow, ocol, wok[q]);
-    if (!wok[q]) wrow = 0;
-    wptr[q] = qw + ((size_t)e * p.N_out + wrow) * kwords + wl_chunk * 4;
+    bool ok;
+    feature_of<NT, FUSE>(n_tile, wave, rw >> 4, rw & 15, p, wrow, ocol, ok);
+    if (!ok) wrow = 0;
+    wptr[q] = qw + ((size_t)e * p.N_out + wrow) * kwords;
   }
 
-  uint4 xr[2][XPASS], wr[2][WPASS];
-  auto load_stage = [&](int st, uint4(&xv)[XPASS], uint4(&wv)[WPASS]) {
-    const int k0 = st * KS;
-#pragma unroll
-    for (int q = 0; q < WPASS; ++q) {
-      wv[q] = make_uint4(0, 0, 0, 0);
-      if (wok[q] && k0 + wl_chunk * 32 + 32 <= K_in)
-        wv[q] = *reinterpret_cast<const uint4*>(wptr[q] + (k0 >> 3));
-    }
-#pragma unroll
-    for (int ps = 0; ps < XPASS; ++ps) {
-      xv[ps] = make_uint4(0, 0, 0, 0);
-      if (xok[ps] && k0 + xr_chunk * 8 + 8 <= K_in)
-        xv[ps] = *reinterpret_cast<const uint4*>(xptr[ps] + k0);
-    }
-  };
-  auto store_stage = [&](const uint4(&xv)[XPASS], const uint4(&wv)[WPASS], unsigned char* xbuf) {
-#pragma unroll
-    for (int q = 0; q < WPASS; ++q)
-      *reinterpret_cast<uint4*>(wsw + (q * RPI + wl_row) * WP + wl_chunk * 16) = wv[q];
-#pragma unroll
-    for (int ps = 0; ps < XPASS; ++ps)
-      *reinterpret_cast<uint4*>(xbuf + (ps * RPP + xr_row) * XP + xr_chunk * 16) = interleave8(xv[ps]);
-  };
+  // Register prefetch ring, two stages deep.  Written as macros over separately named arrays
+  // so every index is a compile-time constant and the ring stays in VGPRs.
+  u32x4 xr0[XPASS], xr1[XPASS], wr0[WPASS], wr1[WPASS];
+#define MOE_LOAD_STAGE(ST, XV, WV)                                                              \
+  {                                                                                             \
+    /* A stage past the end still issues its loads (all lanes at one valid address) so the  */  \
+    /* loop body is branch-free and the compiler can count outstanding loads exactly.       */  \
+    const bool live_ = (ST) < nst;                                                              \
+    const int k0_ = (ST) * KS;                                                                  \
+    int wk_ = k0_ + wl_chunk * 32; /* first reduction index of this lane's 16 B of weights */   \
+    if (wk_ > K_in - 32) wk_ = K_in - 32;                                                       \
+    int xk_ = k0_ + xr_chunk * 8;                                                               \
+    if (xk_ > K_in - 8) xk_ = K_in - 8;                                                         \
+    _Pragma("unroll") for (int q = 0; q < WPASS; ++q) {                                         \
+      const uint32_t* src_ = live_ ? wptr[q] + (wk_ >> 3) : qw;                                 \
+      WV[q] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src_));                 \
+    }                                                                                           \
+    _Pragma("unroll") for (int ps = 0; ps < XPASS; ++ps) {                                      \
+      const uint16_t* src_ = live_ ? xptr[ps] + xk_ : A16;                                      \
+      XV[ps] = *reinterpret_cast<const u32x4*>(src_);                                           \
+    }                                                                                           \
+  }
+#define MOE_STORE_STAGE(XV, WV, XBUF)                                                           \
+  {                                                                                             \
+    _Pragma("unroll") for (int q = 0; q < WPASS; ++q) {                                         \
+      const u32x4 t_ = WV[q];                                                                   \
+      *reinterpret_cast<u32x4*>(wsw + (q * RPI + wl_row) * WP + wl_chunk * 16) =                \
+          t_;                                                                                   \
+    }                                                                                           \
+    _Pragma("unroll") for (int ps = 0; ps < XPASS; ++ps)                                        \
+        *reinterpret_cast<u32x4*>((XBUF) + (ps * RPP + xr_row) * XP + xr_chunk * 16) =          \
+            interleave8(XV[ps]);                                                                \
+  }
 
   const int nst = (K_in + KS - 1) / KS;
-  load_stage(0, xr[0], wr[0]);
-  if (nst > 1) load_stage(1, xr[1], wr[1]);
+  MOE_LOAD_STAGE(0, xr0, wr0)
+  MOE_LOAD_STAGE(1, xr1, wr1)
 
   // ---- stage scales / zero points of this tile's rows into LDS ---------------------
   if (tid < M_T) slot_s[tid] = p.sorted_slot_ids[row0 + tid];
@@ -314,24 +334,24 @@ __global__ void __launch_bounds__(256) w4a16_gemm_kernel(const GemmParams p) {
       feature_of<NT, FUSE>(n_tile, lf / NW, (lf % NW) >> 4, lf & 15, p, wrow, ocol, ok);
       uint16_t sv[8];
       uint8_t zv[8];
+      if (!ok) wrow = 0;      // fetched but never used: the row's outputs are not stored
+      const size_t rbase = ((size_t)e * p.N_out + wrow) * G;
+      if (p.sz_vec) {
+        const u32x4 s4 = *reinterpret_cast<const u32x4*>(sc + rbase + gb);
+        const u32x2 z2 = *reinterpret_cast<const u32x2*>(p.zeros + rbase + gb);
+        const uint32_t sw[4] = {s4.x, s4.y, s4.z, s4.w};
+        const uint32_t zw[2] = {z2.x, z2.y};
 #pragma unroll
-      for (int i = 0; i < 8; ++i) { sv[i] = 0; zv[i] = 0; }
-      if (ok) {
-        const size_t base = ((size_t)e * p.N_out + wrow) * G + gb;
-        if (p.sz_vec) {
-          const uint4 s4 = *reinterpret_cast<const uint4*>(sc + base);
-          const uint2 z2 = *reinterpret_cast<const uint2*>(p.zeros + base);
-          const uint32_t sw[4] = {s4.x, s4.y, s4.z, s4.w};
-          const uint32_t zw[2] = {z2.x, z2.y};
+        for (int i = 0; i < 8; ++i) {
+          sv[i] = (uint16_t)(sw[i >> 1] >> (16 * (i & 1)));
+          zv[i] = (uint8_t)(zw[i >> 2] >> (8 * (i & 3)));
+        }
+      } else {
 #pragma unroll
-          for (int i = 0; i < 8; ++i) {
-            sv[i] = (uint16_t)(sw[i >> 1] >> (16 * (i & 1)));
-            zv[i] = (uint8_t)(zw[i >> 2] >> (8 * (i & 3)));
-          }
-        } else {
-#pragma unroll
-          for (int i = 0; i < 8; ++i)
-            if (gb + i < G) { sv[i] = sc[base + i]; zv[i] = p.zeros[base + i]; }
+        for (int i = 0; i < 8; ++i) {
+          const int gi = gb + i < G ? gb + i : G - 1;
+          sv[i] = sc[rbase + gi];
+          zv[i] = p.zeros[rbase + gi];
         }
       }
 #pragma unroll
@@ -347,7 +367,7 @@ __global__ void __launch_bounds__(256) w4a16_gemm_kernel(const GemmParams p) {
     for (int s = 0; s < NT; ++s) acc[mt][s] = floatx4_t{0.f, 0.f, 0.f, 0.f};
 
   auto compute_stage = [&](int st, const unsigned char* xbuf) {
-    const int left = (K_in - st * KS) / CK;
+    const int left = (K_in - st * KS) / CK;      // <= 0 for a stage past the end
     const int nu = left < UCH ? left : UCH;
 #pragma unroll
     for (int u = 0; u < UCH; ++u) {
@@ -361,39 +381,50 @@ __global__ void __launch_bounds__(256) w4a16_gemm_kernel(const GemmParams p) {
         ent[s] = sz[gi * N_T + wave * NW + s * 16 + ln];
         wv[s] = lds_read_words<KW>(wsw + (s * 16 + ln) * WP + 16 * KW * u + 4 * KW * lj);
       }
+      floatx4_t part[MT][NT];
 #pragma unroll
       for (int i = 0; i < KW; ++i) {
-        uint4 b[NT];
+        u32x4 b[NT];
 #pragma unroll
         for (int s = 0; s < NT; ++s) b[s] = dequant_word<DT>(wv[s].w[i], DeqCtx<DT>(ent[s]));
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
-          const uint4 a = *reinterpret_cast<const uint4*>(
+          const u32x4 a = *reinterpret_cast<const u32x4*>(
               xbuf + (mt * 16 + ln) * XP + 2 * (CK * u + 8 * KW * lj + 8 * i));
 #pragma unroll
-          for (int s = 0; s < NT; ++s) acc[mt][s] = mfma16x16x32<DT>(a, b[s], acc[mt][s]);
+          for (int s = 0; s < NT; ++s)
+            part[mt][s] = mfma16x16x32<DT>(a, b[s], i == 0 ? floatx4_t{0.f, 0.f, 0.f, 0.f} : part[mt][s]);
         }
+      }
+#pragma unroll
+      for (int s = 0; s < NT; ++s) {
+        const float sc = DeqCtx<DT>(ent[s]).s;
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) acc[mt][s][i] = __builtin_fmaf(sc, part[mt][s][i], acc[mt][s][i]);
       }
     }
   };
 
-  store_stage(xr[0], wr[0], xs);
+  MOE_STORE_STAGE(xr0, wr0, xs)
   __syncthreads();
 
-  // Two stages per trip so the register prefetch buffers are indexed statically:
-  // while stage st is computed from LDS, stage st+1 sits in registers and st+2 is in flight.
+  // Two stages per trip so the register ring is indexed statically: while stage st is computed
+  // from LDS, stage st+1 sits in registers and the loads of stage st+2 are in flight.
+  unsigned char* const xs1 = xs + M_T * XP;
   for (int st = 0; st < nst; st += 2) {
-    if (st + 2 < nst) load_stage(st + 2, xr[0], wr[0]);
+    MOE_LOAD_STAGE(st + 2, xr0, wr0)
     compute_stage(st, xs);
-    if (st + 1 < nst) store_stage(xr[1], wr[1], xs + M_T * XP);
+    MOE_STORE_STAGE(xr1, wr1, xs1)
     __syncthreads();
-    if (st + 1 < nst) {
-      if (st + 3 < nst) load_stage(st + 3, xr[1], wr[1]);
-      compute_stage(st + 1, xs + M_T * XP);
-      if (st + 2 < nst) store_stage(xr[0], wr[0], xs);
-      __syncthreads();
-    }
+    MOE_LOAD_STAGE(st + 3, xr1, wr1)
+    compute_stage(st + 1, xs1);       // no chunk-steps left when st + 1 == nst
+    MOE_STORE_STAGE(xr0, wr0, xs)
+    __syncthreads();
   }
+#undef MOE_LOAD_STAGE
+#undef MOE_STORE_STAGE
 
   // ---- epilogue: one rounding to the 16-bit type, rows addressed by slot id ---------
   uint16_t* C16 = reinterpret_cast<uint16_t*>(p.C);
@@ -409,7 +440,10 @@ __global__ void __launch_bounds__(256) w4a16_gemm_kernel(const GemmParams p) {
         for (int s = 0; s < NT; ++s) {
           int wrow, ocol; bool ok;
           feature_of<NT, FUSE>(n_tile, wave, s, ln, p, wrow, ocol, ok);
-          if (ok) crow[ocol] = to_bits16<DT>(acc[mt][s][i]);
+          if (ok) {
+            if (p.out_f32) reinterpret_cast<float*>(p.C)[(size_t)slot * p.ldc + ocol] = acc[mt][s][i];
+            else crow[ocol] = to_bits16<DT>(acc[mt][s][i]);
+          }
         }
       } else {
 #pragma unroll

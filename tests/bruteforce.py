@@ -110,7 +110,7 @@ def layer(x_bits, ids, w, qw1, s1_bits, z1, qw2, s2_bits, z2, g, dt, rounded=Tru
             acc = Fraction(0)
             for n in range(N):
                 acc += act[s][n] * weight(qw2, s2_bits, z2, e, c, n, g, dt)
-            Y[s][c] = r(acc)
+            Y[s][c] = acc          # the layer combines the down projection unrounded
     for t in range(T):
         for c in range(K):
             acc = Fraction(0)

@@ -58,8 +58,8 @@ def test_workspace_covers_tables_and_intermediates(binding):
     T, K, N, E, topk = 128, 7168, 2048, 256, 8
     need = binding.moe_w4a16_layer_workspace_bytes(T, K, N, E, topk, 0)
     S = T * topk
-    assert need >= S * N * 2 + S * K * 2 + O.align_capacity(T, topk, E, 128) * 4
-    assert need < 2 * (S * N * 2 + S * K * 2) + (1 << 22)
+    assert need >= S * N * 2 + S * K * 4 + O.align_capacity(T, topk, E, 128) * 4
+    assert need < 2 * (S * N * 2 + S * K * 4) + (1 << 22)
     assert binding.moe_w4a16_layer_workspace_bytes(-1, K, N, E, topk, 0) == 0
 
 
