@@ -77,62 +77,101 @@ __device__ __forceinline__ floatx4_t mfma16x16x32(const u32x4& a, const u32x4& b
   }
 }
 
-// Per (group, feature row) dequantisation constants, decoded from the 32-bit LDS entry.
-//   f16 : entry = (0x6400 | z) << 16 | scale_bits   -> zc2 = (1024+z, 1024+z) as packed f16
-//   bf16: entry = scale_bits << 16 | z              -> zc = 128+z as fp32
-// The scale itself is applied in fp32 to the partial sum of each chunk-step (which never
-// straddles a quantisation group), so the MFMA consumes the exact integers q - z and the only
-// roundings on the contraction path are those of the fp32 accumulation.
-template <int DT>
+// ---- int4 -> 16-bit float, in registers ---------------------------------------------------
+// The MFMA never sees a rounded weight.  Two ways of removing the zero point, chosen by ZM:
+//
+//   ZM = 1 (small token tiles, VALU is the scarce resource): the B operand holds the BIASED
+//     integers bias + q, produced by one AND-OR per nibble pair; a second MFMA with the constant
+//     operand -(bias + z) subtracts bias and zero point inside the fp32 accumulation.
+//   ZM = 0 (large token tiles, MFMA is the scarce resource): one packed subtract per nibble
+//     pair yields the exact integers q - z.
+// Either way the group scale multiplies the fp32 partial sum of each chunk-step.
+//
+// fp16: nibbles 0/4 of a word are ORed into the mantissa of 1024.0 (ulp 1: value 1024 + q);
+//       nibbles 1/5 sit four bits higher and are ORed into the mantissa of 64.0 (ulp 1/16,
+//       value 64 + q), which saves the shift.  One shift by 8 brings nibbles 2/6 and 3/7 into
+//       the same two positions.  5 VALU ops per 8 weights.
+// bf16: 7 mantissa bits only: every pair is shifted down and ORed into 128.0 (value 128 + q).
+//
+// LDS entry per (group, feature row): fp16: hi = fp16 bits of 1024 + z (sign set when ZM),
+// lo = scale bits.  bf16: hi = scale bits, lo = z.
+// (a & mask) | orv in one VALU op.  v_and_or_b32 is a VOP3 instruction and on gfx9-class
+// encodings VOP3 takes no literal and only one scalar operand, so the compiler only selects it
+// when one of the two constants already lives in a VGPR.  The OR patterns are therefore handed
+// in as VGPR values made opaque once at kernel start (vgpr_const); the selection and all MFMA
+// hazard bookkeeping stay with the compiler (no inline asm near the MFMAs).
+__device__ __forceinline__ uint32_t vgpr_const(uint32_t v) {
+  uint32_t d;
+  asm volatile("v_mov_b32 %0, %1" : "=v"(d) : "s"(v));
+  return d;
+}
+struct UnpackConsts {
+  uint32_t or_hi;   // fp16: 0x64006400 (1024.0 pair)   bf16: 0x43004300 (128.0 pair)
+  uint32_t or_lo;   // fp16: 0x54005400 (64.0 pair)     bf16: unused
+};
+
+template <int DT, int ZM>
+__device__ __forceinline__ uint32_t pack_sz_entry(uint16_t scale_bits, uint8_t z) {
+  if constexpr (DT == kF16) return (((ZM ? 0xE400u : 0x6400u) | (uint32_t)z) << 16) | (uint32_t)scale_bits;
+  else return ((uint32_t)scale_bits << 16) | (uint32_t)z;
+}
+
+template <int DT, int ZM>
 struct DeqCtx;
-template <>
-struct DeqCtx<kF16> {
-  half2_t zc2;
+template <int ZM>
+struct DeqCtx<kF16, ZM> {
+  uint32_t zA, zB;   // packed pairs: (-)(1024 + z) and (-)(64 + z)
   float s;
   __device__ __forceinline__ explicit DeqCtx(uint32_t e) {
-    zc2 = __builtin_bit_cast(half2_t, (e >> 16) * 0x10001u);
+    zA = __builtin_amdgcn_perm(e, e, 0x07060706u);                       // (hi16, hi16)
+    zB = ((zA & 0x000F000Fu) << 4) | (ZM ? 0xD400D400u : 0x54005400u);   // z moved to mantissa bits 4..7
     s = (float)__builtin_bit_cast(_Float16, (uint16_t)(e & 0xffffu));
   }
+  // constant B operand of the zero-point MFMA (ZM only)
+  __device__ __forceinline__ u32x4 zoperand() const { return u32x4{zA, zB, zA, zB}; }
 };
-template <>
-struct DeqCtx<kBF16> {
+template <int ZM>
+struct DeqCtx<kBF16, ZM> {
+  uint32_t zA;       // ZM: packed pair -(128 + z) as bf16
   float zc, s;
   __device__ __forceinline__ explicit DeqCtx(uint32_t e) {
     s = __builtin_bit_cast(float, e & 0xffff0000u);
     zc = 128.0f + (float)(e & 0xffu);
+    zA = ((e & 0xffu) * 0x10001u) | 0xC300C300u;
   }
+  __device__ __forceinline__ u32x4 zoperand() const { return u32x4{zA, zA, zA, zA}; }
 };
 
-template <int DT>
-__device__ __forceinline__ uint32_t pack_sz_entry(uint16_t scale_bits, uint8_t z) {
-  if constexpr (DT == kF16) return ((0x6400u | (uint32_t)z) << 16) | (uint32_t)scale_bits;
-  else return ((uint32_t)scale_bits << 16) | (uint32_t)z;
-}
-
-// One packed word (8 nibbles) -> the 8 exact integers q - z as 16-bit floats, in the order
-// 0,4,1,5,2,6,3,7.
-// f16 : OR the nibble pair into the mantissas of (1024.0, 1024.0) -> exact 1024+q, then one
-//       packed subtract of 1024+z.
-// bf16: OR into (128.0, 128.0) -> exact 128+q; widen each half to fp32 by shifting, subtract
-//       128+z, convert back (exact: |q-z| <= 15).
-template <int DT>
-__device__ __forceinline__ u32x4 dequant_word(uint32_t w, const DeqCtx<DT>& c) {
+// One packed word (8 nibbles) -> 8 sixteen-bit floats in the order 0,4,1,5,2,6,3,7:
+// biased integers (ZM) or exact q - z (not ZM).
+template <int DT, int ZM>
+__device__ __forceinline__ u32x4 dequant_word(uint32_t w, const DeqCtx<DT, ZM>& c, const UnpackConsts& k) {
   uint32_t r[4];
   if constexpr (DT == kF16) {
-#pragma unroll
-    for (int p = 0; p < 4; ++p) {
-      uint32_t t = ((w >> (4 * p)) & 0x000F000Fu) | 0x64006400u;
-      half2_t h = __builtin_bit_cast(half2_t, t) - c.zc2;
-      r[p] = __builtin_bit_cast(uint32_t, h);
+    const uint32_t w8 = w >> 8;
+    r[0] = (w & 0x000F000Fu) | k.or_hi;
+    r[1] = (w & 0x00F000F0u) | k.or_lo;
+    r[2] = (w8 & 0x000F000Fu) | k.or_hi;
+    r[3] = (w8 & 0x00F000F0u) | k.or_lo;
+    if constexpr (!ZM) {
+      const half2_t zA = __builtin_bit_cast(half2_t, c.zA), zB = __builtin_bit_cast(half2_t, c.zB);
+      r[0] = __builtin_bit_cast(uint32_t, __builtin_bit_cast(half2_t, r[0]) - zA);
+      r[1] = __builtin_bit_cast(uint32_t, __builtin_bit_cast(half2_t, r[1]) - zB);
+      r[2] = __builtin_bit_cast(uint32_t, __builtin_bit_cast(half2_t, r[2]) - zA);
+      r[3] = __builtin_bit_cast(uint32_t, __builtin_bit_cast(half2_t, r[3]) - zB);
     }
   } else {
 #pragma unroll
     for (int p = 0; p < 4; ++p) {
-      uint32_t t = ((w >> (4 * p)) & 0x000F000Fu) | 0x43004300u;
-      float lo = __builtin_bit_cast(float, t << 16);
-      float hi = __builtin_bit_cast(float, t & 0xffff0000u);
-      floatx2_t f = {lo - c.zc, hi - c.zc};
-      r[p] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2_t));
+      const uint32_t t = ((w >> (4 * p)) & 0x000F000Fu) | k.or_hi;
+      if constexpr (ZM) {
+        r[p] = t;
+      } else {
+        const float lo = __builtin_bit_cast(float, t << 16);
+        const float hi = __builtin_bit_cast(float, t & 0xffff0000u);
+        floatx2_t f = {lo - c.zc, hi - c.zc};
+        r[p] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2_t));
+      }
     }
   }
   return u32x4{r[0], r[1], r[2], r[3]};
@@ -232,13 +271,14 @@ __device__ __forceinline__ void feature_of(int n_tile, int wave, int sub, int n,
 }
 
 template <int DT, int MT, int NT, int KS, int KW, int FUSE>
-__global__ void __launch_bounds__(256) w4a16_gemm_kernel(const GemmParams p) {
+__global__ void __launch_bounds__(256, (MT * NT <= 4 ? 2 : 1)) w4a16_gemm_kernel(const GemmParams p) {
   using G_ = TileGeom<MT, NT, KS>;
   constexpr int M_T = G_::M_T, NW = G_::NW, N_T = G_::N_T, XP = G_::XP, WP = G_::WP;
   constexpr int CPR = G_::CPR, RPP = G_::RPP, XPASS = G_::XPASS;
   constexpr int LPR = G_::LPR, RPI = G_::RPI, WPASS = G_::WPASS;
   constexpr int CK = 32 * KW, UCH = KS / CK;
   static_assert(FUSE == 0 || NT % 2 == 0, "fused SiLU needs gate/up sub-tile pairs");
+  constexpr int ZM = MT <= 2 ? 1 : 0;   // zero point through a second MFMA when MFMA time is plentiful
 
   extern __shared__ __align__(16) unsigned char smem[];
   unsigned char* xs = smem;                                        // [2][M_T][XP]
@@ -255,6 +295,9 @@ __global__ void __launch_bounds__(256) w4a16_gemm_kernel(const GemmParams p) {
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int ln = lane & 15, lj = lane >> 4;
+  UnpackConsts uk;
+  uk.or_hi = vgpr_const(DT == kF16 ? 0x64006400u : 0x43004300u);
+  uk.or_lo = vgpr_const(0x54005400u);
   unsigned char* wsw = ws_all + wave * NW * WP;
   const int K_in = p.K_in, kwords = K_in >> 3;
 
@@ -289,22 +332,18 @@ __global__ void __launch_bounds__(256) w4a16_gemm_kernel(const GemmParams p) {
   u32x4 xr0[XPASS], xr1[XPASS], wr0[WPASS], wr1[WPASS];
 #define MOE_LOAD_STAGE(ST, XV, WV)                                                              \
   {                                                                                             \
-    /* A stage past the end still issues its loads (all lanes at one valid address) so the  */  \
-    /* loop body is branch-free and the compiler can count outstanding loads exactly.       */  \
-    const bool live_ = (ST) < nst;                                                              \
+    /* A stage past the end still issues its loads (clamped onto the row's last chunk, which */ \
+    /* was just fetched) so the loop body is branch-free and the compiler can count the      */ \
+    /* outstanding loads exactly.                                                            */ \
     const int k0_ = (ST) * KS;                                                                  \
     int wk_ = k0_ + wl_chunk * 32; /* first reduction index of this lane's 16 B of weights */   \
     if (wk_ > K_in - 32) wk_ = K_in - 32;                                                       \
     int xk_ = k0_ + xr_chunk * 8;                                                               \
     if (xk_ > K_in - 8) xk_ = K_in - 8;                                                         \
-    _Pragma("unroll") for (int q = 0; q < WPASS; ++q) {                                         \
-      const uint32_t* src_ = live_ ? wptr[q] + (wk_ >> 3) : qw;                                 \
-      WV[q] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src_));                 \
-    }                                                                                           \
-    _Pragma("unroll") for (int ps = 0; ps < XPASS; ++ps) {                                      \
-      const uint16_t* src_ = live_ ? xptr[ps] + xk_ : A16;                                      \
-      XV[ps] = *reinterpret_cast<const u32x4*>(src_);                                           \
-    }                                                                                           \
+    _Pragma("unroll") for (int q = 0; q < WPASS; ++q)                                           \
+        WV[q] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(wptr[q] + (wk_ >> 3))); \
+    _Pragma("unroll") for (int ps = 0; ps < XPASS; ++ps)                                        \
+        XV[ps] = *reinterpret_cast<const u32x4*>(xptr[ps] + xk_);                               \
   }
 #define MOE_STORE_STAGE(XV, WV, XBUF)                                                           \
   {                                                                                             \
@@ -356,7 +395,7 @@ __global__ void __launch_bounds__(256) w4a16_gemm_kernel(const GemmParams p) {
       }
 #pragma unroll
       for (int i = 0; i < 8; ++i)
-        if (gb + i < G) sz[(gb + i) * N_T + lf] = pack_sz_entry<DT>(sv[i], zv[i]);
+        if (gb + i < G) sz[(gb + i) * N_T + lf] = pack_sz_entry<DT, ZM>(sv[i], zv[i]);
     }
   }
 
@@ -382,11 +421,19 @@ __global__ void __launch_bounds__(256) w4a16_gemm_kernel(const GemmParams p) {
         wv[s] = lds_read_words<KW>(wsw + (s * 16 + ln) * WP + 16 * KW * u + 4 * KW * lj);
       }
       floatx4_t part[MT][NT];
+      u32x4 zop[NT];
+      float scl[NT];
+#pragma unroll
+      for (int s = 0; s < NT; ++s) {
+        const DeqCtx<DT, ZM> c(ent[s]);
+        scl[s] = c.s;
+        if constexpr (ZM) zop[s] = c.zoperand();
+      }
 #pragma unroll
       for (int i = 0; i < KW; ++i) {
         u32x4 b[NT];
 #pragma unroll
-        for (int s = 0; s < NT; ++s) b[s] = dequant_word<DT>(wv[s].w[i], DeqCtx<DT>(ent[s]));
+        for (int s = 0; s < NT; ++s) b[s] = dequant_word<DT, ZM>(wv[s].w[i], DeqCtx<DT, ZM>(ent[s]), uk);
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
           const u32x4 a = *reinterpret_cast<const u32x4*>(
@@ -394,15 +441,18 @@ __global__ void __launch_bounds__(256) w4a16_gemm_kernel(const GemmParams p) {
 #pragma unroll
           for (int s = 0; s < NT; ++s)
             part[mt][s] = mfma16x16x32<DT>(a, b[s], i == 0 ? floatx4_t{0.f, 0.f, 0.f, 0.f} : part[mt][s]);
+          if constexpr (ZM) {
+#pragma unroll
+            for (int s = 0; s < NT; ++s) part[mt][s] = mfma16x16x32<DT>(a, zop[s], part[mt][s]);
+          }
         }
       }
 #pragma unroll
       for (int s = 0; s < NT; ++s) {
-        const float sc = DeqCtx<DT>(ent[s]).s;
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-          for (int i = 0; i < 4; ++i) acc[mt][s][i] = __builtin_fmaf(sc, part[mt][s][i], acc[mt][s][i]);
+          for (int i = 0; i < 4; ++i) acc[mt][s][i] = __builtin_fmaf(scl[s], part[mt][s][i], acc[mt][s][i]);
       }
     }
   };
