@@ -148,10 +148,16 @@ int moe_w4a16_layer(const void* X, const int32_t* topk_ids, const float* topk_we
  * heuristic; (0, 0) restores it.  Unsupported combinations make the GEMM
  * return MOE_UNSUPPORTED_SHAPE.  Thread-local.
  *
+ * moe_set_scale_path: where the grouped GEMM keeps scales / zero points: 0 = choose
+ * (registers when group_size == 128, the scale rows are 16-byte aligned and the token tile is
+ * small; an LDS table otherwise), 1 = always the LDS table, 2 = registers or
+ * MOE_UNSUPPORTED_SHAPE.  Thread-local.
+ *
  * moe_layer_block_m: the bucketing block size the layer picks for these sizes.
  */
 int moe_set_stage_events(void* const* events, int n);
 int moe_set_tile_override(int mt, int nt);
+int moe_set_scale_path(int mode);
 int moe_layer_block_m(int T, int E, int topk);
 
 #ifdef __cplusplus

@@ -16,7 +16,7 @@ _LIB: Optional[ctypes.CDLL] = None
 EXPORTS = [
     "moe_last_error", "moe_align_capacity", "moe_align_by_expert", "moe_w4a16_grouped_gemm",
     "moe_silu_mul", "moe_combine", "moe_w4a16_layer_workspace_bytes", "moe_w4a16_layer",
-    "moe_set_stage_events", "moe_set_tile_override", "moe_layer_block_m",
+    "moe_set_stage_events", "moe_set_tile_override", "moe_set_scale_path", "moe_layer_block_m",
 ]
 
 
@@ -61,6 +61,8 @@ def load_library() -> ctypes.CDLL:
     lib.moe_set_stage_events.argtypes = [ctypes.POINTER(vp), i32]
     lib.moe_set_tile_override.restype = i32
     lib.moe_set_tile_override.argtypes = [i32, i32]
+    lib.moe_set_scale_path.restype = i32
+    lib.moe_set_scale_path.argtypes = [i32]
     lib.moe_layer_block_m.restype = i32
     lib.moe_layer_block_m.argtypes = [i32, i32, i32]
     _LIB = lib
@@ -154,6 +156,10 @@ def moe_w4a16_layer(X, topk_ids, topk_weights, qw1, s1, z1, qw2, s2, z2, out, gr
 
 def moe_set_tile_override(mt: int, nt: int) -> None:
     _check(load_library().moe_set_tile_override(mt, nt))
+
+
+def moe_set_scale_path(mode: int) -> None:
+    _check(load_library().moe_set_scale_path(mode))
 
 
 def moe_set_stage_events(events) -> None:

@@ -17,27 +17,33 @@ int launch_combine(const void*, int, const float*, const int32_t*, int, void*, l
                    hipStream_t);
 
 // ---- table of compiled GEMM variants ------------------------------------------------------
-#define MOE_DECL(DT, MT, NT, KS, KW, F) \
-  extern template int launch_w4a16_gemm<DT, MT, NT, KS, KW, F>(const GemmParams&, int, hipStream_t);
+#define MOE_DECL(DT, MT, NT, KS, KW, F, Z) \
+  extern template int launch_w4a16_gemm<DT, MT, NT, KS, KW, F, Z>(const GemmParams&, int, hipStream_t);
 #define MOE_ALL_DT_KW(M, MT, NT, KS, F) \
-  M(0, MT, NT, KS, 1, F) M(0, MT, NT, KS, 2, F) M(0, MT, NT, KS, 4, F) \
-  M(1, MT, NT, KS, 1, F) M(1, MT, NT, KS, 2, F) M(1, MT, NT, KS, 4, F)
+  M(0, MT, NT, KS, 1, F, 0) M(0, MT, NT, KS, 2, F, 0) M(0, MT, NT, KS, 4, F, 0) \
+  M(1, MT, NT, KS, 1, F, 0) M(1, MT, NT, KS, 2, F, 0) M(1, MT, NT, KS, 4, F, 0)
 #define MOE_TILE(MT, NT, KS) MOE_ALL_DT_KW(MOE_DECL, MT, NT, KS, 0)
 #define MOE_TILE_FUSE(MT, NT, KS) MOE_ALL_DT_KW(MOE_DECL, MT, NT, KS, 1)
 #include "gemm_variants.def"
+#define MOE_TILE_SZR(MT, NT) MOE_DECL(0, MT, NT, 256, 4, 0, 1) MOE_DECL(1, MT, NT, 256, 4, 0, 1)
+#define MOE_TILE_SZR_FUSE(MT, NT) MOE_DECL(0, MT, NT, 256, 4, 1, 1) MOE_DECL(1, MT, NT, 256, 4, 1, 1)
+#include "gemm_variants_szr.def"
 
 typedef int (*GemmLaunchFn)(const GemmParams&, int, hipStream_t);
-struct GemmVariant { int dt, mt, nt, ks, kw, fuse; GemmLaunchFn fn; };
-#define MOE_ENTRY(DT, MT, NT, KS, KW, F) {DT, MT, NT, KS, KW, F, &launch_w4a16_gemm<DT, MT, NT, KS, KW, F>},
+struct GemmVariant { int dt, mt, nt, ks, kw, fuse, szr; GemmLaunchFn fn; };
+#define MOE_ENTRY(DT, MT, NT, KS, KW, F, Z) {DT, MT, NT, KS, KW, F, Z, &launch_w4a16_gemm<DT, MT, NT, KS, KW, F, Z>},
 static const GemmVariant kVariants[] = {
 #define MOE_TILE(MT, NT, KS) MOE_ALL_DT_KW(MOE_ENTRY, MT, NT, KS, 0)
 #define MOE_TILE_FUSE(MT, NT, KS) MOE_ALL_DT_KW(MOE_ENTRY, MT, NT, KS, 1)
 #include "gemm_variants.def"
+#define MOE_TILE_SZR(MT, NT) MOE_ENTRY(0, MT, NT, 256, 4, 0, 1) MOE_ENTRY(1, MT, NT, 256, 4, 0, 1)
+#define MOE_TILE_SZR_FUSE(MT, NT) MOE_ENTRY(0, MT, NT, 256, 4, 1, 1) MOE_ENTRY(1, MT, NT, 256, 4, 1, 1)
+#include "gemm_variants_szr.def"
 };
 
-static const GemmVariant* find_variant(int dt, int mt, int nt, int kw, int fuse) {
+static const GemmVariant* find_variant(int dt, int mt, int nt, int kw, int fuse, int szr) {
   for (const GemmVariant& v : kVariants)
-    if (v.dt == dt && v.mt == mt && v.nt == nt && v.kw == kw && v.fuse == fuse) return &v;
+    if (v.dt == dt && v.mt == mt && v.nt == nt && v.kw == kw && v.fuse == fuse && v.szr == szr) return &v;
   return nullptr;
 }
 
@@ -46,6 +52,7 @@ static thread_local char g_err[512] = "";
 static thread_local void* g_events[5] = {nullptr, nullptr, nullptr, nullptr, nullptr};
 static thread_local int g_nevents = 0;
 static thread_local int g_force_mt = 0, g_force_nt = 0;
+static thread_local int g_scale_path = 0;   // 0 auto, 1 LDS table, 2 registers
 
 static int fail(int status, const char* fmt, ...) {
   va_list ap;
@@ -67,15 +74,15 @@ static size_t align_capacity(long long S, int E, int block_m) {
 constexpr size_t kLdsLimit = 160 * 1024;
 constexpr int kMaxGroups = 512;
 
-static size_t gemm_lds_bytes(int mt, int nt, int ks, int G) {
+static size_t gemm_lds_bytes(int mt, int nt, int ks, int G, int szr) {
   const size_t M_T = 16 * mt, NW = 16 * nt;
-  return 2 * M_T * (ks * 2 + 16) + 4 * NW * (ks / 2 + 16) + (size_t)G * 64 * nt * 4 + M_T * 4;
+  return 2 * M_T * (ks * 2 + 16) + 4 * NW * (ks / 2 + 16) + (szr ? 0 : (size_t)G * 64 * nt * 4) + M_T * 4;
 }
 
 // Tile choice.  Tokens per tile follow the bucketing block; the feature width per workgroup is
 // as wide as LDS allows while still giving every CU a couple of workgroups (256 CUs).
-static int choose_tile(int num_slots, int E, int feat, int G, int block_m, int fuse, int& mt, int& nt,
-                       int& ks) {
+static int choose_tile(int num_slots, int E, int feat, int G, int block_m, int fuse, int szr_ok, int dt,
+                       int& mt, int& nt, int& ks, int& szr) {
   mt = block_m / 16;
   if (mt > 8) mt = 8;
   if (g_force_mt > 0) {
@@ -84,16 +91,25 @@ static int choose_tile(int num_slots, int E, int feat, int G, int block_m, int f
   }
   ks = mt >= 4 ? 128 : 256;
   const int min_nt = (fuse || mt >= 4) ? 2 : 1;
+  // register-resident scales when the shape allows it and such a variant is compiled
+  auto pick_szr = [&](int nt_) {
+    if (g_scale_path == 1 || !szr_ok) return 0;
+    return find_variant(dt, mt, nt_, 4, fuse, 1) ? 1 : 0;
+  };
   if (g_force_nt > 0) {
     nt = g_force_nt;
-    return (nt >= min_nt && (nt == 1 || nt == 2 || nt == 4) && gemm_lds_bytes(mt, nt, ks, G) <= kLdsLimit) ? 0 : -1;
+    szr = pick_szr(nt);
+    if (g_scale_path == 2 && !szr) return -1;
+    return (nt >= min_nt && (nt == 1 || nt == 2 || nt == 4) && gemm_lds_bytes(mt, nt, ks, G, szr) <= kLdsLimit) ? 0 : -1;
   }
   const long long est_blocks = (num_slots + 16 * mt - 1) / (16 * mt) + (num_slots < E ? num_slots : E) / 2;
   nt = mt >= 4 ? 4 : 2;
   for (;;) {
     const int fpw = fuse ? 32 * nt : 64 * nt;
     const long long wgs = est_blocks * ((feat + fpw - 1) / fpw);
-    const bool fits = gemm_lds_bytes(mt, nt, ks, G) <= kLdsLimit;
+    szr = pick_szr(nt);
+    if (g_scale_path == 2 && !szr) { if (nt == min_nt) return -1; nt >>= 1; continue; }
+    const bool fits = gemm_lds_bytes(mt, nt, ks, G, szr) <= kLdsLimit;
     if (fits && (wgs >= 512 || nt == min_nt)) return 0;
     if (nt == min_nt) return -1;
     nt >>= 1;
@@ -130,12 +146,14 @@ static int run_gemm(const GemmArgs& a, hipStream_t stream) {
   const int fuse = a.fuse_half_n > 0 ? 1 : 0;
   const int feat = fuse ? a.fuse_half_n : a.N_out;
   const int kw = a.group % 128 == 0 ? 4 : (a.group % 64 == 0 ? 2 : 1);
-  int mt, nt, ks;
-  if (choose_tile(a.num_slots, a.E, feat, G, a.block_m, fuse, mt, nt, ks) != 0)
+  int mt, nt, ks, szr;
+  const int sz_vec = (G % 8 == 0 && (uintptr_t)a.scales % 16 == 0 && (uintptr_t)a.zeros % 8 == 0) ? 1 : 0;
+  const int szr_ok = sz_vec && a.group == 128;
+  if (choose_tile(a.num_slots, a.E, feat, G, a.block_m, fuse, szr_ok, a.dt, mt, nt, ks, szr) != 0)
     return fail(MOE_UNSUPPORTED_SHAPE, "no GEMM tile fits (K_in/group_size = %d, block_m = %d, override %d/%d)",
                 G, a.block_m, g_force_mt, g_force_nt);
-  const GemmVariant* v = find_variant(a.dt, mt, nt, kw, fuse);
-  if (!v) return fail(MOE_UNSUPPORTED_SHAPE, "GEMM variant mt=%d nt=%d kw=%d fuse=%d is not compiled", mt, nt, kw, fuse);
+  const GemmVariant* v = find_variant(a.dt, mt, nt, kw, fuse, szr);
+  if (!v) return fail(MOE_UNSUPPORTED_SHAPE, "GEMM variant mt=%d nt=%d kw=%d fuse=%d szr=%d is not compiled", mt, nt, kw, fuse, szr);
 
   GemmParams p;
   p.A = a.A; p.row_div = a.row_div;
@@ -149,7 +167,7 @@ static int run_gemm(const GemmArgs& a, hipStream_t stream) {
   p.cpg = a.group / (32 * kw);
   p.half_n = a.fuse_half_n;
   p.out_f32 = a.out_f32;
-  p.sz_vec = (G % 8 == 0 && (uintptr_t)a.scales % 16 == 0 && (uintptr_t)a.zeros % 8 == 0) ? 1 : 0;
+  p.sz_vec = sz_vec;
   const size_t cap = align_capacity(a.num_slots, a.E, a.block_m);
   const long long grid = (long long)(cap / (16 * mt)) * p.n_tiles;
   if (grid > 0x7fffffffLL) return fail(MOE_UNSUPPORTED_SHAPE, "grid too large");
@@ -326,6 +344,12 @@ int moe_set_stage_events(void* const* events, int n) {
   if (n != 5) return fail(MOE_INVALID_ARGUMENT, "expected 5 events");
   for (int i = 0; i < 5; ++i) g_events[i] = events[i];
   g_nevents = 5;
+  return MOE_OK;
+}
+
+int moe_set_scale_path(int mode) {
+  if (mode < 0 || mode > 2) return fail(MOE_INVALID_ARGUMENT, "scale path mode must be 0, 1 or 2");
+  g_scale_path = mode;
   return MOE_OK;
 }
 

@@ -11,10 +11,10 @@
 
 namespace moe {
 
-template <int DT, int MT, int NT, int KS, int KW, int FUSE>
+template <int DT, int MT, int NT, int KS, int KW, int FUSE, int SZR>
 int launch_w4a16_gemm(const GemmParams& p, int grid, hipStream_t stream) {
-  auto kern = w4a16_gemm_kernel<DT, MT, NT, KS, KW, FUSE>;
-  const size_t lds = TileGeom<MT, NT, KS>::lds_bytes(p.G);
+  auto kern = w4a16_gemm_kernel<DT, MT, NT, KS, KW, FUSE, SZR>;
+  const size_t lds = TileGeom<MT, NT, KS>::lds_bytes(p.G, SZR);
   static size_t lds_allowed = 64 * 1024;   // raise the dynamic LDS limit once per size class
   if (lds > lds_allowed) {
     hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -27,9 +27,18 @@ int launch_w4a16_gemm(const GemmParams& p, int grid, hipStream_t stream) {
 }
 
 #define MOE_TILE(MT, NT, KS) \
-  template int launch_w4a16_gemm<MOE_DT, MT, NT, KS, MOE_KW, 0>(const GemmParams&, int, hipStream_t);
+  template int launch_w4a16_gemm<MOE_DT, MT, NT, KS, MOE_KW, 0, 0>(const GemmParams&, int, hipStream_t);
 #define MOE_TILE_FUSE(MT, NT, KS) \
-  template int launch_w4a16_gemm<MOE_DT, MT, NT, KS, MOE_KW, 1>(const GemmParams&, int, hipStream_t);
+  template int launch_w4a16_gemm<MOE_DT, MT, NT, KS, MOE_KW, 1, 0>(const GemmParams&, int, hipStream_t);
 #include "gemm_variants.def"
+
+// register-resident scale variants: group 128 only (KW == 4), small token tiles
+#if MOE_KW == 4
+#define MOE_TILE_SZR(MT, NT) \
+  template int launch_w4a16_gemm<MOE_DT, MT, NT, 256, 4, 0, 1>(const GemmParams&, int, hipStream_t);
+#define MOE_TILE_SZR_FUSE(MT, NT) \
+  template int launch_w4a16_gemm<MOE_DT, MT, NT, 256, 4, 1, 1>(const GemmParams&, int, hipStream_t);
+#include "gemm_variants_szr.def"
+#endif
 
 }  // namespace moe

@@ -32,6 +32,9 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+#include <utility>
+
 namespace moe {
 
 struct GemmParams {
@@ -203,10 +206,15 @@ __device__ __forceinline__ u32x4 interleave8(const u32x4& a) {
 // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2).  Map the hardware
 // block id to a logical tile index so that every XCD walks a contiguous range of tiles:
 // tiles that share an activation tile (same slot block, neighbouring feature tiles) or the
-// same expert's weights (neighbouring slot blocks) then meet in one L2.
-__device__ __forceinline__ int xcd_contiguous_index(int pid, int nwg) {
+// same expert's weights (neighbouring slot blocks) then meet in one L2.  `total` is the number
+// of tiles that really exist (known on the device only: it follows from num_padded); the
+// launch grid covers the worst case.  Returns -1 for a workgroup with nothing to do.  Every
+// XCD gets total/8 tiles (+1 for the first total%8), so unused block capacity does not idle
+// whole XCDs.
+__device__ __forceinline__ int xcd_contiguous_index(int pid, int total) {
   const int xcd = pid & 7, idx = pid >> 3;
-  const int per = nwg >> 3, rem = nwg & 7;
+  const int per = total >> 3, rem = total & 7;
+  if (idx >= per + (xcd < rem ? 1 : 0)) return -1;
   return xcd < rem ? xcd * (per + 1) + idx : rem * (per + 1) + (xcd - rem) * per + idx;
 }
 
@@ -248,8 +256,8 @@ struct TileGeom {
   static constexpr int RPI = 64 / LPR;       // weight rows per wave load instruction
   static constexpr int WPASS = NW / RPI;     // weight load instructions per stage per wave
   static_assert(XPASS >= 1 && WPASS >= 1, "tile too small for the load mapping");
-  static size_t lds_bytes(int G) {
-    return (size_t)2 * M_T * XP + (size_t)4 * NW * WP + (size_t)G * N_T * 4 + (size_t)M_T * 4;
+  static size_t lds_bytes(int G, int szr) {
+    return (size_t)2 * M_T * XP + (size_t)4 * NW * WP + (szr ? 0 : (size_t)G * N_T * 4) + (size_t)M_T * 4;
   }
 };
 
@@ -270,8 +278,15 @@ __device__ __forceinline__ void feature_of(int n_tile, int wave, int sub, int n,
   }
 }
 
-template <int DT, int MT, int NT, int KS, int KW, int FUSE>
+// SZR = 1: scales and zero points are not staged in LDS; every lane fetches the 8 groups of
+// the current 1024-k panel of its own feature rows straight into registers (one 16-byte and
+// one 8-byte load per sub-tile and panel, prefetched one panel ahead).  Needs group == 128
+// (one group per chunk-step, KW == 4, KS == 256) and 16-byte aligned scale rows (G % 8 == 0).
+// It frees the largest LDS consumer of the bandwidth-bound shapes, which is what bounds the
+// number of resident workgroups per CU there.
+template <int DT, int MT, int NT, int KS, int KW, int FUSE, int SZR>
 __global__ void __launch_bounds__(256, (MT * NT <= 4 ? 2 : 1)) w4a16_gemm_kernel(const GemmParams p) {
+  static_assert(SZR == 0 || (KW == 4 && KS == 256), "register-resident scales need 128-k chunk-steps");
   using G_ = TileGeom<MT, NT, KS>;
   constexpr int M_T = G_::M_T, NW = G_::NW, N_T = G_::N_T, XP = G_::XP, WP = G_::WP;
   constexpr int CPR = G_::CPR, RPP = G_::RPP, XPASS = G_::XPASS;
@@ -283,13 +298,13 @@ __global__ void __launch_bounds__(256, (MT * NT <= 4 ? 2 : 1)) w4a16_gemm_kernel
   extern __shared__ __align__(16) unsigned char smem[];
   unsigned char* xs = smem;                                        // [2][M_T][XP]
   unsigned char* ws_all = xs + 2 * M_T * XP;                       // [4][NW][WP]
-  uint32_t* sz = reinterpret_cast<uint32_t*>(ws_all + 4 * NW * WP);  // [G][N_T]
-  int* slot_s = reinterpret_cast<int*>(sz + p.G * N_T);            // [M_T]
+  uint32_t* sz = reinterpret_cast<uint32_t*>(ws_all + 4 * NW * WP);  // [G][N_T] (absent when SZR)
+  int* slot_s = reinterpret_cast<int*>(sz + (SZR ? 0 : p.G * N_T));  // [M_T]
 
-  const int L = xcd_contiguous_index(blockIdx.x, gridDim.x);
+  const int L = xcd_contiguous_index(blockIdx.x, (*p.num_padded / M_T) * p.n_tiles);
+  if (L < 0) return;
   const int n_tile = L % p.n_tiles;
   const int row0 = (L / p.n_tiles) * M_T;
-  if (row0 >= *p.num_padded) return;
   const int e = p.block_expert_ids[row0 / p.block_m];
   if (e < 0 || e >= p.E) return;
 
@@ -327,9 +342,13 @@ __global__ void __launch_bounds__(256, (MT * NT <= 4 ? 2 : 1)) w4a16_gemm_kernel
     wptr[q] = qw + ((size_t)e * p.N_out + wrow) * kwords;
   }
 
-  // Register prefetch ring, two stages deep.  Written as macros over separately named arrays
-  // so every index is a compile-time constant and the ring stays in VGPRs.
-  u32x4 xr0[XPASS], xr1[XPASS], wr0[WPASS], wr1[WPASS];
+  // Register prefetch ring: PD slots, loads issued PD stages ahead (all indices are compile-time
+  // constants after unrolling, so the ring stays in VGPRs).  Deeper rings were measured slower
+  // on the decode shapes: the K loops are short and the extra dead steps at the end cost more
+  // than the additional bytes in flight gain.
+  constexpr int PD = 2;
+  constexpr int UNR = SZR ? 4 : PD;      // steps per loop trip (one 1024-k scale panel when SZR)
+  u32x4 xr[PD][XPASS], wr[PD][WPASS];
 #define MOE_LOAD_STAGE(ST, XV, WV)                                                              \
   {                                                                                             \
     /* A stage past the end still issues its loads (clamped onto the row's last chunk, which */ \
@@ -358,12 +377,30 @@ __global__ void __launch_bounds__(256, (MT * NT <= 4 ? 2 : 1)) w4a16_gemm_kernel
   }
 
   const int nst = (K_in + KS - 1) / KS;
-  MOE_LOAD_STAGE(0, xr0, wr0)
-  MOE_LOAD_STAGE(1, xr1, wr1)
+#pragma unroll
+  for (int r = 0; r < PD; ++r) MOE_LOAD_STAGE(r, xr[r], wr[r])
+
+  // ---- register-resident scales / zero points (SZR) -----------------------------------
+  // scur/snext: 8 fp16 scales and 8 zero-point bytes of the current / next panel, per sub-tile.
+  u32x4 s_cur[NT], s_nxt[NT];
+  u32x2 z_cur[NT], z_nxt[NT];
+  size_t sz_row[NT];
+  if constexpr (SZR) {
+#pragma unroll
+    for (int s = 0; s < NT; ++s) {
+      int wrow, ocol;
+      bool ok;
+      feature_of<NT, FUSE>(n_tile, wave, s, ln, p, wrow, ocol, ok);
+      if (!ok) wrow = 0;
+      sz_row[s] = ((size_t)e * p.N_out + wrow) * p.G;
+      s_cur[s] = *reinterpret_cast<const u32x4*>(reinterpret_cast<const uint16_t*>(p.scales) + sz_row[s]);
+      z_cur[s] = *reinterpret_cast<const u32x2*>(p.zeros + sz_row[s]);
+    }
+  }
 
   // ---- stage scales / zero points of this tile's rows into LDS ---------------------
   if (tid < M_T) slot_s[tid] = p.sorted_slot_ids[row0 + tid];
-  {
+  if constexpr (!SZR) {
     const uint16_t* sc = reinterpret_cast<const uint16_t*>(p.scales);
     const int G = p.G, G8 = (G + 7) >> 3;
     for (int idx = tid; idx < N_T * G8; idx += 256) {
@@ -405,7 +442,8 @@ __global__ void __launch_bounds__(256, (MT * NT <= 4 ? 2 : 1)) w4a16_gemm_kernel
 #pragma unroll
     for (int s = 0; s < NT; ++s) acc[mt][s] = floatx4_t{0.f, 0.f, 0.f, 0.f};
 
-  auto compute_stage = [&](int st, const unsigned char* xbuf) {
+  auto compute_stage = [&](int st, const unsigned char* xbuf, auto rc) {
+    constexpr int R = decltype(rc)::value;       // step index inside the unrolled trip
     const int left = (K_in - st * KS) / CK;      // <= 0 for a stage past the end
     const int nu = left < UCH ? left : UCH;
 #pragma unroll
@@ -417,7 +455,14 @@ __global__ void __launch_bounds__(256, (MT * NT <= 4 ? 2 : 1)) w4a16_gemm_kernel
       uint32_t ent[NT];
 #pragma unroll
       for (int s = 0; s < NT; ++s) {
-        ent[s] = sz[gi * N_T + wave * NW + s * 16 + ln];
+        if constexpr (SZR) {
+          const int gp = (2 * R + u) & 7;   // group inside the panel: constant after unrolling
+          const uint32_t sbits = (s_cur[s][gp >> 1] >> (16 * (gp & 1))) & 0xffffu;
+          const uint32_t zb = (z_cur[s][gp >> 2] >> (8 * (gp & 3))) & 0xffu;
+          ent[s] = pack_sz_entry<DT, ZM>((uint16_t)sbits, (uint8_t)zb);
+        } else {
+          ent[s] = sz[gi * N_T + wave * NW + s * 16 + ln];
+        }
         wv[s] = lds_read_words<KW>(wsw + (s * 16 + ln) * WP + 16 * KW * u + 4 * KW * lj);
       }
       floatx4_t part[MT][NT];
@@ -457,21 +502,39 @@ __global__ void __launch_bounds__(256, (MT * NT <= 4 ? 2 : 1)) w4a16_gemm_kernel
     }
   };
 
-  MOE_STORE_STAGE(xr0, wr0, xs)
+  MOE_STORE_STAGE(xr[0], wr[0], xs)
   __syncthreads();
 
-  // Two stages per trip so the register ring is indexed statically: while stage st is computed
-  // from LDS, stage st+1 sits in registers and the loads of stage st+2 are in flight.
-  unsigned char* const xs1 = xs + M_T * XP;
-  for (int st = 0; st < nst; st += 2) {
-    MOE_LOAD_STAGE(st + 2, xr0, wr0)
-    compute_stage(st, xs);
-    MOE_STORE_STAGE(xr1, wr1, xs1)
-    __syncthreads();
-    MOE_LOAD_STAGE(st + 3, xr1, wr1)
-    compute_stage(st + 1, xs1);       // no chunk-steps left when st + 1 == nst
-    MOE_STORE_STAGE(xr0, wr0, xs)
-    __syncthreads();
+  // Step st: issue the loads of stage st+PD into the ring slot that held stage st (it went to
+  // LDS in the previous step), compute stage st from LDS, move stage st+1 from its ring slot
+  // into LDS, barrier.  UNR steps per trip so ring slots, activation buffers and (SZR) the
+  // scale registers are indexed statically.  Steps past the last stage compute nothing (their
+  // loads are clamped onto valid addresses, their LDS stores are never read).
+  for (int st0 = 0; st0 < nst; st0 += UNR) {
+    if constexpr (SZR) {
+      // prefetch the next panel's scales / zero points (clamped onto the last panel)
+      int g0 = (st0 >> 2) * 8 + 8;
+      if (g0 > p.G - 8) g0 = p.G - 8;
+#pragma unroll
+      for (int s = 0; s < NT; ++s) {
+        s_nxt[s] = *reinterpret_cast<const u32x4*>(reinterpret_cast<const uint16_t*>(p.scales) + sz_row[s] + g0);
+        z_nxt[s] = *reinterpret_cast<const u32x2*>(p.zeros + sz_row[s] + g0);
+      }
+    }
+    [&]<int... Rs>(std::integer_sequence<int, Rs...>) {
+      (([&] {
+         constexpr int r = Rs;
+         MOE_LOAD_STAGE(st0 + r + PD, xr[r % PD], wr[r % PD])
+         compute_stage(st0 + r, xs + (r % 2) * (M_T * XP), std::integral_constant<int, r>{});
+         MOE_STORE_STAGE(xr[(r + 1) % PD], wr[(r + 1) % PD], xs + ((r + 1) % 2) * (M_T * XP))
+         __syncthreads();
+       }()),
+       ...);
+    }(std::make_integer_sequence<int, UNR>{});
+    if constexpr (SZR) {
+#pragma unroll
+      for (int s = 0; s < NT; ++s) { s_cur[s] = s_nxt[s]; z_cur[s] = z_nxt[s]; }
+    }
   }
 #undef MOE_LOAD_STAGE
 #undef MOE_STORE_STAGE
@@ -513,7 +576,7 @@ __global__ void __launch_bounds__(256, (MT * NT <= 4 ? 2 : 1)) w4a16_gemm_kernel
 }
 
 // Host-side launcher, one per instantiation.  Returns hipError_t as int.
-template <int DT, int MT, int NT, int KS, int KW, int FUSE>
+template <int DT, int MT, int NT, int KS, int KW, int FUSE, int SZR>
 int launch_w4a16_gemm(const GemmParams& p, int grid, hipStream_t stream);
 
 }  // namespace moe

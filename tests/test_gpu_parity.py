@@ -133,6 +133,34 @@ def test_every_gemm_tile_variant(tile, dtype, group):
     staged_gemm_case(cfg, 128, "w1", tile=tile)
 
 
+@pytest.mark.parametrize("tile", [(1, 1), (1, 2), (1, 4), (2, 1), (2, 2)])
+@pytest.mark.parametrize("dtype,K", [("f16", 1024), ("bf16", 3072)])
+@pytest.mark.parametrize("which", ["w1", "w2"])
+def test_register_resident_scale_variants(tile, dtype, K, which):
+    """group 128 with 16-byte aligned scale rows: scales / zero points live in registers."""
+    cfg = MoEConfig(name="szr", T=90, K=K, N=1024, E=4, topk=2, group=128, dtype=dtype, seed=12)
+    say(f"gemm register-scale variant tile={tile} dtype={dtype} K={K} {which}")
+    M.moe_set_scale_path(2)
+    try:
+        staged_gemm_case(cfg, 32, which, tile=tile)
+    finally:
+        M.moe_set_scale_path(0)
+
+
+def test_scale_paths_agree_bitwise():
+    cfg = MoEConfig(name="szr_eq", T=64, K=2048, N=1024, E=6, topk=2, group=128, dtype="f16", seed=13)
+    say("layer with LDS-table scales vs register scales")
+    d = U.DevInputs(make_inputs(cfg))
+    outs = []
+    for mode in (1, 2):
+        M.moe_set_scale_path(mode)
+        try:
+            outs.append(U.dev_to_f64(U.run_layer(d)))
+        finally:
+            M.moe_set_scale_path(0)
+    assert np.array_equal(outs[0], outs[1])
+
+
 def test_grouped_gemm_ignores_invalid_slots_and_leaves_rows_untouched():
     cfg = MoEConfig(name="inv", T=30, K=256, N=128, E=4, topk=2, group=128, dtype="f16", seed=6)
     say("gemm with out-of-range expert ids")
