@@ -44,10 +44,13 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", default="deepseek_decode")
     ap.add_argument("--tile", default="", help="mt,nt override of the GEMM tile (tuning)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="run 5 plain 1 GiB device-to-device copies and exit (known-size traffic "
+                         "for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE readings)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); use --gpus 1",
@@ -61,6 +64,15 @@ def main():
     cfg = CONFIGS[args.config]
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+    if args.copy_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")      # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration": {"bytes_read": src.numel() * 4, "bytes_written": src.numel() * 4,
+                                               "copies": 5}}))
+        return
     t0 = time.time()
     inp = make_inputs(cfg)
     print(f"[bench] generated {cfg.name} in {time.time() - t0:.1f}s", file=sys.stderr, flush=True)
@@ -154,36 +166,44 @@ def main():
     print(json.dumps(result), flush=True)
 
 
-def cpu_baseline(cfg, inp):
-    """The CPU oracle as it stands, on a bounded sample: token 0 with as many of its routed
-    experts as keep the run to roughly 10-30 s; throughput in the metric's unit (algorithmic
-    weight bytes of the experts it touched per second)."""
+def cpu_baseline(cfg, inp, target_s=15.0, cap_s=30.0):
+    """The CPU oracle as it stands, timed on a bounded sample of the same workload: the first
+    tokens of the batch with their routed experts, as many as fit in roughly target_s seconds
+    (sized from a one-slot probe).  Throughput is in the metric's unit: algorithmic weight bytes
+    of the expert evaluations the oracle performed per second."""
     from oracle import moe_oracle as O
     try:
         from threadpoolctl import threadpool_info
         threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
         threads = os.cpu_count() or 1
-    per_expert = 3.0 * cfg.K * cfg.N            # weights unpacked per expert (W1 + W2)
-    n_exp = int(max(1, min(cfg.topk, 1.2e8 // per_expert if per_expert < 1.2e8 else 1)))
-    n_tok = 1
-    if per_expert * cfg.topk < 3e7:             # small experts: take more tokens
-        n_tok = int(min(cfg.T, max(1, 1.2e8 // (per_expert * cfg.topk))))
-        n_exp = cfg.topk
-    ids = inp.topk_ids[:n_tok].copy()
-    ids[:, n_exp:] = -1                          # ignored slots: not computed
-    X = O.decode_bits(inp.x_bits[:n_tok], cfg.dtype)
     s1 = O.decode_bits(inp.s1_bits, cfg.dtype)
     s2 = O.decode_bits(inp.s2_bits, cfg.dtype)
-    t0 = time.perf_counter()
-    O.layer(X, ids, inp.topk_weights[:n_tok], inp.qw1, s1, inp.z1, inp.qw2, s2, inp.z2, cfg.group, cfg.dtype)
-    dt = time.perf_counter() - t0
-    touched = int(np.unique(ids[ids >= 0]).size)
+
+    def run(n_slots):
+        """Oracle layer on the first n_slots routed slots (token-major); returns seconds."""
+        n_tok = -(-n_slots // cfg.topk)
+        ids = inp.topk_ids[:n_tok].copy()
+        flat = ids.reshape(-1)
+        flat[n_slots:] = -1                         # ignored slots are not computed
+        X = O.decode_bits(inp.x_bits[:n_tok], cfg.dtype)
+        t0 = time.perf_counter()
+        O.layer(X, ids, inp.topk_weights[:n_tok], inp.qw1, s1, inp.z1, inp.qw2, s2, inp.z2, cfg.group, cfg.dtype)
+        return time.perf_counter() - t0, n_tok
+
+    probe, _ = run(1)
+    n_slots = int(max(1, min(cfg.S, target_s / max(probe, 1e-4))))
+    if probe * n_slots > cap_s:
+        n_slots = max(1, int(cap_s / probe))
+    dt, n_tok = run(n_slots)
     g = cfg.group
-    wbytes = touched * (1.5 * cfg.K * cfg.N + 3 * cfg.K * cfg.N // g * 3)
-    return {"value": round(wbytes / dt / 1e9, 4), "unit": "GB/s", "cores": int(threads), "kind": "oracle",
-            "seconds": round(dt, 2),
-            "sample": f"{n_tok} token(s) x {n_exp} routed expert(s) of {cfg.name} ({touched} experts touched), "
+    per_expert = 1.5 * cfg.K * cfg.N + 3 * cfg.K * cfg.N // g * 3
+    # the oracle dequantises an expert once per call and applies it to all its sampled slots
+    ids = inp.topk_ids[:n_tok].reshape(-1)[:n_slots]
+    touched = int(np.unique(ids[(ids >= 0) & (ids < cfg.E)]).size)
+    return {"value": round(touched * per_expert / dt / 1e9, 4), "unit": "GB/s", "cores": int(threads),
+            "kind": "oracle", "seconds": round(dt, 2),
+            "sample": f"first {n_slots} routed slots ({n_tok} tokens, {touched} distinct experts) of {cfg.name}, "
                       f"NumPy fp64 oracle, whole-layer definition"}
 
 
