@@ -25,8 +25,8 @@ int launch_combine(const void*, int, const float*, const int32_t*, int, void*, l
 #define MOE_TILE(MT, NT, KS) MOE_ALL_DT_KW(MOE_DECL, MT, NT, KS, 0)
 #define MOE_TILE_FUSE(MT, NT, KS) MOE_ALL_DT_KW(MOE_DECL, MT, NT, KS, 1)
 #include "gemm_variants.def"
-#define MOE_TILE_SZR(MT, NT) MOE_DECL(0, MT, NT, 256, 4, 0, 1) MOE_DECL(1, MT, NT, 256, 4, 0, 1)
-#define MOE_TILE_SZR_FUSE(MT, NT) MOE_DECL(0, MT, NT, 256, 4, 1, 1) MOE_DECL(1, MT, NT, 256, 4, 1, 1)
+#define MOE_TILE_SZR(MT, NT, KS) MOE_DECL(0, MT, NT, KS, 4, 0, 1) MOE_DECL(1, MT, NT, KS, 4, 0, 1)
+#define MOE_TILE_SZR_FUSE(MT, NT, KS) MOE_DECL(0, MT, NT, KS, 4, 1, 1) MOE_DECL(1, MT, NT, KS, 4, 1, 1)
 #include "gemm_variants_szr.def"
 
 typedef int (*GemmLaunchFn)(const GemmParams&, int, hipStream_t);
@@ -36,8 +36,8 @@ static const GemmVariant kVariants[] = {
 #define MOE_TILE(MT, NT, KS) MOE_ALL_DT_KW(MOE_ENTRY, MT, NT, KS, 0)
 #define MOE_TILE_FUSE(MT, NT, KS) MOE_ALL_DT_KW(MOE_ENTRY, MT, NT, KS, 1)
 #include "gemm_variants.def"
-#define MOE_TILE_SZR(MT, NT) MOE_ENTRY(0, MT, NT, 256, 4, 0, 1) MOE_ENTRY(1, MT, NT, 256, 4, 0, 1)
-#define MOE_TILE_SZR_FUSE(MT, NT) MOE_ENTRY(0, MT, NT, 256, 4, 1, 1) MOE_ENTRY(1, MT, NT, 256, 4, 1, 1)
+#define MOE_TILE_SZR(MT, NT, KS) MOE_ENTRY(0, MT, NT, KS, 4, 0, 1) MOE_ENTRY(1, MT, NT, KS, 4, 0, 1)
+#define MOE_TILE_SZR_FUSE(MT, NT, KS) MOE_ENTRY(0, MT, NT, KS, 4, 1, 1) MOE_ENTRY(1, MT, NT, KS, 4, 1, 1)
 #include "gemm_variants_szr.def"
 };
 
@@ -143,12 +143,17 @@ static int run_gemm(const GemmArgs& a, hipStream_t stream) {
   if (((uintptr_t)a.C | (uintptr_t)a.scales) % 2 != 0)
     return fail(MOE_INVALID_ARGUMENT, "C and scales must be 2-byte aligned");
 
+  // kernels address with 32-bit per-lane byte offsets from a per-expert / per-matrix base
+  if ((long long)a.N_out * (a.K_in / 2) >= (1LL << 31))
+    return fail(MOE_UNSUPPORTED_SHAPE, "one expert's packed weights must stay below 2 GiB");
+  if (((long long)(a.num_slots + a.row_div - 1) / a.row_div) * a.K_in * 2 >= (1LL << 31))
+    return fail(MOE_UNSUPPORTED_SHAPE, "the A matrix must stay below 2 GiB");
   const int fuse = a.fuse_half_n > 0 ? 1 : 0;
   const int feat = fuse ? a.fuse_half_n : a.N_out;
   const int kw = a.group % 128 == 0 ? 4 : (a.group % 64 == 0 ? 2 : 1);
   int mt, nt, ks, szr;
   const int sz_vec = (G % 8 == 0 && (uintptr_t)a.scales % 16 == 0 && (uintptr_t)a.zeros % 8 == 0) ? 1 : 0;
-  const int szr_ok = sz_vec && a.group == 128;
+  const int szr_ok = sz_vec && a.group == 128 && (long long)a.E * a.N_out * G < (1LL << 31);
   if (choose_tile(a.num_slots, a.E, feat, G, a.block_m, fuse, szr_ok, a.dt, mt, nt, ks, szr) != 0)
     return fail(MOE_UNSUPPORTED_SHAPE, "no GEMM tile fits (K_in/group_size = %d, block_m = %d, override %d/%d)",
                 G, a.block_m, g_force_mt, g_force_nt);
@@ -180,8 +185,7 @@ static int pick_block_m(long long S, int E) {
   const long long avg = S / (E > 0 ? E : 1);
   if (avg <= 8) return 16;
   if (avg <= 24) return 32;
-  if (avg <= 64) return 64;
-  return 128;
+  return 64;     // 64-slot tiles at two workgroups per CU beat 128-slot tiles (measured)
 }
 
 struct Workspace {
@@ -312,7 +316,9 @@ int moe_w4a16_layer(const void* X, const int32_t* topk_ids, const float* topk_we
   int32_t* blocks = (int32_t*)(base + w.blocks);
   void* act = base + w.act;
   void* Y = base + w.Y;
-  const int block_m = pick_block_m(S, E);
+  // a forced token tile (tuning hook) also fixes the bucketing block
+  const int block_m = (g_force_mt == 1 || g_force_mt == 2 || g_force_mt == 4 || g_force_mt == 8)
+                          ? 16 * g_force_mt : pick_block_m(S, E);
   const bool ev = g_nevents == 5;
 
   if (ev) (void)hipEventRecord((hipEvent_t)g_events[0], stream);

@@ -34,10 +34,10 @@ int launch_w4a16_gemm(const GemmParams& p, int grid, hipStream_t stream) {
 
 // register-resident scale variants: group 128 only (KW == 4), small token tiles
 #if MOE_KW == 4
-#define MOE_TILE_SZR(MT, NT) \
-  template int launch_w4a16_gemm<MOE_DT, MT, NT, 256, 4, 0, 1>(const GemmParams&, int, hipStream_t);
-#define MOE_TILE_SZR_FUSE(MT, NT) \
-  template int launch_w4a16_gemm<MOE_DT, MT, NT, 256, 4, 1, 1>(const GemmParams&, int, hipStream_t);
+#define MOE_TILE_SZR(MT, NT, KS) \
+  template int launch_w4a16_gemm<MOE_DT, MT, NT, KS, 4, 0, 1>(const GemmParams&, int, hipStream_t);
+#define MOE_TILE_SZR_FUSE(MT, NT, KS) \
+  template int launch_w4a16_gemm<MOE_DT, MT, NT, KS, 4, 1, 1>(const GemmParams&, int, hipStream_t);
 #include "gemm_variants_szr.def"
 #endif
 

@@ -218,6 +218,15 @@ __device__ __forceinline__ int xcd_contiguous_index(int pid, int total) {
   return xcd < rem ? xcd * (per + 1) + idx : rem * (per + 1) + (xcd - rem) * per + idx;
 }
 
+// Packed weights: streamed once per launch in the small-token regime (non-temporal, so they
+// do not displace the activation tiles in L2); with large token tiles the same expert rows are
+// read again by the neighbouring slot blocks and should stay cached.
+template <bool STREAM>
+__device__ __forceinline__ u32x4 load_weights(const unsigned char* p) {
+  if constexpr (STREAM) return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+  else return *reinterpret_cast<const u32x4*>(p);
+}
+
 template <int KW>
 struct WordVec;
 template <>
@@ -278,15 +287,16 @@ __device__ __forceinline__ void feature_of(int n_tile, int wave, int sub, int n,
   }
 }
 
-// SZR = 1: scales and zero points are not staged in LDS; every lane fetches the 8 groups of
-// the current 1024-k panel of its own feature rows straight into registers (one 16-byte and
-// one 8-byte load per sub-tile and panel, prefetched one panel ahead).  Needs group == 128
-// (one group per chunk-step, KW == 4, KS == 256) and 16-byte aligned scale rows (G % 8 == 0).
+// SZR = 1: scales and zero points are not staged in LDS; every lane fetches the groups of the
+// current panel (4 pipeline stages: 8 groups for KS = 256, 4 for KS = 128) of its own feature
+// rows straight into registers, prefetched one panel ahead.  Needs group == 128 (one group per
+// chunk-step, KW == 4) and 16-byte aligned scale rows (G % 8 == 0).
 // It frees the largest LDS consumer of the bandwidth-bound shapes, which is what bounds the
 // number of resident workgroups per CU there.
 template <int DT, int MT, int NT, int KS, int KW, int FUSE, int SZR>
-__global__ void __launch_bounds__(256, (MT * NT <= 4 ? 2 : 1)) w4a16_gemm_kernel(const GemmParams p) {
-  static_assert(SZR == 0 || (KW == 4 && KS == 256), "register-resident scales need 128-k chunk-steps");
+__global__ void __launch_bounds__(256, ((MT * NT <= 4 || (SZR && MT <= 4)) ? 2 : 1))
+w4a16_gemm_kernel(const GemmParams p) {
+  static_assert(SZR == 0 || KW == 4, "register-resident scales need 128-k chunk-steps (group 128)");
   using G_ = TileGeom<MT, NT, KS>;
   constexpr int M_T = G_::M_T, NW = G_::NW, N_T = G_::N_T, XP = G_::XP, WP = G_::WP;
   constexpr int CPR = G_::CPR, RPP = G_::RPP, XPASS = G_::XPASS;
@@ -294,6 +304,15 @@ __global__ void __launch_bounds__(256, (MT * NT <= 4 ? 2 : 1)) w4a16_gemm_kernel
   constexpr int CK = 32 * KW, UCH = KS / CK;
   static_assert(FUSE == 0 || NT % 2 == 0, "fused SiLU needs gate/up sub-tile pairs");
   constexpr int ZM = MT <= 2 ? 1 : 0;   // zero point through a second MFMA when MFMA time is plentiful
+  // RS = 1 (large token tiles): no separate partial-sum registers.  The accumulator of feature
+  // row n is kept in units of the scale of the group being processed: on entering a group with
+  // scale s it is multiplied by unit/s (unit := s), the MFMAs then add the exact integer products
+  // straight into it, and the epilogue multiplies by the last unit.  Costs the same one VALU op
+  // per accumulator element and group as the fused multiply-add on partial sums, but halves the
+  // accumulator registers, which is what lets 64x256 tiles run two workgroups per CU.  Each
+  // rescale is one fp32 rounding (and a 1-ulp reciprocal): about 1e-6 relative over a row.
+  // A zero scale keeps the unit and zeroes the group's operand instead.
+  constexpr int RS = MT >= 4 ? 1 : 0;
 
   extern __shared__ __align__(16) unsigned char smem[];
   unsigned char* xs = smem;                                        // [2][M_T][XP]
@@ -314,23 +333,27 @@ __global__ void __launch_bounds__(256, (MT * NT <= 4 ? 2 : 1)) w4a16_gemm_kernel
   uk.or_hi = vgpr_const(DT == kF16 ? 0x64006400u : 0x43004300u);
   uk.or_lo = vgpr_const(0x54005400u);
   unsigned char* wsw = ws_all + wave * NW * WP;
-  const int K_in = p.K_in, kwords = K_in >> 3;
+  const int K_in = p.K_in;
 
-  // ---- per-thread global pointers -------------------------------------------------
-  // Loads are never predicated: padding rows, feature rows past N_out and reduction chunks
-  // past K_in are redirected to a valid address.  What they fetch only ever reaches output
-  // rows / columns that are not stored, or chunk-steps that are not executed.
-  const uint16_t* A16 = reinterpret_cast<const uint16_t*>(p.A);
-  const uint16_t* xptr[XPASS];
+  // ---- per-thread global addresses ------------------------------------------------
+  // Every load address is (workgroup-uniform 64-bit base) + (32-bit per-lane byte offset): the
+  // stage advance is scalar arithmetic on the base and costs no VALU, and the per-lane part is
+  // a single register per load.  Loads are never predicated: padding rows, feature rows past
+  // N_out and reduction chunks past K_in are redirected to a valid address; what they fetch
+  // only ever reaches output rows / columns that are not stored, or chunk-steps that are not
+  // executed.  (The host checks that one expert's weights and the A matrix stay below 2 GiB.)
+  const unsigned char* const xbase = reinterpret_cast<const unsigned char*>(p.A);
+  uint32_t xoff[XPASS];
   const int xr_row = tid / CPR, xr_chunk = tid % CPR;
 #pragma unroll
   for (int ps = 0; ps < XPASS; ++ps) {
     const int slot = p.sorted_slot_ids[row0 + ps * RPP + xr_row];
-    const int arow = (slot >= 0 && slot < p.num_slots) ? slot / p.row_div : 0;
-    xptr[ps] = A16 + (size_t)arow * K_in;
+    const uint32_t arow = (slot >= 0 && slot < p.num_slots) ? (uint32_t)(slot / p.row_div) : 0u;
+    xoff[ps] = arow * (uint32_t)(K_in * 2) + (uint32_t)(xr_chunk * 16);
   }
-  const uint32_t* qw = reinterpret_cast<const uint32_t*>(p.qweight);
-  const uint32_t* wptr[WPASS];
+  const unsigned char* const wbase =
+      reinterpret_cast<const unsigned char*>(p.qweight) + (size_t)e * p.N_out * (size_t)(K_in >> 1);
+  uint32_t woff[WPASS];
   const int wl_row = lane / LPR, wl_chunk = lane % LPR;
 #pragma unroll
   for (int q = 0; q < WPASS; ++q) {
@@ -339,7 +362,18 @@ __global__ void __launch_bounds__(256, (MT * NT <= 4 ? 2 : 1)) w4a16_gemm_kernel
     bool ok;
     feature_of<NT, FUSE>(n_tile, wave, rw >> 4, rw & 15, p, wrow, ocol, ok);
     if (!ok) wrow = 0;
-    wptr[q] = qw + ((size_t)e * p.N_out + wrow) * kwords;
+    woff[q] = (uint32_t)wrow * (uint32_t)(K_in >> 1) + (uint32_t)(wl_chunk * 16);
+  }
+  // K tail (K_in % KS != 0): in the last stage, chunks past K_in step back onto the row's last
+  // valid 16 bytes.  wback / xback are the per-lane byte distances; zero when there is no tail.
+  const int nst = (K_in + KS - 1) / KS;
+  const bool has_tail = (K_in % KS) != 0;
+  uint32_t wback = 0, xback = 0;
+  if (has_tail) {
+    const int tail_k = K_in - (nst - 1) * KS;            // valid reduction indices of the last stage
+    const int wmax = tail_k / 2 - 16, xmax = tail_k * 2 - 16;
+    wback = wl_chunk * 16 > wmax ? (uint32_t)(wl_chunk * 16 - wmax) : 0u;
+    xback = xr_chunk * 16 > xmax ? (uint32_t)(xr_chunk * 16 - xmax) : 0u;
   }
 
   // Register prefetch ring: PD slots, loads issued PD stages ahead (all indices are compile-time
@@ -351,18 +385,18 @@ __global__ void __launch_bounds__(256, (MT * NT <= 4 ? 2 : 1)) w4a16_gemm_kernel
   u32x4 xr[PD][XPASS], wr[PD][WPASS];
 #define MOE_LOAD_STAGE(ST, XV, WV)                                                              \
   {                                                                                             \
-    /* A stage past the end still issues its loads (clamped onto the row's last chunk, which */ \
-    /* was just fetched) so the loop body is branch-free and the compiler can count the      */ \
-    /* outstanding loads exactly.                                                            */ \
-    const int k0_ = (ST) * KS;                                                                  \
-    int wk_ = k0_ + wl_chunk * 32; /* first reduction index of this lane's 16 B of weights */   \
-    if (wk_ > K_in - 32) wk_ = K_in - 32;                                                       \
-    int xk_ = k0_ + xr_chunk * 8;                                                               \
-    if (xk_ > K_in - 8) xk_ = K_in - 8;                                                         \
+    /* A stage past the end still issues its loads (onto the last stage, which was just      */ \
+    /* fetched) so the loop body is branch-free and the compiler can count the outstanding   */ \
+    /* loads exactly.                                                                        */ \
+    const int stc_ = (ST) < nst ? (ST) : nst - 1;                                               \
+    const unsigned char* wb_ = wbase + (size_t)stc_ * (KS / 2);                                 \
+    const unsigned char* xb_ = xbase + (size_t)stc_ * (KS * 2);                                 \
+    uint32_t wsub_ = 0, xsub_ = 0;                                                              \
+    if (has_tail && stc_ == nst - 1) { wsub_ = wback; xsub_ = xback; }                          \
     _Pragma("unroll") for (int q = 0; q < WPASS; ++q)                                           \
-        WV[q] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(wptr[q] + (wk_ >> 3))); \
+        WV[q] = load_weights<(MT <= 2)>(wb_ + (woff[q] - wsub_));                               \
     _Pragma("unroll") for (int ps = 0; ps < XPASS; ++ps)                                        \
-        XV[ps] = *reinterpret_cast<const u32x4*>(xptr[ps] + xk_);                               \
+        XV[ps] = *reinterpret_cast<const u32x4*>(xb_ + (xoff[ps] - xsub_));                     \
   }
 #define MOE_STORE_STAGE(XV, WV, XBUF)                                                           \
   {                                                                                             \
@@ -376,15 +410,34 @@ __global__ void __launch_bounds__(256, (MT * NT <= 4 ? 2 : 1)) w4a16_gemm_kernel
             interleave8(XV[ps]);                                                                \
   }
 
-  const int nst = (K_in + KS - 1) / KS;
 #pragma unroll
   for (int r = 0; r < PD; ++r) MOE_LOAD_STAGE(r, xr[r], wr[r])
 
   // ---- register-resident scales / zero points (SZR) -----------------------------------
-  // scur/snext: 8 fp16 scales and 8 zero-point bytes of the current / next panel, per sub-tile.
-  u32x4 s_cur[NT], s_nxt[NT];
-  u32x2 z_cur[NT], z_nxt[NT];
-  size_t sz_row[NT];
+  // s_cur/s_nxt: fp16/bf16 scales (two per register) and zero-point bytes (four per register)
+  // of the current / next panel, per sub-tile.
+  constexpr int PG = SZR ? UNR * UCH : 8;          // groups per panel
+  uint32_t s_cur[NT][PG / 2], s_nxt[NT][PG / 2];
+  uint32_t z_cur[NT][(PG + 3) / 4], z_nxt[NT][(PG + 3) / 4];
+  uint32_t sz_row[NT];                             // element offset of the lane's row (host checks the range)
+  auto load_sz = [&](int g0, uint32_t(&sv)[NT][PG / 2], uint32_t(&zv)[NT][(PG + 3) / 4]) {
+    if (g0 > p.G - PG) g0 = p.G - PG;               // clamp onto the last panel
+#pragma unroll
+    for (int s = 0; s < NT; ++s) {
+      const uint16_t* sp = reinterpret_cast<const uint16_t*>(p.scales) + sz_row[s] + g0;
+      const uint8_t* zp = p.zeros + sz_row[s] + g0;
+      if constexpr (PG == 8) {
+        const u32x4 a = *reinterpret_cast<const u32x4*>(sp);
+        const u32x2 b = *reinterpret_cast<const u32x2*>(zp);
+        sv[s][0] = a.x; sv[s][1] = a.y; sv[s][2] = a.z; sv[s][3] = a.w;
+        zv[s][0] = b.x; zv[s][1] = b.y;
+      } else {
+        const u32x2 a = *reinterpret_cast<const u32x2*>(sp);
+        sv[s][0] = a.x; sv[s][1] = a.y;
+        zv[s][0] = *reinterpret_cast<const uint32_t*>(zp);
+      }
+    }
+  };
   if constexpr (SZR) {
 #pragma unroll
     for (int s = 0; s < NT; ++s) {
@@ -392,10 +445,9 @@ __global__ void __launch_bounds__(256, (MT * NT <= 4 ? 2 : 1)) w4a16_gemm_kernel
       bool ok;
       feature_of<NT, FUSE>(n_tile, wave, s, ln, p, wrow, ocol, ok);
       if (!ok) wrow = 0;
-      sz_row[s] = ((size_t)e * p.N_out + wrow) * p.G;
-      s_cur[s] = *reinterpret_cast<const u32x4*>(reinterpret_cast<const uint16_t*>(p.scales) + sz_row[s]);
-      z_cur[s] = *reinterpret_cast<const u32x2*>(p.zeros + sz_row[s]);
+      sz_row[s] = ((uint32_t)e * (uint32_t)p.N_out + (uint32_t)wrow) * (uint32_t)p.G;
     }
+    load_sz(0, s_cur, z_cur);
   }
 
   // ---- stage scales / zero points of this tile's rows into LDS ---------------------
@@ -441,6 +493,9 @@ __global__ void __launch_bounds__(256, (MT * NT <= 4 ? 2 : 1)) w4a16_gemm_kernel
   for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
     for (int s = 0; s < NT; ++s) acc[mt][s] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+  float unit[NT];      // RS: scale the accumulator of each sub-tile is currently expressed in
+#pragma unroll
+  for (int s = 0; s < NT; ++s) unit[s] = 1.f;
 
   auto compute_stage = [&](int st, const unsigned char* xbuf, auto rc) {
     constexpr int R = decltype(rc)::value;       // step index inside the unrolled trip
@@ -456,7 +511,7 @@ __global__ void __launch_bounds__(256, (MT * NT <= 4 ? 2 : 1)) w4a16_gemm_kernel
 #pragma unroll
       for (int s = 0; s < NT; ++s) {
         if constexpr (SZR) {
-          const int gp = (2 * R + u) & 7;   // group inside the panel: constant after unrolling
+          const int gp = (UCH * R + u) % PG;   // group inside the panel: constant after unrolling
           const uint32_t sbits = (s_cur[s][gp >> 1] >> (16 * (gp & 1))) & 0xffffu;
           const uint32_t zb = (z_cur[s][gp >> 2] >> (8 * (gp & 3))) & 0xffu;
           ent[s] = pack_sz_entry<DT, ZM>((uint16_t)sbits, (uint8_t)zb);
@@ -465,7 +520,6 @@ __global__ void __launch_bounds__(256, (MT * NT <= 4 ? 2 : 1)) w4a16_gemm_kernel
         }
         wv[s] = lds_read_words<KW>(wsw + (s * 16 + ln) * WP + 16 * KW * u + 4 * KW * lj);
       }
-      floatx4_t part[MT][NT];
       u32x4 zop[NT];
       float scl[NT];
 #pragma unroll
@@ -474,30 +528,76 @@ __global__ void __launch_bounds__(256, (MT * NT <= 4 ? 2 : 1)) w4a16_gemm_kernel
         scl[s] = c.s;
         if constexpr (ZM) zop[s] = c.zoperand();
       }
+      if constexpr (RS) {
+        bool zero_scale[NT];
+        bool any_zero = false;
+        float rs[NT];
 #pragma unroll
-      for (int i = 0; i < KW; ++i) {
-        u32x4 b[NT];
+        for (int s = 0; s < NT; ++s) {
+          zero_scale[s] = scl[s] == 0.f;
+          any_zero |= zero_scale[s];
+          rs[s] = zero_scale[s] ? 1.f : unit[s] * __builtin_amdgcn_rcpf(scl[s]);
+          unit[s] = zero_scale[s] ? unit[s] : scl[s];
+        }
+        if (__builtin_expect(__ballot(any_zero) != 0ull, 0)) {
+          // Rare: a group with scale 0 contributes nothing.  Replace its packed words by q == z
+          // (exact zero after the subtract).  The empty asm keeps this a real branch.
+          asm volatile("" ::: "memory");
 #pragma unroll
-        for (int s = 0; s < NT; ++s) b[s] = dequant_word<DT, ZM>(wv[s].w[i], DeqCtx<DT, ZM>(ent[s]), uk);
+          for (int s = 0; s < NT; ++s) {
+            const uint32_t zword = ((ent[s] >> (DT == kF16 ? 16 : 0)) & 0xfu) * 0x11111111u;
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-          const u32x4 a = *reinterpret_cast<const u32x4*>(
-              xbuf + (mt * 16 + ln) * XP + 2 * (CK * u + 8 * KW * lj + 8 * i));
-#pragma unroll
-          for (int s = 0; s < NT; ++s)
-            part[mt][s] = mfma16x16x32<DT>(a, b[s], i == 0 ? floatx4_t{0.f, 0.f, 0.f, 0.f} : part[mt][s]);
-          if constexpr (ZM) {
-#pragma unroll
-            for (int s = 0; s < NT; ++s) part[mt][s] = mfma16x16x32<DT>(a, zop[s], part[mt][s]);
+            for (int i = 0; i < KW; ++i) wv[s].w[i] = zero_scale[s] ? zword : wv[s].w[i];
           }
         }
-      }
 #pragma unroll
-      for (int s = 0; s < NT; ++s) {
+        for (int i = 0; i < KW; ++i) {
+          u32x4 b[NT];
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
+          for (int s = 0; s < NT; ++s) b[s] = dequant_word<DT, ZM>(wv[s].w[i], DeqCtx<DT, ZM>(ent[s]), uk);
 #pragma unroll
-          for (int i = 0; i < 4; ++i) acc[mt][s][i] = __builtin_fmaf(scl[s], part[mt][s][i], acc[mt][s][i]);
+          for (int mt = 0; mt < MT; ++mt) {
+            const u32x4 a = *reinterpret_cast<const u32x4*>(
+                xbuf + (mt * 16 + ln) * XP + 2 * (CK * u + 8 * KW * lj + 8 * i));
+#pragma unroll
+            for (int s = 0; s < NT; ++s) {
+              // the rescale of each accumulator tile sits right before its first MFMA of the
+              // group, so it overlaps with the MFMAs of the neighbouring tiles
+              if (i == 0) {
+#pragma unroll
+                for (int c = 0; c < 4; ++c) acc[mt][s][c] *= rs[s];
+              }
+              acc[mt][s] = mfma16x16x32<DT>(a, b[s], acc[mt][s]);
+            }
+          }
+        }
+      } else {
+        floatx4_t part[MT][NT];
+#pragma unroll
+        for (int i = 0; i < KW; ++i) {
+          u32x4 b[NT];
+#pragma unroll
+          for (int s = 0; s < NT; ++s) b[s] = dequant_word<DT, ZM>(wv[s].w[i], DeqCtx<DT, ZM>(ent[s]), uk);
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt) {
+            const u32x4 a = *reinterpret_cast<const u32x4*>(
+                xbuf + (mt * 16 + ln) * XP + 2 * (CK * u + 8 * KW * lj + 8 * i));
+#pragma unroll
+            for (int s = 0; s < NT; ++s)
+              part[mt][s] = mfma16x16x32<DT>(a, b[s], i == 0 ? floatx4_t{0.f, 0.f, 0.f, 0.f} : part[mt][s]);
+            if constexpr (ZM) {
+#pragma unroll
+              for (int s = 0; s < NT; ++s) part[mt][s] = mfma16x16x32<DT>(a, zop[s], part[mt][s]);
+            }
+          }
+        }
+#pragma unroll
+        for (int s = 0; s < NT; ++s) {
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) acc[mt][s][i] = __builtin_fmaf(scl[s], part[mt][s][i], acc[mt][s][i]);
+        }
       }
     }
   };
@@ -511,16 +611,7 @@ __global__ void __launch_bounds__(256, (MT * NT <= 4 ? 2 : 1)) w4a16_gemm_kernel
   // scale registers are indexed statically.  Steps past the last stage compute nothing (their
   // loads are clamped onto valid addresses, their LDS stores are never read).
   for (int st0 = 0; st0 < nst; st0 += UNR) {
-    if constexpr (SZR) {
-      // prefetch the next panel's scales / zero points (clamped onto the last panel)
-      int g0 = (st0 >> 2) * 8 + 8;
-      if (g0 > p.G - 8) g0 = p.G - 8;
-#pragma unroll
-      for (int s = 0; s < NT; ++s) {
-        s_nxt[s] = *reinterpret_cast<const u32x4*>(reinterpret_cast<const uint16_t*>(p.scales) + sz_row[s] + g0);
-        z_nxt[s] = *reinterpret_cast<const u32x2*>(p.zeros + sz_row[s] + g0);
-      }
-    }
+    if constexpr (SZR) load_sz((st0 / UNR) * PG + PG, s_nxt, z_nxt);   // next panel, one trip ahead
     [&]<int... Rs>(std::integer_sequence<int, Rs...>) {
       (([&] {
          constexpr int r = Rs;
@@ -533,13 +624,26 @@ __global__ void __launch_bounds__(256, (MT * NT <= 4 ? 2 : 1)) w4a16_gemm_kernel
     }(std::make_integer_sequence<int, UNR>{});
     if constexpr (SZR) {
 #pragma unroll
-      for (int s = 0; s < NT; ++s) { s_cur[s] = s_nxt[s]; z_cur[s] = z_nxt[s]; }
+      for (int s = 0; s < NT; ++s) {
+#pragma unroll
+        for (int i = 0; i < PG / 2; ++i) s_cur[s][i] = s_nxt[s][i];
+#pragma unroll
+        for (int i = 0; i < (PG + 3) / 4; ++i) z_cur[s][i] = z_nxt[s][i];
+      }
     }
   }
 #undef MOE_LOAD_STAGE
 #undef MOE_STORE_STAGE
 
   // ---- epilogue: one rounding to the 16-bit type, rows addressed by slot id ---------
+  if constexpr (RS) {
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int s = 0; s < NT; ++s)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) acc[mt][s][i] *= unit[s];
+  }
   uint16_t* C16 = reinterpret_cast<uint16_t*>(p.C);
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {

@@ -66,7 +66,7 @@ def test_workspace_covers_tables_and_intermediates(binding):
 def test_layer_block_choice_tracks_rows_per_expert(binding):
     assert binding.moe_layer_block_m(128, 256, 8) == 16      # about 4 rows per expert
     assert binding.moe_layer_block_m(64, 8, 2) == 32         # 16 rows per expert
-    assert binding.moe_layer_block_m(4096, 256, 8) == 128    # 128 rows per expert
+    assert binding.moe_layer_block_m(4096, 256, 8) == 64     # 128 rows per expert
 
 
 def test_validation_before_launch_returns_status(binding):
