@@ -153,11 +153,15 @@ int moe_w4a16_layer(const void* X, const int32_t* topk_ids, const float* topk_we
  * small; an LDS table otherwise), 1 = always the LDS table, 2 = registers or
  * MOE_UNSUPPORTED_SHAPE.  Thread-local.
  *
+ * moe_set_tiles_per_workgroup: how many consecutive feature tiles one workgroup of the
+ * register-scale GEMM walks with a continuous load pipeline; 0 = choose.  Thread-local.
+ *
  * moe_layer_block_m: the bucketing block size the layer picks for these sizes.
  */
 int moe_set_stage_events(void* const* events, int n);
 int moe_set_tile_override(int mt, int nt);
 int moe_set_scale_path(int mode);
+int moe_set_tiles_per_workgroup(int n);
 int moe_layer_block_m(int T, int E, int topk);
 
 #ifdef __cplusplus

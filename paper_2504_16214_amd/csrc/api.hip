@@ -53,6 +53,7 @@ static thread_local void* g_events[5] = {nullptr, nullptr, nullptr, nullptr, nul
 static thread_local int g_nevents = 0;
 static thread_local int g_force_mt = 0, g_force_nt = 0;
 static thread_local int g_scale_path = 0;   // 0 auto, 1 LDS table, 2 registers
+static thread_local int g_force_tpw = 0;    // feature tiles per workgroup (register-scale kernels), 0 = auto
 
 static int fail(int status, const char* fmt, ...) {
   va_list ap;
@@ -174,7 +175,20 @@ static int run_gemm(const GemmArgs& a, hipStream_t stream) {
   p.out_f32 = a.out_f32;
   p.sz_vec = sz_vec;
   const size_t cap = align_capacity(a.num_slots, a.E, a.block_m);
-  const long long grid = (long long)(cap / (16 * mt)) * p.n_tiles;
+  // Register-scale kernels can walk several feature tiles per workgroup: aim for at least ~24
+  // pipeline stages per workgroup while keeping a few thousand workgroups in the launch.
+  int tpw = 1;
+  if (szr) {
+    const int nst = a.K_in / ks;
+    tpw = (24 + nst - 1) / nst;
+    if (tpw > 8) tpw = 8;
+    if (tpw > p.n_tiles) tpw = p.n_tiles;
+    const long long est_blocks = (a.num_slots + 16 * mt - 1) / (16 * mt) + (a.num_slots < a.E ? a.num_slots : a.E) / 2;
+    while (tpw > 1 && est_blocks * ((p.n_tiles + tpw - 1) / tpw) < 2048) --tpw;
+  }
+  if (g_force_tpw > 0) tpw = szr ? (g_force_tpw < p.n_tiles ? g_force_tpw : p.n_tiles) : 1;
+  p.tiles_per_wg = tpw;
+  const long long grid = (long long)(cap / (16 * mt)) * ((p.n_tiles + tpw - 1) / tpw);
   if (grid > 0x7fffffffLL) return fail(MOE_UNSUPPORTED_SHAPE, "grid too large");
   const int err = v->fn(p, (int)grid, stream);
   if (err != 0) return hip_fail(err, "grouped GEMM launch");
@@ -356,6 +370,12 @@ int moe_set_stage_events(void* const* events, int n) {
 int moe_set_scale_path(int mode) {
   if (mode < 0 || mode > 2) return fail(MOE_INVALID_ARGUMENT, "scale path mode must be 0, 1 or 2");
   g_scale_path = mode;
+  return MOE_OK;
+}
+
+int moe_set_tiles_per_workgroup(int n) {
+  if (n < 0 || n > 64) return fail(MOE_INVALID_ARGUMENT, "tiles per workgroup must be in 0..64");
+  g_force_tpw = n;
   return MOE_OK;
 }
 

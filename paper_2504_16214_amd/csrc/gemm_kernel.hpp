@@ -55,6 +55,7 @@ struct GemmParams {
   int half_n;     // fused SiLU-and-multiply: N (weight rows [0,N) gate, [N,2N) up); else 0
   int sz_vec;     // 1 if scale rows are 16-byte aligned (G % 8 == 0 and aligned base pointers)
   int out_f32;    // 1: C is float32 (the layer's down projection feeds the combine unrounded)
+  int tiles_per_wg;  // consecutive feature tiles one workgroup walks (1 unless SZR)
 };
 
 typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
@@ -320,10 +321,16 @@ w4a16_gemm_kernel(const GemmParams p) {
   uint32_t* sz = reinterpret_cast<uint32_t*>(ws_all + 4 * NW * WP);  // [G][N_T] (absent when SZR)
   int* slot_s = reinterpret_cast<int*>(sz + (SZR ? 0 : p.G * N_T));  // [M_T]
 
-  const int L = xcd_contiguous_index(blockIdx.x, (*p.num_padded / M_T) * p.n_tiles);
+  // A workgroup owns one block of M_T slots and `tiles_per_wg` consecutive feature tiles; it
+  // walks them with one continuous load pipeline (no drain between tiles), so the fixed cost of
+  // starting a workgroup is paid once per several tiles when the reduction is short.
+  const int tpw = SZR ? p.tiles_per_wg : 1;
+  const int tgroups = (p.n_tiles + tpw - 1) / tpw;
+  const int L = xcd_contiguous_index(blockIdx.x, (*p.num_padded / M_T) * tgroups);
   if (L < 0) return;
-  const int n_tile = L % p.n_tiles;
-  const int row0 = (L / p.n_tiles) * M_T;
+  const int tile0 = (L % tgroups) * tpw;
+  const int ntl = p.n_tiles - tile0 < tpw ? p.n_tiles - tile0 : tpw;     // tiles this workgroup walks
+  const int row0 = (L / tgroups) * M_T;
   const int e = p.block_expert_ids[row0 / p.block_m];
   if (e < 0 || e >= p.E) return;
 
@@ -353,17 +360,20 @@ w4a16_gemm_kernel(const GemmParams p) {
   }
   const unsigned char* const wbase =
       reinterpret_cast<const unsigned char*>(p.qweight) + (size_t)e * p.N_out * (size_t)(K_in >> 1);
-  uint32_t woff[WPASS];
+  uint32_t woff[WPASS];      // rows of the tile the LOAD cursor is in
   const int wl_row = lane / LPR, wl_chunk = lane % LPR;
+  auto set_w_rows = [&](int tile) {
 #pragma unroll
-  for (int q = 0; q < WPASS; ++q) {
-    const int rw = q * RPI + wl_row;
-    int wrow, ocol;
-    bool ok;
-    feature_of<NT, FUSE>(n_tile, wave, rw >> 4, rw & 15, p, wrow, ocol, ok);
-    if (!ok) wrow = 0;
-    woff[q] = (uint32_t)wrow * (uint32_t)(K_in >> 1) + (uint32_t)(wl_chunk * 16);
-  }
+    for (int q = 0; q < WPASS; ++q) {
+      const int rw = q * RPI + wl_row;
+      int wrow, ocol;
+      bool ok;
+      feature_of<NT, FUSE>(tile, wave, rw >> 4, rw & 15, p, wrow, ocol, ok);
+      if (!ok) wrow = 0;
+      woff[q] = (uint32_t)wrow * (uint32_t)(K_in >> 1) + (uint32_t)(wl_chunk * 16);
+    }
+  };
+  set_w_rows(tile0);
   // K tail (K_in % KS != 0): in the last stage, chunks past K_in step back onto the row's last
   // valid 16 bytes.  wback / xback are the per-lane byte distances; zero when there is no tail.
   const int nst = (K_in + KS - 1) / KS;
@@ -410,8 +420,27 @@ w4a16_gemm_kernel(const GemmParams p) {
             interleave8(XV[ps]);                                                                \
   }
 
+  // Flattened step index over (tile, stage).  nst_pad rounds the stages of a tile up to whole
+  // trips; stages in [nst, nst_pad) are dead (clamped loads, no compute).
+  const int nst_pad = (nst + UNR - 1) / UNR * UNR;
+  int ld_t = 0, ld_st = 0;          // LOAD cursor: tile (local) and stage of the next stage to fetch
+#define MOE_ADVANCE_LOAD_CURSOR()                                   \
+  {                                                                 \
+    if (++ld_st == nst_pad) {                                       \
+      ld_st = 0;                                                    \
+      if (++ld_t < ntl) {                                           \
+        set_w_rows(tile0 + ld_t);                                   \
+      } else { /* past the last tile: re-read row 0 of the expert; the lane keeps its own  */ \
+               /* chunk offset so that subtracting wback (<= wl_chunk*16) cannot underflow  */ \
+        _Pragma("unroll") for (int q = 0; q < WPASS; ++q) woff[q] = (uint32_t)(wl_chunk * 16); \
+      }                                                             \
+    }                                                               \
+  }
 #pragma unroll
-  for (int r = 0; r < PD; ++r) MOE_LOAD_STAGE(r, xr[r], wr[r])
+  for (int r = 0; r < PD; ++r) {
+    MOE_LOAD_STAGE(ld_st, xr[r], wr[r])
+    MOE_ADVANCE_LOAD_CURSOR()
+  }
 
   // ---- register-resident scales / zero points (SZR) -----------------------------------
   // s_cur/s_nxt: fp16/bf16 scales (two per register) and zero-point bytes (four per register)
@@ -438,16 +467,22 @@ w4a16_gemm_kernel(const GemmParams p) {
       }
     }
   };
-  if constexpr (SZR) {
+  auto set_sz_rows = [&](int tile) {
 #pragma unroll
     for (int s = 0; s < NT; ++s) {
       int wrow, ocol;
       bool ok;
-      feature_of<NT, FUSE>(n_tile, wave, s, ln, p, wrow, ocol, ok);
+      feature_of<NT, FUSE>(tile, wave, s, ln, p, wrow, ocol, ok);
       if (!ok) wrow = 0;
       sz_row[s] = ((uint32_t)e * (uint32_t)p.N_out + (uint32_t)wrow) * (uint32_t)p.G;
     }
+  };
+  int sp_t = 0, sp_pan = 1;          // panel cursor: tile (local) and panel of the next prefetch
+  const int npan = nst_pad / UNR;
+  if constexpr (SZR) {
+    set_sz_rows(tile0);
     load_sz(0, s_cur, z_cur);
+    if (npan == 1) { sp_pan = 0; sp_t = 1; if (sp_t < ntl) set_sz_rows(tile0 + sp_t); }
   }
 
   // ---- stage scales / zero points of this tile's rows into LDS ---------------------
@@ -459,7 +494,7 @@ w4a16_gemm_kernel(const GemmParams p) {
       const int lf = idx % N_T, gb = (idx / N_T) * 8;
       int wrow, ocol;
       bool ok;
-      feature_of<NT, FUSE>(n_tile, lf / NW, (lf % NW) >> 4, lf & 15, p, wrow, ocol, ok);
+      feature_of<NT, FUSE>(tile0, lf / NW, (lf % NW) >> 4, lf & 15, p, wrow, ocol, ok);
       uint16_t sv[8];
       uint8_t zv[8];
       if (!ok) wrow = 0;      // fetched but never used: the row's outputs are not stored
@@ -605,18 +640,79 @@ w4a16_gemm_kernel(const GemmParams p) {
   MOE_STORE_STAGE(xr[0], wr[0], xs)
   __syncthreads();
 
-  // Step st: issue the loads of stage st+PD into the ring slot that held stage st (it went to
-  // LDS in the previous step), compute stage st from LDS, move stage st+1 from its ring slot
-  // into LDS, barrier.  UNR steps per trip so ring slots, activation buffers and (SZR) the
-  // scale registers are indexed statically.  Steps past the last stage compute nothing (their
-  // loads are clamped onto valid addresses, their LDS stores are never read).
-  for (int st0 = 0; st0 < nst; st0 += UNR) {
-    if constexpr (SZR) load_sz((st0 / UNR) * PG + PG, s_nxt, z_nxt);   // next panel, one trip ahead
+  // ---- store one finished feature tile: one rounding to the 16-bit type, rows by slot id ----
+  auto store_tile = [&](int tile) {
+    if constexpr (RS) {
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int s = 0; s < NT; ++s)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) acc[mt][s][i] *= unit[s];
+    }
+    uint16_t* C16 = reinterpret_cast<uint16_t*>(p.C);
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int slot = slot_s[mt * 16 + lj * 4 + i];
+        if (slot < 0 || slot >= p.num_slots) continue;
+        uint16_t* crow = C16 + (size_t)slot * p.ldc;
+        if constexpr (FUSE == 0) {
+#pragma unroll
+          for (int s = 0; s < NT; ++s) {
+            int wrow, ocol; bool ok;
+            feature_of<NT, FUSE>(tile, wave, s, ln, p, wrow, ocol, ok);
+            if (ok) {
+              if (p.out_f32) reinterpret_cast<float*>(p.C)[(size_t)slot * p.ldc + ocol] = acc[mt][s][i];
+              else crow[ocol] = to_bits16<DT>(acc[mt][s][i]);
+            }
+          }
+        } else {
+#pragma unroll
+          for (int s = 0; s < NT; s += 2) {
+            int wrow, ocol; bool ok;
+            feature_of<NT, FUSE>(tile, wave, s, ln, p, wrow, ocol, ok);
+            if (ok) {
+              // round gate/up to the storage type first so the fused path equals the staged one
+              const float g = from_bits16<DT>(to_bits16<DT>(acc[mt][s][i]));
+              const float u = from_bits16<DT>(to_bits16<DT>(acc[mt][s + 1][i]));
+              crow[ocol] = to_bits16<DT>(silu_f32(g) * u);
+            }
+          }
+        }
+      }
+    }
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int s = 0; s < NT; ++s) acc[mt][s] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int s = 0; s < NT; ++s) unit[s] = 1.f;
+  };
+
+  // Step: issue the loads PD stages ahead into the ring slot whose stage went to LDS in the
+  // previous step, compute the current stage from LDS, move the next stage from its ring slot
+  // into LDS, barrier.  UNR steps per trip so ring slots, activation buffers and (SZR) the scale
+  // registers are indexed statically.  Dead stages compute nothing (their loads are clamped onto
+  // valid addresses, their LDS stores are never read).  A trip never straddles two tiles.
+  int c_t = 0, c_st = 0;             // compute cursor
+  const int trips = ntl * npan;
+  for (int trip = 0; trip < trips; ++trip) {
+    if constexpr (SZR) {
+      // prefetch the scales / zero points of the next panel (possibly of the next tile)
+      load_sz(sp_pan * PG, s_nxt, z_nxt);
+      if (++sp_pan == npan) {
+        sp_pan = 0;
+        if (++sp_t < ntl) set_sz_rows(tile0 + sp_t);
+      }
+    }
     [&]<int... Rs>(std::integer_sequence<int, Rs...>) {
       (([&] {
          constexpr int r = Rs;
-         MOE_LOAD_STAGE(st0 + r + PD, xr[r % PD], wr[r % PD])
-         compute_stage(st0 + r, xs + (r % 2) * (M_T * XP), std::integral_constant<int, r>{});
+         MOE_LOAD_STAGE(ld_st, xr[r % PD], wr[r % PD])
+         MOE_ADVANCE_LOAD_CURSOR()
+         compute_stage(c_st + r, xs + (r % 2) * (M_T * XP), std::integral_constant<int, r>{});
          MOE_STORE_STAGE(xr[(r + 1) % PD], wr[(r + 1) % PD], xs + ((r + 1) % 2) * (M_T * XP))
          __syncthreads();
        }()),
@@ -631,52 +727,16 @@ w4a16_gemm_kernel(const GemmParams p) {
         for (int i = 0; i < (PG + 3) / 4; ++i) z_cur[s][i] = z_nxt[s][i];
       }
     }
+    c_st += UNR;
+    if (c_st == nst_pad) {
+      store_tile(tile0 + c_t);
+      c_st = 0;
+      ++c_t;
+    }
   }
 #undef MOE_LOAD_STAGE
 #undef MOE_STORE_STAGE
-
-  // ---- epilogue: one rounding to the 16-bit type, rows addressed by slot id ---------
-  if constexpr (RS) {
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-      for (int s = 0; s < NT; ++s)
-#pragma unroll
-        for (int i = 0; i < 4; ++i) acc[mt][s][i] *= unit[s];
-  }
-  uint16_t* C16 = reinterpret_cast<uint16_t*>(p.C);
-#pragma unroll
-  for (int mt = 0; mt < MT; ++mt) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int slot = slot_s[mt * 16 + lj * 4 + i];
-      if (slot < 0 || slot >= p.num_slots) continue;
-      uint16_t* crow = C16 + (size_t)slot * p.ldc;
-      if constexpr (FUSE == 0) {
-#pragma unroll
-        for (int s = 0; s < NT; ++s) {
-          int wrow, ocol; bool ok;
-          feature_of<NT, FUSE>(n_tile, wave, s, ln, p, wrow, ocol, ok);
-          if (ok) {
-            if (p.out_f32) reinterpret_cast<float*>(p.C)[(size_t)slot * p.ldc + ocol] = acc[mt][s][i];
-            else crow[ocol] = to_bits16<DT>(acc[mt][s][i]);
-          }
-        }
-      } else {
-#pragma unroll
-        for (int s = 0; s < NT; s += 2) {
-          int wrow, ocol; bool ok;
-          feature_of<NT, FUSE>(n_tile, wave, s, ln, p, wrow, ocol, ok);
-          if (ok) {
-            // round gate/up to the storage type first so the fused path equals the staged one
-            const float g = from_bits16<DT>(to_bits16<DT>(acc[mt][s][i]));
-            const float u = from_bits16<DT>(to_bits16<DT>(acc[mt][s + 1][i]));
-            crow[ocol] = to_bits16<DT>(silu_f32(g) * u);
-          }
-        }
-      }
-    }
-  }
+#undef MOE_ADVANCE_LOAD_CURSOR
 }
 
 // Host-side launcher, one per instantiation.  Returns hipError_t as int.

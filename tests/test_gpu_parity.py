@@ -147,6 +147,22 @@ def test_register_resident_scale_variants(tile, dtype, K, which):
         M.moe_set_scale_path(0)
 
 
+@pytest.mark.parametrize("tpw", [1, 2, 3, 8])
+@pytest.mark.parametrize("which", ["w1", "w2"])
+def test_multi_tile_workgroups(tpw, which):
+    """Several feature tiles per workgroup (continuous pipeline across tiles), including a
+    ragged last group of tiles."""
+    cfg = MoEConfig(name="tpw", T=70, K=1024, N=2048, E=5, topk=2, group=128, dtype="f16", seed=14)
+    say(f"gemm tiles_per_workgroup={tpw} {which}")
+    M.moe_set_scale_path(2)
+    M.moe_set_tiles_per_workgroup(tpw)
+    try:
+        staged_gemm_case(cfg, 16, which, tile=(1, 2))
+    finally:
+        M.moe_set_tiles_per_workgroup(0)
+        M.moe_set_scale_path(0)
+
+
 def test_scale_paths_agree_bitwise():
     cfg = MoEConfig(name="szr_eq", T=64, K=2048, N=1024, E=6, topk=2, group=128, dtype="f16", seed=13)
     say("layer with LDS-table scales vs register scales")
