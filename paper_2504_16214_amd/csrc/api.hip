@@ -104,7 +104,8 @@ static int choose_tile(int num_slots, int E, int feat, int G, int block_m, int f
     return (nt >= min_nt && (nt == 1 || nt == 2 || nt == 4) && gemm_lds_bytes(mt, nt, ks, G, szr) <= kLdsLimit) ? 0 : -1;
   }
   const long long est_blocks = (num_slots + 16 * mt - 1) / (16 * mt) + (num_slots < E ? num_slots : E) / 2;
-  nt = mt >= 4 ? 4 : 2;
+  // 256-feature tiles only pay off with register-resident scales (two workgroups per CU)
+  nt = (mt >= 4 && pick_szr(4)) ? 4 : 2;
   for (;;) {
     const int fpw = fuse ? 32 * nt : 64 * nt;
     const long long wgs = est_blocks * ((feat + fpw - 1) / fpw);

@@ -304,7 +304,10 @@ w4a16_gemm_kernel(const GemmParams p) {
   constexpr int LPR = G_::LPR, RPI = G_::RPI, WPASS = G_::WPASS;
   constexpr int CK = 32 * KW, UCH = KS / CK;
   static_assert(FUSE == 0 || NT % 2 == 0, "fused SiLU needs gate/up sub-tile pairs");
-  constexpr int ZM = MT <= 2 ? 1 : 0;   // zero point through a second MFMA when MFMA time is plentiful
+  // zero point through a second MFMA when MFMA time is plentiful (small token tiles), and for
+  // bf16 at any tile size: without packed bf16 arithmetic the per-pair subtract costs four
+  // times the VALU work of the fp16 one, which is the scarcer resource even for large tiles
+  constexpr int ZM = (MT <= 2 || DT == kBF16) ? 1 : 0;
   // RS = 1 (large token tiles): no separate partial-sum registers.  The accumulator of feature
   // row n is kept in units of the scale of the group being processed: on entering a group with
   // scale s it is multiplied by unit/s (unit := s), the MFMAs then add the exact integer products
@@ -580,6 +583,7 @@ w4a16_gemm_kernel(const GemmParams p) {
           asm volatile("" ::: "memory");
 #pragma unroll
           for (int s = 0; s < NT; ++s) {
+            // q == z everywhere: the subtract (or the zero-point MFMA) cancels it exactly
             const uint32_t zword = ((ent[s] >> (DT == kF16 ? 16 : 0)) & 0xfu) * 0x11111111u;
 #pragma unroll
             for (int i = 0; i < KW; ++i) wv[s].w[i] = zero_scale[s] ? zword : wv[s].w[i];
@@ -603,6 +607,10 @@ w4a16_gemm_kernel(const GemmParams p) {
                 for (int c = 0; c < 4; ++c) acc[mt][s][c] *= rs[s];
               }
               acc[mt][s] = mfma16x16x32<DT>(a, b[s], acc[mt][s]);
+            }
+            if constexpr (ZM) {
+#pragma unroll
+              for (int s = 0; s < NT; ++s) acc[mt][s] = mfma16x16x32<DT>(a, zop[s], acc[mt][s]);
             }
           }
         }

@@ -177,6 +177,33 @@ def test_scale_paths_agree_bitwise():
     assert np.array_equal(outs[0], outs[1])
 
 
+@pytest.mark.parametrize("dtype,group,K", [("f16", 128, 1024), ("bf16", 64, 512), ("f16", 32, 256)])
+@pytest.mark.parametrize("block_m", [16, 64, 128])
+def test_zero_and_negative_scales(dtype, group, K, block_m):
+    """A zero scale silences its group, a negative one flips it: both are legal inputs (the
+    large-tile kernels keep the accumulator in units of the group scale and must not divide by
+    zero)."""
+    cfg = MoEConfig(name="zs", T=100, K=K, N=256, E=3, topk=2, group=group, dtype=dtype, seed=15)
+    say(f"gemm zero/negative scales dtype={dtype} group={group} block_m={block_m}")
+    inp = make_inputs(cfg)
+    rng = np.random.default_rng(3)
+    s = O.decode_bits(inp.s1_bits, dtype)
+    s[rng.random(s.shape) < 0.25] = 0.0
+    s[rng.random(s.shape) < 0.15] *= -1.0
+    s[:, :, 0] = 0.0                       # first group of every row
+    s[0, :8, :] = 0.0                      # whole rows
+    inp.s1_bits = O.encode_bits(s, dtype)
+    d = U.DevInputs(inp)
+    al = U.run_align(d.ids, cfg.E, block_m)
+    C = torch.full((cfg.S, 2 * cfg.N), 777.0, dtype=U.TORCH_DT[dtype], device="cuda")
+    M.moe_w4a16_grouped_gemm(d.X, cfg.topk, d.qw1, d.s1, d.z1, al["sorted_slot_ids"], al["block_expert_ids"],
+                             al["num_padded"], cfg.S, cfg.group, block_m, C)
+    torch.cuda.synchronize()
+    want = O.grouped_gemm(O.decode_bits(inp.x_bits, dtype), cfg.topk, inp.qw1, s, inp.z1,
+                          inp.topk_ids.reshape(-1), cfg.group, dtype)
+    U.assert_close(U.dev_to_f64(C), want, "zero/negative scales")
+
+
 def test_grouped_gemm_ignores_invalid_slots_and_leaves_rows_untouched():
     cfg = MoEConfig(name="inv", T=30, K=256, N=128, E=4, topk=2, group=128, dtype="f16", seed=6)
     say("gemm with out-of-range expert ids")
