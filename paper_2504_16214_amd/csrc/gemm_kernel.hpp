@@ -304,10 +304,12 @@ w4a16_gemm_kernel(const GemmParams p) {
   constexpr int LPR = G_::LPR, RPI = G_::RPI, WPASS = G_::WPASS;
   constexpr int CK = 32 * KW, UCH = KS / CK;
   static_assert(FUSE == 0 || NT % 2 == 0, "fused SiLU needs gate/up sub-tile pairs");
-  // zero point through a second MFMA when MFMA time is plentiful (small token tiles), and for
-  // bf16 at any tile size: without packed bf16 arithmetic the per-pair subtract costs four
-  // times the VALU work of the fp16 one, which is the scarcer resource even for large tiles
-  constexpr int ZM = (MT <= 2 || DT == kBF16) ? 1 : 0;
+  // Zero point: fp16 subtracts bias + z with one packed op per pair (exact: integers below 2048).
+  // bf16 has no packed arithmetic, the per-pair subtract would cost four times the VALU work, so
+  // there the biased integers go to the MFMA and bias + z is subtracted by a second MFMA against a
+  // constant operand.  (VALU and MFMA instructions of one SIMD largely serialise on this chip --
+  // measured -- so for fp16 four packed ops are cheaper than one more 16-cycle MFMA.)
+  constexpr int ZM = DT == kBF16 ? 1 : 0;
   // RS = 1 (large token tiles): no separate partial-sum registers.  The accumulator of feature
   // row n is kept in units of the scale of the group being processed: on entering a group with
   // scale s it is multiplied by unit/s (unit := s), the MFMAs then add the exact integer products
@@ -392,9 +394,11 @@ w4a16_gemm_kernel(const GemmParams p) {
   // Register prefetch ring: PD slots, loads issued PD stages ahead (all indices are compile-time
   // constants after unrolling, so the ring stays in VGPRs).  Deeper rings were measured slower
   // on the decode shapes: the K loops are short and the extra dead steps at the end cost more
-  // than the additional bytes in flight gain.
-  constexpr int PD = 2;
-  constexpr int UNR = SZR ? 4 : PD;      // steps per loop trip (one 1024-k scale panel when SZR)
+  // than the additional bytes in flight gain.  Large token tiles spend several microseconds per
+  // stage, one stage of flight time covers the memory latency and the second slot's registers
+  // are worth more to the compiler (no spills at 64x256).
+  constexpr int PD = MT >= 4 ? 1 : 2;
+  constexpr int UNR = SZR ? 4 : 2;      // steps per loop trip (one 1024-k scale panel when SZR)
   u32x4 xr[PD][XPASS], wr[PD][WPASS];
 #define MOE_LOAD_STAGE(ST, XV, WV)                                                              \
   {                                                                                             \
