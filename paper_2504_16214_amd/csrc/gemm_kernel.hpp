@@ -252,13 +252,23 @@ __device__ __forceinline__ WordVec<KW> lds_read_words(const unsigned char* p) {
   return v;
 }
 
+// LDS row padding.  Measured with a 128-bit read microbenchmark: a lane (n, j) reading row n at
+// 16-byte chunk j runs at full rate when the row pitch is 2 mod 4 chunks (6, 10) and 1.35x slower
+// at the odd pitches 5 and 9.  The activation tile is read the same way (row n, chunk j + 4i for
+// the i-th MFMA of a chunk-step), which is why its chunks are stored transposed inside each
+// chunk-step (chunk KW*j + i at position j + 4*i): with the natural order (chunk 4j + i) no
+// pitch gets rid of the 1.35x.  (End to end the effect is within run-to-run noise: LDS time is a
+// few percent of the kernel.)
+constexpr int kXRowPad = 32;
+constexpr int kWRowPad = 32;
+
 template <int MT, int NT, int KS>
 struct TileGeom {
   static constexpr int M_T = 16 * MT;        // slots per workgroup tile
   static constexpr int NW = 16 * NT;         // features per wave
   static constexpr int N_T = 4 * NW;         // features per workgroup
-  static constexpr int XP = KS * 2 + 16;     // LDS bytes per activation row (padded)
-  static constexpr int WP = KS / 2 + 16;     // LDS bytes per packed weight row (padded)
+  static constexpr int XP = KS * 2 + kXRowPad;   // LDS bytes per activation row (padded)
+  static constexpr int WP = KS / 2 + kWRowPad;   // LDS bytes per packed weight row (padded)
   static constexpr int CPR = KS / 8;         // 16-byte chunks per activation row
   static constexpr int RPP = 256 / CPR;      // activation rows per cooperative pass
   static constexpr int XPASS = M_T / RPP;    // passes per stage
@@ -357,6 +367,8 @@ w4a16_gemm_kernel(const GemmParams p) {
   const unsigned char* const xbase = reinterpret_cast<const unsigned char*>(p.A);
   uint32_t xoff[XPASS];
   const int xr_row = tid / CPR, xr_chunk = tid % CPR;
+  // LDS position of the thread's 16-byte chunk: transposed inside its chunk-step (4*KW chunks)
+  const int xw_pos = (xr_chunk / (4 * KW)) * (4 * KW) + (xr_chunk % (4 * KW)) / KW + 4 * (xr_chunk % KW);
 #pragma unroll
   for (int ps = 0; ps < XPASS; ++ps) {
     const int slot = p.sorted_slot_ids[row0 + ps * RPP + xr_row];
@@ -423,7 +435,7 @@ w4a16_gemm_kernel(const GemmParams p) {
           t_;                                                                                   \
     }                                                                                           \
     _Pragma("unroll") for (int ps = 0; ps < XPASS; ++ps)                                        \
-        *reinterpret_cast<u32x4*>((XBUF) + (ps * RPP + xr_row) * XP + xr_chunk * 16) =          \
+        *reinterpret_cast<u32x4*>((XBUF) + (ps * RPP + xr_row) * XP + xw_pos * 16) =            \
             interleave8(XV[ps]);                                                                \
   }
 
@@ -601,7 +613,7 @@ w4a16_gemm_kernel(const GemmParams p) {
 #pragma unroll
           for (int mt = 0; mt < MT; ++mt) {
             const u32x4 a = *reinterpret_cast<const u32x4*>(
-                xbuf + (mt * 16 + ln) * XP + 2 * (CK * u + 8 * KW * lj + 8 * i));
+                xbuf + (mt * 16 + ln) * XP + 16 * (4 * KW * u + lj + 4 * i));
 #pragma unroll
             for (int s = 0; s < NT; ++s) {
               // the rescale of each accumulator tile sits right before its first MFMA of the
@@ -628,7 +640,7 @@ w4a16_gemm_kernel(const GemmParams p) {
 #pragma unroll
           for (int mt = 0; mt < MT; ++mt) {
             const u32x4 a = *reinterpret_cast<const u32x4*>(
-                xbuf + (mt * 16 + ln) * XP + 2 * (CK * u + 8 * KW * lj + 8 * i));
+                xbuf + (mt * 16 + ln) * XP + 16 * (4 * KW * u + lj + 4 * i));
 #pragma unroll
             for (int s = 0; s < NT; ++s)
               part[mt][s] = mfma16x16x32<DT>(a, b[s], i == 0 ? floatx4_t{0.f, 0.f, 0.f, 0.f} : part[mt][s]);
