@@ -43,8 +43,8 @@ def algorithmic_bytes(cfg, topk_ids):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=100)
     ap.add_argument("--config", default="deepseek_decode")
     ap.add_argument("--tile", default="", help="mt,nt override of the GEMM tile (tuning)")
     ap.add_argument("--no-cpu-baseline", action="store_true")

@@ -156,12 +156,20 @@ int moe_w4a16_layer(const void* X, const int32_t* topk_ids, const float* topk_we
  * moe_set_tiles_per_workgroup: how many consecutive feature tiles one workgroup of the
  * register-scale GEMM walks with a continuous load pipeline; 0 = choose.  Thread-local.
  *
+ * moe_set_reduction_splits: into how many ranges moe_w4a16_layer cuts the reduction of its down
+ * projection (one workgroup per range, float32 partial planes in the workspace, added by the
+ * combine); 0 = choose (more than one only for small batches on few experts, where the launch
+ * would otherwise have too few workgroups).  Limited by the planes the workspace holds and by the
+ * number of 1024-index scale panels; ignored by kernels without register-resident scales.
+ * Thread-local.
+ *
  * moe_layer_block_m: the bucketing block size the layer picks for these sizes.
  */
 int moe_set_stage_events(void* const* events, int n);
 int moe_set_tile_override(int mt, int nt);
 int moe_set_scale_path(int mode);
 int moe_set_tiles_per_workgroup(int n);
+int moe_set_reduction_splits(int n);
 int moe_layer_block_m(int T, int E, int topk);
 
 #ifdef __cplusplus

@@ -16,7 +16,7 @@ _LIB: Optional[ctypes.CDLL] = None
 EXPORTS = [
     "moe_last_error", "moe_align_capacity", "moe_align_by_expert", "moe_w4a16_grouped_gemm",
     "moe_silu_mul", "moe_combine", "moe_w4a16_layer_workspace_bytes", "moe_w4a16_layer",
-    "moe_set_stage_events", "moe_set_tile_override", "moe_set_scale_path", "moe_set_tiles_per_workgroup", "moe_layer_block_m",
+    "moe_set_stage_events", "moe_set_tile_override", "moe_set_scale_path", "moe_set_tiles_per_workgroup", "moe_set_reduction_splits", "moe_layer_block_m",
 ]
 
 
@@ -65,6 +65,8 @@ def load_library() -> ctypes.CDLL:
     lib.moe_set_scale_path.argtypes = [i32]
     lib.moe_set_tiles_per_workgroup.restype = i32
     lib.moe_set_tiles_per_workgroup.argtypes = [i32]
+    lib.moe_set_reduction_splits.restype = i32
+    lib.moe_set_reduction_splits.argtypes = [i32]
     lib.moe_layer_block_m.restype = i32
     lib.moe_layer_block_m.argtypes = [i32, i32, i32]
     _LIB = lib
@@ -166,6 +168,10 @@ def moe_set_scale_path(mode: int) -> None:
 
 def moe_set_tiles_per_workgroup(n: int) -> None:
     _check(load_library().moe_set_tiles_per_workgroup(n))
+
+
+def moe_set_reduction_splits(n: int) -> None:
+    _check(load_library().moe_set_reduction_splits(n))
 
 
 def moe_set_stage_events(events) -> None:

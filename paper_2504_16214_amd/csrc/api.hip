@@ -13,7 +13,7 @@ namespace moe {
 int launch_align(const int32_t*, int, int, int, int, int32_t*, int32_t*, int32_t*, int32_t*, int32_t*,
                  hipStream_t);
 int launch_silu_mul(const void*, void*, long long, int, int, hipStream_t);
-int launch_combine(const void*, int, const float*, const int32_t*, int, void*, long long, int, int, int,
+int launch_combine(const void*, int, int, const float*, const int32_t*, int, void*, long long, int, int, int,
                    hipStream_t);
 
 // ---- table of compiled GEMM variants ------------------------------------------------------
@@ -54,6 +54,7 @@ static thread_local int g_nevents = 0;
 static thread_local int g_force_mt = 0, g_force_nt = 0;
 static thread_local int g_scale_path = 0;   // 0 auto, 1 LDS table, 2 registers
 static thread_local int g_force_tpw = 0;    // feature tiles per workgroup (register-scale kernels), 0 = auto
+static thread_local int g_force_ksplit = 0; // reduction splits of the layer's down projection, 0 = auto
 
 static int fail(int status, const char* fmt, ...) {
   va_list ap;
@@ -112,7 +113,9 @@ static int choose_tile(int num_slots, int E, int feat, int G, int block_m, int f
     szr = pick_szr(nt);
     if (g_scale_path == 2 && !szr) { if (nt == min_nt) return -1; nt >>= 1; continue; }
     const bool fits = gemm_lds_bytes(mt, nt, ks, G, szr) <= kLdsLimit;
-    if (fits && (wgs >= 512 || nt == min_nt)) return 0;
+    // 128-feature tiles stay even when they leave fewer than two workgroups per CU: measured
+    // faster than twice as many 64-feature tiles (same bytes in flight, less activation staging)
+    if (fits && (wgs >= 512 || nt <= 2 || nt == min_nt)) return 0;
     if (nt == min_nt) return -1;
     nt >>= 1;
   }
@@ -124,6 +127,8 @@ struct GemmArgs {
   const int32_t* sorted_slot_ids; const int32_t* block_expert_ids; const int32_t* num_padded;
   int num_slots, E, N_out, K_in, group, block_m, dt;
   void* C; int ldc; int fuse_half_n; int out_f32;
+  int k_splits = 1;          // wanted reduction splits (float32 output planes num_slots*ldc apart)
+  int* used_splits = nullptr;  // out: the number of planes the launch really wrote
 };
 
 static int run_gemm(const GemmArgs& a, hipStream_t stream) {
@@ -175,21 +180,31 @@ static int run_gemm(const GemmArgs& a, hipStream_t stream) {
   p.half_n = a.fuse_half_n;
   p.out_f32 = a.out_f32;
   p.sz_vec = sz_vec;
+  // Split reduction: whole scale panels (4 pipeline stages) per range, every range non-empty.
+  int ksp = 1, kspan = a.K_in;
+  if (a.k_splits > 1 && szr && a.out_f32 && !fuse) {
+    const int pan = 4 * ks, npan = a.K_in / pan;
+    const int pps = (npan + a.k_splits - 1) / a.k_splits;
+    ksp = (npan + pps - 1) / pps;
+    kspan = pps * pan;
+  }
+  p.k_splits = ksp; p.k_span = kspan; p.split_stride = (long long)a.num_slots * a.ldc;
+  if (a.used_splits) *a.used_splits = ksp;
   const size_t cap = align_capacity(a.num_slots, a.E, a.block_m);
   // Register-scale kernels can walk several feature tiles per workgroup: aim for at least ~24
   // pipeline stages per workgroup while keeping a few thousand workgroups in the launch.
   int tpw = 1;
   if (szr) {
-    const int nst = a.K_in / ks;
+    const int nst = kspan / ks;
     tpw = (24 + nst - 1) / nst;
     if (tpw > 8) tpw = 8;
     if (tpw > p.n_tiles) tpw = p.n_tiles;
     const long long est_blocks = (a.num_slots + 16 * mt - 1) / (16 * mt) + (a.num_slots < a.E ? a.num_slots : a.E) / 2;
-    while (tpw > 1 && est_blocks * ((p.n_tiles + tpw - 1) / tpw) < 2048) --tpw;
+    while (tpw > 1 && est_blocks * ((p.n_tiles + tpw - 1) / tpw) * ksp < 2048) --tpw;
   }
   if (g_force_tpw > 0) tpw = szr ? (g_force_tpw < p.n_tiles ? g_force_tpw : p.n_tiles) : 1;
   p.tiles_per_wg = tpw;
-  const long long grid = (long long)(cap / (16 * mt)) * ((p.n_tiles + tpw - 1) / tpw);
+  const long long grid = (long long)(cap / (16 * mt)) * ((p.n_tiles + tpw - 1) / tpw) * ksp;
   if (grid > 0x7fffffffLL) return fail(MOE_UNSUPPORTED_SHAPE, "grid too large");
   const int err = v->fn(p, (int)grid, stream);
   if (err != 0) return hip_fail(err, "grouped GEMM launch");
@@ -201,6 +216,21 @@ static int pick_block_m(long long S, int E) {
   if (avg <= 8) return 16;
   if (avg <= 24) return 32;
   return 64;     // 64-slot tiles at two workgroups per CU beat 128-slot tiles (measured)
+}
+
+// Reduction splits of the layer's down projection.  With few experts and few rows the launch has
+// too few workgroups to keep enough loads in flight; cutting the reduction multiplies them (the
+// combine adds the partial planes).  Only for small token tiles: large ones have rows to spare.
+static int pick_k_splits(long long S, int E, int K, int N, int block_m) {
+  if (block_m > 32) return 1;
+  const long long est_blocks = (S + block_m - 1) / block_m + (S < E ? S : E) / 2;
+  const long long wgs = est_blocks * ((K + 127) / 128);
+  if (wgs <= 0 || wgs >= 1024) return 1;
+  long long want = (1536 + wgs - 1) / wgs;
+  const int npan = N / 1024;
+  if (want > npan) want = npan;
+  if (want > 8) want = 8;
+  return want < 1 ? 1 : (int)want;
 }
 
 struct Workspace {
@@ -216,7 +246,8 @@ static Workspace carve(long long T, int K, int N, int E, int topk) {
   w.sorted = o;      o += round_up(align_capacity(S, E, 128) * 4, 256);
   w.blocks = o;      o += round_up((align_capacity(S, E, 16) / 16 + 1) * 4, 256);
   w.act = o;         o += round_up((size_t)S * N * 2, 256);
-  w.Y = o;           o += round_up((size_t)S * K * 4, 256);   // float32: combined unrounded
+  // float32 (combined unrounded); one plane per reduction split (at most 8, small batches only)
+  w.Y = o;           o += round_up((size_t)S * K * 4 * pick_k_splits(S, E, K, N, pick_block_m(S, E)), 256);
   w.total = o;
   return w;
 }
@@ -281,7 +312,7 @@ int moe_combine(const void* Y, const float* topk_weights, void* out, int T, int 
   if (!Y || !topk_weights || !out) return fail(MOE_INVALID_ARGUMENT, "null pointer argument");
   if (K % 8 == 0 && ((uintptr_t)Y | (uintptr_t)out) % 16 != 0)
     return fail(MOE_INVALID_ARGUMENT, "Y and out must be 16-byte aligned");
-  const int err = launch_combine(Y, 0, topk_weights, nullptr, 0, out, T, topk, K, (int)dt, (hipStream_t)stream);
+  const int err = launch_combine(Y, 0, 1, topk_weights, nullptr, 0, out, T, topk, K, (int)dt, (hipStream_t)stream);
   if (err != 0) return hip_fail(err, "combine launch");
   return MOE_OK;
 }
@@ -350,11 +381,18 @@ int moe_w4a16_layer(const void* X, const int32_t* topk_ids, const float* topk_we
   if (ev) (void)hipEventRecord((hipEvent_t)g_events[2], stream);
   GemmArgs g2{act, 1, qw2, s2, z2, sorted, blocks, num_padded, (int)S, E, K, N, group_size, block_m,
               (int)dt, Y, K, 0, 1};
+  // reduction splits: as many partial planes as the caller's workspace holds
+  int want = g_force_ksplit > 0 ? g_force_ksplit : pick_k_splits(S, E, K, N, block_m);
+  const size_t planes_fit = (workspace_bytes - w.Y) / ((size_t)S * K * 4);
+  if ((size_t)want > planes_fit) want = (int)planes_fit;
+  int planes = 1;
+  g2.k_splits = want;
+  g2.used_splits = &planes;
   st = run_gemm(g2, stream);
   if (st != MOE_OK) return st;
 
   if (ev) (void)hipEventRecord((hipEvent_t)g_events[3], stream);
-  err = launch_combine(Y, 1, topk_weights, topk_ids, E, out, T, topk, K, (int)dt, stream);
+  err = launch_combine(Y, 1, planes, topk_weights, topk_ids, E, out, T, topk, K, (int)dt, stream);
   if (err != 0) return hip_fail(err, "combine launch");
   if (ev) (void)hipEventRecord((hipEvent_t)g_events[4], stream);
   return MOE_OK;
@@ -377,6 +415,12 @@ int moe_set_scale_path(int mode) {
 int moe_set_tiles_per_workgroup(int n) {
   if (n < 0 || n > 64) return fail(MOE_INVALID_ARGUMENT, "tiles per workgroup must be in 0..64");
   g_force_tpw = n;
+  return MOE_OK;
+}
+
+int moe_set_reduction_splits(int n) {
+  if (n < 0 || n > 64) return fail(MOE_INVALID_ARGUMENT, "reduction splits must be in 0..64");
+  g_force_ksplit = n;
   return MOE_OK;
 }
 

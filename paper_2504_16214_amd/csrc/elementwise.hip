@@ -43,7 +43,7 @@ silu_mul_kernel(const uint16_t* __restrict__ H, uint16_t* __restrict__ act, long
 template <int DT, int YF32>
 __global__ void __launch_bounds__(256)
 combine_kernel(const void* __restrict__ Yv, const float* __restrict__ w, const int32_t* __restrict__ ids,
-               int E, uint16_t* __restrict__ out, long long T, int topk, int K) {
+               int E, uint16_t* __restrict__ out, long long T, int topk, int K, int planes, long long plane) {
   const uint16_t* Y = reinterpret_cast<const uint16_t*>(Yv);
   const float* Yf = reinterpret_cast<const float*>(Yv);
   const bool vec = (K & 7) == 0;
@@ -63,7 +63,15 @@ combine_kernel(const void* __restrict__ Yv, const float* __restrict__ w, const i
         if constexpr (YF32) {
           const float4 y0 = *reinterpret_cast<const float4*>(Yf + slot * (long long)K + c * 8);
           const float4 y1 = *reinterpret_cast<const float4*>(Yf + slot * (long long)K + c * 8 + 4);
-          const float yv[8] = {y0.x, y0.y, y0.z, y0.w, y1.x, y1.y, y1.z, y1.w};
+          float yv[8] = {y0.x, y0.y, y0.z, y0.w, y1.x, y1.y, y1.z, y1.w};
+          // a split reduction left one partial sum per plane: add them in plane order
+          for (int pl = 1; pl < planes; ++pl) {
+            const float* yp = Yf + pl * plane + slot * (long long)K + c * 8;
+            const float4 a0 = *reinterpret_cast<const float4*>(yp);
+            const float4 a1 = *reinterpret_cast<const float4*>(yp + 4);
+            yv[0] += a0.x; yv[1] += a0.y; yv[2] += a0.z; yv[3] += a0.w;
+            yv[4] += a1.x; yv[5] += a1.y; yv[6] += a1.z; yv[7] += a1.w;
+          }
 #pragma unroll
           for (int k = 0; k < 8; ++k) acc[k] = __builtin_fmaf(wj, yv[k], acc[k]);
         } else {
@@ -86,7 +94,8 @@ combine_kernel(const void* __restrict__ Yv, const float* __restrict__ w, const i
       for (int j = 0; j < topk; ++j) {
         const long long slot = t * topk + j;
         if (ids) { const int e = ids[slot]; if (e < 0 || e >= E) continue; }
-        const float yv = YF32 ? Yf[slot * (long long)K + c] : from_bits16<DT>(Y[slot * (long long)K + c]);
+        float yv = YF32 ? Yf[slot * (long long)K + c] : from_bits16<DT>(Y[slot * (long long)K + c]);
+        if constexpr (YF32) for (int pl = 1; pl < planes; ++pl) yv += Yf[pl * plane + slot * (long long)K + c];
         acc = __builtin_fmaf(w[slot], yv, acc);
       }
       out[t * (long long)K + c] = to_bits16<DT>(acc);
@@ -114,13 +123,14 @@ int launch_silu_mul(const void* H, void* act, long long S, int N, int dt, hipStr
   return (int)hipGetLastError();
 }
 
-int launch_combine(const void* Y, int y_f32, const float* w, const int32_t* ids, int E, void* out,
+int launch_combine(const void* Y, int y_f32, int planes, const float* w, const int32_t* ids, int E, void* out,
                    long long T, int topk, int K, int dt, hipStream_t stream) {
+  const long long plane = T * topk * (long long)K;      // elements per partial-sum plane
   const long long items = T * (((K & 7) == 0) ? (K >> 3) : K);
   if (items == 0) return 0;
   const dim3 grid(grid_for(items)), block(256);
 #define MOE_LAUNCH_COMBINE(DT, F) \
-  hipLaunchKernelGGL((combine_kernel<DT, F>), grid, block, 0, stream, Y, w, ids, E, (uint16_t*)out, T, topk, K)
+  hipLaunchKernelGGL((combine_kernel<DT, F>), grid, block, 0, stream, Y, w, ids, E, (uint16_t*)out, T, topk, K, planes, plane)
   if (dt == kF16) { if (y_f32) MOE_LAUNCH_COMBINE(kF16, 1); else MOE_LAUNCH_COMBINE(kF16, 0); }
   else { if (y_f32) MOE_LAUNCH_COMBINE(kBF16, 1); else MOE_LAUNCH_COMBINE(kBF16, 0); }
 #undef MOE_LAUNCH_COMBINE

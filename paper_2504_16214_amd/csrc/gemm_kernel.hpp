@@ -55,6 +55,9 @@ struct GemmParams {
   int half_n;     // fused SiLU-and-multiply: N (weight rows [0,N) gate, [N,2N) up); else 0
   int sz_vec;     // 1 if scale rows are 16-byte aligned (G % 8 == 0 and aligned base pointers)
   int out_f32;    // 1: C is float32 (the layer's down projection feeds the combine unrounded)
+  int k_splits;   // > 1: the reduction is cut into k_splits ranges of k_span indices, one workgroup each;
+  int k_span;     //      split i writes its partial sums to the float32 plane C + i * split_stride
+  long long split_stride;   // elements between planes (register-scale kernels with out_f32 only)
   int tiles_per_wg;  // consecutive feature tiles one workgroup walks (1 unless SZR)
 };
 
@@ -111,7 +114,7 @@ __device__ __forceinline__ uint32_t vgpr_const(uint32_t v) {
 }
 struct UnpackConsts {
   uint32_t or_hi;   // fp16: 0x64006400 (1024.0 pair)   bf16: 0x43004300 (128.0 pair)
-  uint32_t or_lo;   // fp16: 0x54005400 (64.0 pair)     bf16: unused
+  uint32_t or_lo;   // fp16: 0x54005400 (64.0 pair)     bf16: 0xC300C300 (-128.0 pair, zero-point operand)
 };
 
 template <int DT, int ZM>
@@ -126,6 +129,22 @@ template <int ZM>
 struct DeqCtx<kF16, ZM> {
   uint32_t zA, zB;   // packed pairs: (-)(1024 + z) and (-)(64 + z)
   float s;
+  DeqCtx() = default;
+  // Straight from the register-resident panel: zreg holds the zero points of four groups (one
+  // per byte), z4reg the same shifted left by four, sreg two fp16 scales.  One byte permute per
+  // constant: byte gq of zreg under the exponent byte of 1024.0 (or of 64.0, mantissa bits 4..7).
+  // (gp is a constant after unrolling, so the selector is a scalar literal.)
+  __device__ __forceinline__ static DeqCtx from_panel(int gp, uint32_t sreg, uint32_t zreg, uint32_t z4reg,
+                                                      const UnpackConsts& k) {
+    static_assert(ZM == 0, "fp16 uses the packed subtract");
+    const uint32_t sel = 0x05000500u | ((uint32_t)(gp & 3) << 16) | (uint32_t)(gp & 3);
+    DeqCtx c;
+    c.zA = __builtin_amdgcn_perm(k.or_hi, zreg, sel);
+    c.zB = __builtin_amdgcn_perm(k.or_lo, z4reg, sel);
+    c.s = (float)__builtin_bit_cast(_Float16, (uint16_t)((gp & 1) ? (sreg >> 16) : (sreg & 0xffffu)));
+    return c;
+  }
+  __device__ __forceinline__ uint32_t zero_point() const { return zA & 0xfu; }
   __device__ __forceinline__ explicit DeqCtx(uint32_t e) {
     zA = __builtin_amdgcn_perm(e, e, 0x07060706u);                       // (hi16, hi16)
     zB = ((zA & 0x000F000Fu) << 4) | (ZM ? 0xD400D400u : 0x54005400u);   // z moved to mantissa bits 4..7
@@ -138,6 +157,17 @@ template <int ZM>
 struct DeqCtx<kBF16, ZM> {
   uint32_t zA;       // ZM: packed pair -(128 + z) as bf16
   float zc, s;
+  DeqCtx() = default;
+  __device__ __forceinline__ static DeqCtx from_panel(int gp, uint32_t sreg, uint32_t zreg, uint32_t /*z4reg*/,
+                                                      const UnpackConsts& k) {
+    const uint32_t sel = 0x05000500u | ((uint32_t)(gp & 3) << 16) | (uint32_t)(gp & 3);
+    DeqCtx c;
+    c.zA = __builtin_amdgcn_perm(k.or_lo, zreg, sel);       // or_lo = 0xC300C300: -(128 + z) pairs
+    c.zc = 128.0f + (float)((zreg >> (8 * (gp & 3))) & 0xffu);
+    c.s = __builtin_bit_cast(float, (gp & 1) ? (sreg & 0xffff0000u) : (sreg << 16));
+    return c;
+  }
+  __device__ __forceinline__ uint32_t zero_point() const { return zA & 0xfu; }
   __device__ __forceinline__ explicit DeqCtx(uint32_t e) {
     s = __builtin_bit_cast(float, e & 0xffff0000u);
     zc = 128.0f + (float)(e & 0xffu);
@@ -341,8 +371,11 @@ w4a16_gemm_kernel(const GemmParams p) {
   // starting a workgroup is paid once per several tiles when the reduction is short.
   const int tpw = SZR ? p.tiles_per_wg : 1;
   const int tgroups = (p.n_tiles + tpw - 1) / tpw;
-  const int L = xcd_contiguous_index(blockIdx.x, (*p.num_padded / M_T) * tgroups);
+  const int ksp = SZR ? p.k_splits : 1;
+  int L = xcd_contiguous_index(blockIdx.x, (*p.num_padded / M_T) * tgroups * ksp);
   if (L < 0) return;
+  const int split = L % ksp;        // neighbouring workgroups take the ranges of one tile
+  L /= ksp;
   const int tile0 = (L % tgroups) * tpw;
   const int ntl = p.n_tiles - tile0 < tpw ? p.n_tiles - tile0 : tpw;     // tiles this workgroup walks
   const int row0 = (L / tgroups) * M_T;
@@ -353,9 +386,12 @@ w4a16_gemm_kernel(const GemmParams p) {
   const int ln = lane & 15, lj = lane >> 4;
   UnpackConsts uk;
   uk.or_hi = vgpr_const(DT == kF16 ? 0x64006400u : 0x43004300u);
-  uk.or_lo = vgpr_const(0x54005400u);
+  uk.or_lo = vgpr_const(DT == kF16 ? 0x54005400u : 0xC300C300u);
   unsigned char* wsw = ws_all + wave * NW * WP;
-  const int K_in = p.K_in;
+  const int K_in = p.K_in;                          // row stride of A and of the packed weights
+  // reduction range of this workgroup: [k0, k0 + K_ext); the whole row unless the launch splits it
+  const int k0 = ksp > 1 ? split * p.k_span : 0;
+  const int K_ext = ksp > 1 ? (K_in - k0 < p.k_span ? K_in - k0 : p.k_span) : K_in;
 
   // ---- per-thread global addresses ------------------------------------------------
   // Every load address is (workgroup-uniform 64-bit base) + (32-bit per-lane byte offset): the
@@ -364,7 +400,7 @@ w4a16_gemm_kernel(const GemmParams p) {
   // N_out and reduction chunks past K_in are redirected to a valid address; what they fetch
   // only ever reaches output rows / columns that are not stored, or chunk-steps that are not
   // executed.  (The host checks that one expert's weights and the A matrix stay below 2 GiB.)
-  const unsigned char* const xbase = reinterpret_cast<const unsigned char*>(p.A);
+  const unsigned char* const xbase = reinterpret_cast<const unsigned char*>(p.A) + (size_t)k0 * 2;
   uint32_t xoff[XPASS];
   const int xr_row = tid / CPR, xr_chunk = tid % CPR;
   // LDS position of the thread's 16-byte chunk: transposed inside its chunk-step (4*KW chunks)
@@ -376,7 +412,7 @@ w4a16_gemm_kernel(const GemmParams p) {
     xoff[ps] = arow * (uint32_t)(K_in * 2) + (uint32_t)(xr_chunk * 16);
   }
   const unsigned char* const wbase =
-      reinterpret_cast<const unsigned char*>(p.qweight) + (size_t)e * p.N_out * (size_t)(K_in >> 1);
+      reinterpret_cast<const unsigned char*>(p.qweight) + (size_t)e * p.N_out * (size_t)(K_in >> 1) + (size_t)(k0 >> 1);
   uint32_t woff[WPASS];      // rows of the tile the LOAD cursor is in
   const int wl_row = lane / LPR, wl_chunk = lane % LPR;
   auto set_w_rows = [&](int tile) {
@@ -393,11 +429,12 @@ w4a16_gemm_kernel(const GemmParams p) {
   set_w_rows(tile0);
   // K tail (K_in % KS != 0): in the last stage, chunks past K_in step back onto the row's last
   // valid 16 bytes.  wback / xback are the per-lane byte distances; zero when there is no tail.
-  const int nst = (K_in + KS - 1) / KS;
-  const bool has_tail = (K_in % KS) != 0;
+  const int nst = (K_ext + KS - 1) / KS;
+  // (register-scale kernels only run on reductions of whole 4-stage panels: never a tail)
+  const bool has_tail = SZR ? false : (K_ext % KS) != 0;
   uint32_t wback = 0, xback = 0;
   if (has_tail) {
-    const int tail_k = K_in - (nst - 1) * KS;            // valid reduction indices of the last stage
+    const int tail_k = K_ext - (nst - 1) * KS;           // valid reduction indices of the last stage
     const int wmax = tail_k / 2 - 16, xmax = tail_k * 2 - 16;
     wback = wl_chunk * 16 > wmax ? (uint32_t)(wl_chunk * 16 - wmax) : 0u;
     xback = xr_chunk * 16 > xmax ? (uint32_t)(xr_chunk * 16 - xmax) : 0u;
@@ -422,10 +459,17 @@ w4a16_gemm_kernel(const GemmParams p) {
     const unsigned char* xb_ = xbase + (size_t)stc_ * (KS * 2);                                 \
     uint32_t wsub_ = 0, xsub_ = 0;                                                              \
     if (has_tail && stc_ == nst - 1) { wsub_ = wback; xsub_ = xback; }                          \
-    _Pragma("unroll") for (int q = 0; q < WPASS; ++q)                                           \
-        WV[q] = load_weights<(MT <= 2)>(wb_ + (woff[q] - wsub_));                               \
-    _Pragma("unroll") for (int ps = 0; ps < XPASS; ++ps)                                        \
-        XV[ps] = *reinterpret_cast<const u32x4*>(xb_ + (xoff[ps] - xsub_));                     \
+    /* The per-lane offsets pass through an empty asm so that they stay opaque 32-bit VGPR  */ \
+    /* values: the loads then take the scalar-base + 32-bit-offset form instead of 64-bit   */ \
+    /* per-lane addresses (which cost two registers per load and VALU adds per stage).      */ \
+    _Pragma("unroll") for (int q = 0; q < WPASS; ++q) {                                         \
+      asm("" : "+v"(woff[q]));                                                                  \
+      WV[q] = load_weights<(MT <= 2)>(wb_ + (woff[q] - wsub_));                                 \
+    }                                                                                           \
+    _Pragma("unroll") for (int ps = 0; ps < XPASS; ++ps) {                                      \
+      asm("" : "+v"(xoff[ps]));                                                                 \
+      XV[ps] = *reinterpret_cast<const u32x4*>(xb_ + (xoff[ps] - xsub_));                       \
+    }                                                                                           \
   }
 #define MOE_STORE_STAGE(XV, WV, XBUF)                                                           \
   {                                                                                             \
@@ -467,9 +511,20 @@ w4a16_gemm_kernel(const GemmParams p) {
   constexpr int PG = SZR ? UNR * UCH : 8;          // groups per panel
   uint32_t s_cur[NT][PG / 2], s_nxt[NT][PG / 2];
   uint32_t z_cur[NT][(PG + 3) / 4], z_nxt[NT][(PG + 3) / 4];
+  uint32_t z4_cur[NT][(PG + 3) / 4];               // z_cur with every byte shifted left by four
+  auto adopt_zero_points = [&](const uint32_t(&zv)[NT][(PG + 3) / 4]) {
+#pragma unroll
+    for (int s = 0; s < NT; ++s)
+#pragma unroll
+      for (int i = 0; i < (PG + 3) / 4; ++i) {
+        z_cur[s][i] = zv[s][i] & 0x0f0f0f0fu;      // zero points are 4-bit by contract
+        z4_cur[s][i] = z_cur[s][i] << 4;
+      }
+  };
   uint32_t sz_row[NT];                             // element offset of the lane's row (host checks the range)
+  const int G_ext = ksp > 1 ? K_ext / 128 : p.G;   // groups in the reduction range (SZR: group 128)
   auto load_sz = [&](int g0, uint32_t(&sv)[NT][PG / 2], uint32_t(&zv)[NT][(PG + 3) / 4]) {
-    if (g0 > p.G - PG) g0 = p.G - PG;               // clamp onto the last panel
+    if (g0 > G_ext - PG) g0 = G_ext - PG;           // clamp onto the last panel of the range
 #pragma unroll
     for (int s = 0; s < NT; ++s) {
       const uint16_t* sp = reinterpret_cast<const uint16_t*>(p.scales) + sz_row[s] + g0;
@@ -493,14 +548,15 @@ w4a16_gemm_kernel(const GemmParams p) {
       bool ok;
       feature_of<NT, FUSE>(tile, wave, s, ln, p, wrow, ocol, ok);
       if (!ok) wrow = 0;
-      sz_row[s] = ((uint32_t)e * (uint32_t)p.N_out + (uint32_t)wrow) * (uint32_t)p.G;
+      sz_row[s] = ((uint32_t)e * (uint32_t)p.N_out + (uint32_t)wrow) * (uint32_t)p.G + (uint32_t)(k0 / 128);
     }
   };
   int sp_t = 0, sp_pan = 1;          // panel cursor: tile (local) and panel of the next prefetch
   const int npan = nst_pad / UNR;
   if constexpr (SZR) {
     set_sz_rows(tile0);
-    load_sz(0, s_cur, z_cur);
+    load_sz(0, s_cur, z_nxt);
+    adopt_zero_points(z_nxt);
     if (npan == 1) { sp_pan = 0; sp_t = 1; if (sp_t < ntl) set_sz_rows(tile0 + sp_t); }
   }
 
@@ -553,24 +609,24 @@ w4a16_gemm_kernel(const GemmParams p) {
 
   auto compute_stage = [&](int st, const unsigned char* xbuf, auto rc) {
     constexpr int R = decltype(rc)::value;       // step index inside the unrolled trip
-    const int left = (K_in - st * KS) / CK;      // <= 0 for a stage past the end
-    const int nu = left < UCH ? left : UCH;
+    const int left = (K_ext - st * KS) / CK;     // <= 0 for a stage past the end
+    // (the run-time bound also keeps the chunk-steps apart for the scheduler: with a constant bound
+    // it interleaves them and needs ~40 more registers, which costs a workgroup per CU)
+    const int nu = left < UCH ? left : UCH;   // SZR: whole panels, no partial or dead stage
 #pragma unroll
     for (int u = 0; u < UCH; ++u) {
       if (u >= nu) break;
       const int cc = st * UCH + u;
       const int gi = p.cpg == 1 ? cc : cc / p.cpg;
       WordVec<KW> wv[NT];
-      uint32_t ent[NT];
+      DeqCtx<DT, ZM> ctx[NT];
 #pragma unroll
       for (int s = 0; s < NT; ++s) {
         if constexpr (SZR) {
           const int gp = (UCH * R + u) % PG;   // group inside the panel: constant after unrolling
-          const uint32_t sbits = (s_cur[s][gp >> 1] >> (16 * (gp & 1))) & 0xffffu;
-          const uint32_t zb = (z_cur[s][gp >> 2] >> (8 * (gp & 3))) & 0xffu;
-          ent[s] = pack_sz_entry<DT, ZM>((uint16_t)sbits, (uint8_t)zb);
+          ctx[s] = DeqCtx<DT, ZM>::from_panel(gp, s_cur[s][gp >> 1], z_cur[s][gp >> 2], z4_cur[s][gp >> 2], uk);
         } else {
-          ent[s] = sz[gi * N_T + wave * NW + s * 16 + ln];
+          ctx[s] = DeqCtx<DT, ZM>(sz[gi * N_T + wave * NW + s * 16 + ln]);
         }
         wv[s] = lds_read_words<KW>(wsw + (s * 16 + ln) * WP + 16 * KW * u + 4 * KW * lj);
       }
@@ -578,9 +634,8 @@ w4a16_gemm_kernel(const GemmParams p) {
       float scl[NT];
 #pragma unroll
       for (int s = 0; s < NT; ++s) {
-        const DeqCtx<DT, ZM> c(ent[s]);
-        scl[s] = c.s;
-        if constexpr (ZM) zop[s] = c.zoperand();
+        scl[s] = ctx[s].s;
+        if constexpr (ZM) zop[s] = ctx[s].zoperand();
       }
       if constexpr (RS) {
         bool zero_scale[NT];
@@ -600,7 +655,7 @@ w4a16_gemm_kernel(const GemmParams p) {
 #pragma unroll
           for (int s = 0; s < NT; ++s) {
             // q == z everywhere: the subtract (or the zero-point MFMA) cancels it exactly
-            const uint32_t zword = ((ent[s] >> (DT == kF16 ? 16 : 0)) & 0xfu) * 0x11111111u;
+            const uint32_t zword = ctx[s].zero_point() * 0x11111111u;
 #pragma unroll
             for (int i = 0; i < KW; ++i) wv[s].w[i] = zero_scale[s] ? zword : wv[s].w[i];
           }
@@ -609,7 +664,7 @@ w4a16_gemm_kernel(const GemmParams p) {
         for (int i = 0; i < KW; ++i) {
           u32x4 b[NT];
 #pragma unroll
-          for (int s = 0; s < NT; ++s) b[s] = dequant_word<DT, ZM>(wv[s].w[i], DeqCtx<DT, ZM>(ent[s]), uk);
+          for (int s = 0; s < NT; ++s) b[s] = dequant_word<DT, ZM>(wv[s].w[i], ctx[s], uk);
 #pragma unroll
           for (int mt = 0; mt < MT; ++mt) {
             const u32x4 a = *reinterpret_cast<const u32x4*>(
@@ -636,7 +691,7 @@ w4a16_gemm_kernel(const GemmParams p) {
         for (int i = 0; i < KW; ++i) {
           u32x4 b[NT];
 #pragma unroll
-          for (int s = 0; s < NT; ++s) b[s] = dequant_word<DT, ZM>(wv[s].w[i], DeqCtx<DT, ZM>(ent[s]), uk);
+          for (int s = 0; s < NT; ++s) b[s] = dequant_word<DT, ZM>(wv[s].w[i], ctx[s], uk);
 #pragma unroll
           for (int mt = 0; mt < MT; ++mt) {
             const u32x4 a = *reinterpret_cast<const u32x4*>(
@@ -688,7 +743,7 @@ w4a16_gemm_kernel(const GemmParams p) {
             int wrow, ocol; bool ok;
             feature_of<NT, FUSE>(tile, wave, s, ln, p, wrow, ocol, ok);
             if (ok) {
-              if (p.out_f32) reinterpret_cast<float*>(p.C)[(size_t)slot * p.ldc + ocol] = acc[mt][s][i];
+              if (p.out_f32) (reinterpret_cast<float*>(p.C) + (size_t)split * p.split_stride)[(size_t)slot * p.ldc + ocol] = acc[mt][s][i];
               else crow[ocol] = to_bits16<DT>(acc[mt][s][i]);
             }
           }
@@ -747,9 +802,8 @@ w4a16_gemm_kernel(const GemmParams p) {
       for (int s = 0; s < NT; ++s) {
 #pragma unroll
         for (int i = 0; i < PG / 2; ++i) s_cur[s][i] = s_nxt[s][i];
-#pragma unroll
-        for (int i = 0; i < (PG + 3) / 4; ++i) z_cur[s][i] = z_nxt[s][i];
       }
+      adopt_zero_points(z_nxt);
     }
     c_st += UNR;
     if (c_st == nst_pad) {

@@ -61,6 +61,13 @@ def test_workspace_covers_tables_and_intermediates(binding):
     assert need >= S * N * 2 + S * K * 4 + O.align_capacity(T, topk, E, 128) * 4
     assert need < 2 * (S * N * 2 + S * K * 4) + (1 << 22)
     assert binding.moe_w4a16_layer_workspace_bytes(-1, K, N, E, topk, 0) == 0
+    # an empty batch still has a (table-only) workspace size
+    assert 0 < binding.moe_w4a16_layer_workspace_bytes(0, K, N, E, topk, 0) < (1 << 20)
+    # few experts, few rows, long reduction: room for several partial planes of the down projection
+    T, K, N, E, topk = 64, 4096, 14336, 8, 2
+    S = T * topk
+    need = binding.moe_w4a16_layer_workspace_bytes(T, K, N, E, topk, 0)
+    assert S * N * 2 + 2 * S * K * 4 <= need <= S * N * 2 + 8 * S * K * 4 + (1 << 20)
 
 
 def test_layer_block_choice_tracks_rows_per_expert(binding):

@@ -264,6 +264,38 @@ def test_layer_matches_oracle_elementwise(cfg):
     U.assert_close(U.dev_to_f64(out), oracle_layer(inp), f"layer {cfg.name}")
 
 
+@pytest.mark.parametrize("N,splits", [(2048, 2), (3072, 2), (3072, 3), (3072, 8), (5120, 0), (5120, 3)])
+@pytest.mark.parametrize("tile", [(1, 2), (2, 2), (4, 2)])
+def test_layer_with_split_reduction(N, splits, tile):
+    """The down projection's reduction cut into ranges (partial float32 planes added by the
+    combine): even and ragged ranges, more splits than scale panels, the automatic choice."""
+    cfg = MoEConfig("ksplit", T=20, K=256, N=N, E=3, topk=2, group=128, dtype="f16", seed=21)
+    say(f"layer reduction splits={splits} tile={tile} {cfg}")
+    inp = make_inputs(cfg)
+    M.moe_set_reduction_splits(splits)
+    M.moe_set_tile_override(*tile)
+    try:
+        out = U.run_layer(U.DevInputs(inp))
+    finally:
+        M.moe_set_reduction_splits(0)
+        M.moe_set_tile_override(0, 0)
+    U.assert_close(U.dev_to_f64(out), oracle_layer(inp), f"layer split {N}/{splits}")
+
+
+def test_layer_split_reduction_limited_by_workspace():
+    """More splits requested than partial planes fit in the workspace (large token tiles reserve
+    one plane): the layer uses what fits and the result is unchanged."""
+    cfg = MoEConfig("ksplit_ws", T=200, K=256, N=3072, E=2, topk=1, group=128, dtype="f16", seed=22)
+    say(f"layer reduction splits vs workspace {cfg}")
+    inp = make_inputs(cfg)
+    M.moe_set_reduction_splits(3)
+    try:
+        out = U.run_layer(U.DevInputs(inp))
+    finally:
+        M.moe_set_reduction_splits(0)
+    U.assert_close(U.dev_to_f64(out), oracle_layer(inp), "layer split vs workspace")
+
+
 def test_layer_with_invalid_expert_ids_contributes_zero():
     cfg = MoEConfig("inv_layer", T=24, K=256, N=128, E=6, topk=3, group=128, dtype="f16", seed=9)
     say(f"layer invalid ids {cfg}")
