@@ -489,7 +489,10 @@ w4a16_gemm_kernel(const GemmParams p) {
   int ld_t = 0, ld_st = 0;          // LOAD cursor: tile (local) and stage of the next stage to fetch
 #define MOE_ADVANCE_LOAD_CURSOR()                                   \
   {                                                                 \
-    if (++ld_st == nst_pad) {                                       \
+    if (__builtin_expect(++ld_st == nst_pad, 0)) {                  \
+      /* once per tile: the empty asm keeps this a real (scalar) branch; if-converted it     */ \
+      /* costs ~24 VALU instructions in every stage                                          */ \
+      asm volatile("");                                             \
       ld_st = 0;                                                    \
       if (++ld_t < ntl) {                                           \
         set_w_rows(tile0 + ld_t);                                   \
@@ -781,7 +784,8 @@ w4a16_gemm_kernel(const GemmParams p) {
     if constexpr (SZR) {
       // prefetch the scales / zero points of the next panel (possibly of the next tile)
       load_sz(sp_pan * PG, s_nxt, z_nxt);
-      if (++sp_pan == npan) {
+      if (__builtin_expect(++sp_pan == npan, 0)) {
+        asm volatile("");      // a real branch, taken once per tile
         sp_pan = 0;
         if (++sp_t < ntl) set_sz_rows(tile0 + sp_t);
       }
