@@ -440,32 +440,41 @@ w4a16_gemm_kernel(const GemmParams p) {
     xback = xr_chunk * 16 > xmax ? (uint32_t)(xr_chunk * 16 - xmax) : 0u;
   }
 
-  // Register prefetch ring: PD slots, loads issued PD stages ahead (all indices are compile-time
-  // constants after unrolling, so the ring stays in VGPRs).  Deeper rings were measured slower
-  // on the decode shapes: the K loops are short and the extra dead steps at the end cost more
-  // than the additional bytes in flight gain.  Large token tiles spend several microseconds per
-  // stage, one stage of flight time covers the memory latency and the second slot's registers
-  // are worth more to the compiler (no spills at 64x256).
-  constexpr int PD = MT >= 4 ? 1 : 2;
+  // Register prefetch rings (all slot indices are compile-time constants after unrolling, so the
+  // rings stay in VGPRs).  Weights come from HBM: their loads are issued PDW stages ahead.
+  // Activations come from L2 (every feature tile of a block re-reads them): PDX stages ahead.
+  // Small token tiles: two stages ahead.  Four-deep weight rings (with two- or four-deep
+  // activation rings) were measured 4-8 % slower on the decode shapes: the extra 32-48 registers
+  // cost a workgroup per CU at 16x128 tiles and buy nothing at 32x128, where occupancy is the same.
+  // Large token tiles spend several microseconds per stage, one stage of flight time is enough
+  // and the registers are worth more to the compiler (no spills at 64x256).
   constexpr int UNR = SZR ? 4 : 2;      // steps per loop trip (one 1024-k scale panel when SZR)
-  u32x4 xr[PD][XPASS], wr[PD][WPASS];
-#define MOE_LOAD_STAGE(ST, XV, WV)                                                              \
+  constexpr int PDW = MT >= 4 ? 1 : 2;
+  constexpr int PDX = MT >= 4 ? 1 : 2;
+  static_assert(UNR % PDW == 0 && UNR % PDX == 0, "ring slots must repeat with the unrolled trip");
+  u32x4 xr[PDX][XPASS], wr[PDW][WPASS];
+  // A stage past the end still issues its loads (onto the last stage, which was just fetched) so
+  // the loop body is branch-free and the compiler can count the outstanding loads exactly.
+  // The per-lane offsets pass through an empty asm so that they stay opaque 32-bit VGPR values:
+  // the loads then take the scalar-base + 32-bit-offset form instead of 64-bit per-lane addresses
+  // (which cost two registers per load and VALU adds per stage).
+#define MOE_LOAD_W(ST, WV)                                                                      \
   {                                                                                             \
-    /* A stage past the end still issues its loads (onto the last stage, which was just      */ \
-    /* fetched) so the loop body is branch-free and the compiler can count the outstanding   */ \
-    /* loads exactly.                                                                        */ \
     const int stc_ = (ST) < nst ? (ST) : nst - 1;                                               \
     const unsigned char* wb_ = wbase + (size_t)stc_ * (KS / 2);                                 \
-    const unsigned char* xb_ = xbase + (size_t)stc_ * (KS * 2);                                 \
-    uint32_t wsub_ = 0, xsub_ = 0;                                                              \
-    if (has_tail && stc_ == nst - 1) { wsub_ = wback; xsub_ = xback; }                          \
-    /* The per-lane offsets pass through an empty asm so that they stay opaque 32-bit VGPR  */ \
-    /* values: the loads then take the scalar-base + 32-bit-offset form instead of 64-bit   */ \
-    /* per-lane addresses (which cost two registers per load and VALU adds per stage).      */ \
+    uint32_t wsub_ = 0;                                                                         \
+    if (has_tail && stc_ == nst - 1) wsub_ = wback;                                             \
     _Pragma("unroll") for (int q = 0; q < WPASS; ++q) {                                         \
       asm("" : "+v"(woff[q]));                                                                  \
       WV[q] = load_weights<(MT <= 2)>(wb_ + (woff[q] - wsub_));                                 \
     }                                                                                           \
+  }
+#define MOE_LOAD_X(ST, XV)                                                                      \
+  {                                                                                             \
+    const int stc_ = (ST) < nst ? (ST) : nst - 1;                                               \
+    const unsigned char* xb_ = xbase + (size_t)stc_ * (KS * 2);                                 \
+    uint32_t xsub_ = 0;                                                                         \
+    if (has_tail && stc_ == nst - 1) xsub_ = xback;                                             \
     _Pragma("unroll") for (int ps = 0; ps < XPASS; ++ps) {                                      \
       asm("" : "+v"(xoff[ps]));                                                                 \
       XV[ps] = *reinterpret_cast<const u32x4*>(xb_ + (xoff[ps] - xsub_));                       \
@@ -486,8 +495,9 @@ w4a16_gemm_kernel(const GemmParams p) {
   // Flattened step index over (tile, stage).  nst_pad rounds the stages of a tile up to whole
   // trips; stages in [nst, nst_pad) are dead (clamped loads, no compute).
   const int nst_pad = (nst + UNR - 1) / UNR * UNR;
-  int ld_t = 0, ld_st = 0;          // LOAD cursor: tile (local) and stage of the next stage to fetch
-#define MOE_ADVANCE_LOAD_CURSOR()                                   \
+  int ld_t = 0, ld_st = 0;          // weight LOAD cursor: tile (local) and stage of the next stage to fetch
+  int lx_st = 0;                    // activation LOAD cursor: stage only (every tile reads the same rows)
+#define MOE_ADVANCE_W_CURSOR()                                      \
   {                                                                 \
     if (__builtin_expect(++ld_st == nst_pad, 0)) {                  \
       /* once per tile: the empty asm keeps this a real (scalar) branch; if-converted it     */ \
@@ -502,10 +512,17 @@ w4a16_gemm_kernel(const GemmParams p) {
       }                                                             \
     }                                                               \
   }
+#define MOE_ADVANCE_X_CURSOR() { if (++lx_st == nst_pad) lx_st = 0; }
 #pragma unroll
-  for (int r = 0; r < PD; ++r) {
-    MOE_LOAD_STAGE(ld_st, xr[r], wr[r])
-    MOE_ADVANCE_LOAD_CURSOR()
+  for (int r = 0; r < (PDW > PDX ? PDW : PDX); ++r) {
+    if (r < PDX) {
+      MOE_LOAD_X(lx_st, xr[r])
+      MOE_ADVANCE_X_CURSOR()
+    }
+    if (r < PDW) {
+      MOE_LOAD_W(ld_st, wr[r])
+      MOE_ADVANCE_W_CURSOR()
+    }
   }
 
   // ---- register-resident scales / zero points (SZR) -----------------------------------
@@ -793,10 +810,14 @@ w4a16_gemm_kernel(const GemmParams p) {
     [&]<int... Rs>(std::integer_sequence<int, Rs...>) {
       (([&] {
          constexpr int r = Rs;
-         MOE_LOAD_STAGE(ld_st, xr[r % PD], wr[r % PD])
-         MOE_ADVANCE_LOAD_CURSOR()
+         // activations first: the wait for them (loads complete in issue order) then leaves the
+         // younger weight loads of PDW - PDX + 1 stages in flight
+         MOE_LOAD_X(lx_st, xr[r % PDX])
+         MOE_ADVANCE_X_CURSOR()
+         MOE_LOAD_W(ld_st, wr[r % PDW])
+         MOE_ADVANCE_W_CURSOR()
          compute_stage(c_st + r, xs + (r % 2) * (M_T * XP), std::integral_constant<int, r>{});
-         MOE_STORE_STAGE(xr[(r + 1) % PD], wr[(r + 1) % PD], xs + ((r + 1) % 2) * (M_T * XP))
+         MOE_STORE_STAGE(xr[(r + 1) % PDX], wr[(r + 1) % PDW], xs + ((r + 1) % 2) * (M_T * XP))
          __syncthreads();
        }()),
        ...);
@@ -816,9 +837,11 @@ w4a16_gemm_kernel(const GemmParams p) {
       ++c_t;
     }
   }
-#undef MOE_LOAD_STAGE
+#undef MOE_LOAD_W
+#undef MOE_LOAD_X
 #undef MOE_STORE_STAGE
-#undef MOE_ADVANCE_LOAD_CURSOR
+#undef MOE_ADVANCE_W_CURSOR
+#undef MOE_ADVANCE_X_CURSOR
 }
 
 // Host-side launcher, one per instantiation.  Returns hipError_t as int.
