@@ -31,7 +31,9 @@ move between value space and raw uint16 patterns.
 Parity pins (tests/test_oracle_*.py): exact rational brute force on tiny
 shapes, pack/unpack round trip and the 0x76543210 vector, all-zero nibbles
 => -z*s, one-hot routing => dense GEMM chain, E=1 => dense MLP, top-k weights
-sum to one, token permutation equivariance (bit-identical), W2-scale doubling
+sum to one, top-k against a scalar selection loop and (k = E) a library softmax,
+the dense GEMM against a closed form and an independent dequantisation,
+token permutation equivariance (bit-identical), W2-scale doubling
 doubles the output, combine linearity, rounding against NumPy's fp16 cast,
 PyTorch's bf16 cast and hand-derived tie cases.  The paper prints no worked
 numeric example for this operator, so there is no paper-valued fixture.
@@ -131,9 +133,15 @@ def dequant(qweight, scales, zeros, group: int) -> np.ndarray:
 # --------------------------------------------------------------------------
 # routing weights (input preparation; kept here to pin the generator's router)
 # --------------------------------------------------------------------------
-def route_topk(logits, topk: int):
+def route_topk(logits, topk: int, bias=None):
     """Top-k experts per token (descending logit, ties to the lower index) and the
-    full softmax renormalised over the selected experts, in float64."""
+    full softmax renormalised over the selected experts, in float64.
+
+    `bias` [E] (optional) is added to every token's logits first, in float32 with one
+    rounding per element (router logits and the per-expert bias are float32 tensors);
+    everything after that is exact comparisons and float64 arithmetic."""
+    if bias is not None:
+        logits = np.asarray(logits, dtype=np.float32) + np.asarray(bias, dtype=np.float32)[None, :]
     logits = np.asarray(logits, dtype=np.float64)
     T, E = logits.shape
     ids = np.empty((T, topk), dtype=np.int32)
@@ -216,6 +224,16 @@ def grouped_gemm(A, row_div: int, qweight, scales, zeros, slot_expert, group: in
     if dt is not None:
         C = np.where(np.isnan(C), C, rnd(C, dt))
     return C
+
+
+def dense_gemm(A, qweight, scales, zeros, group: int, dt=None) -> np.ndarray:
+    """The plain FP16xINT4 GEMM of Section II-C / Fig. 4(b): C = A @ W^T with
+    W[n, k] = (q[n, k] - z[n, k // g]) * s[n, k // g].  A [M, K] float64 values,
+    qweight [N, K/8], scales float64 values [N, K/g], zeros [N, K/g].  float64
+    accumulation, one rounding to dt (None keeps float64)."""
+    W = dequant(qweight, scales, zeros, group)                    # [N, K]
+    C = np.asarray(A, dtype=np.float64) @ W.T
+    return C if dt is None else rnd(C, dt)
 
 
 def gemm_entry(A, row_div: int, qweight, scales, zeros, slot_expert, group: int,

@@ -181,6 +181,81 @@ def test_router_generator_matches_oracle_and_sums_to_one():
     np.testing.assert_allclose(w_o, p / p.sum(axis=1, keepdims=True), rtol=1e-13)
 
 
+def test_router_against_scalar_selection_and_library_softmax():
+    """ids: repeated arg-max with the tie rule written out as a scalar loop; weights for k = E:
+    scipy's softmax; k = 1: exactly one; invariance under a common shift of the logits."""
+    from scipy.special import softmax
+    rng = np.random.default_rng(6)
+    T, E, k = 30, 24, 5
+    logits = rng.standard_normal((T, E)).astype(np.float32)
+    logits[0, :] = 0.25                                   # all equal: ids 0..k-1
+    logits[1, 7] = logits[1, 3] = 9.0                     # tie for the first place
+    logits[2, 5] = -0.0; logits[2, 6] = 0.0; logits[2, [0, 1, 2, 3, 4]] = -1.0   # signed zeros compare equal
+    logits[2, 7:] = -2.0
+    ids, w = O.route_topk(logits, k)
+    for t in range(T):
+        taken, want = set(), []
+        for _ in range(k):
+            best = None
+            for e in range(E):
+                if e in taken:
+                    continue
+                if best is None or float(logits[t, e]) > float(logits[t, best]):
+                    best = e                               # strict '>' keeps the lower index on ties
+            taken.add(best); want.append(best)
+        assert list(ids[t]) == want, (t, list(ids[t]), want)
+    assert list(ids[0]) == [0, 1, 2, 3, 4] and list(ids[1][:2]) == [3, 7] and list(ids[2][:2]) == [5, 6]
+    ids_all, w_all = O.route_topk(logits, E)
+    full = softmax(logits.astype(np.float64), axis=1)
+    np.testing.assert_allclose(w_all, np.take_along_axis(full, ids_all.astype(np.int64), axis=1), rtol=1e-12)
+    ids1, w1 = O.route_topk(logits, 1)
+    assert np.all(w1 == 1.0) and np.array_equal(ids1[:, 0], ids[:, 0])
+    ids_s, w_s = O.route_topk(logits.astype(np.float64) + 3.0, k)
+    np.testing.assert_array_equal(ids_s, ids)
+    np.testing.assert_allclose(w_s, w, rtol=1e-12)
+
+
+def test_router_bias_is_added_in_float32():
+    rng = np.random.default_rng(7)
+    logits = rng.standard_normal((12, 16)).astype(np.float32)
+    bias = skew_bias(16)
+    ids_b, w_b = O.route_topk(logits, 3, bias=bias)
+    ids_r, w_r = O.route_topk((logits + bias[None, :]).astype(np.float32), 3)
+    np.testing.assert_array_equal(ids_b, ids_r)
+    np.testing.assert_array_equal(w_b, w_r)
+    # mutation check: adding the bias in float64 instead changes at least the weights' last bits
+    ids_m, w_m = O.route_topk(logits.astype(np.float64) + bias.astype(np.float64)[None, :], 3)
+    assert not np.array_equal(w_m, w_b)
+
+
+def test_dense_gemm_closed_form_and_independent_dequant():
+    """q = z + 1 everywhere with all-ones activations gives K * s per output when the scale is
+    constant along the row; random data against nibbles taken from the words' hex digits."""
+    rng = np.random.default_rng(8)
+    M, N, K, g = 5, 12, 64, 32
+    z = rng.integers(0, 15, size=(N, K // g), dtype=np.uint8)
+    q = np.repeat(z, g, axis=1) + 1
+    s = np.repeat(rng.uniform(0.01, 0.02, size=(N, 1)), K // g, axis=1)
+    C = O.dense_gemm(np.ones((M, K)), O.pack_int4(q), s, z, g)
+    np.testing.assert_allclose(C, np.broadcast_to(K * s[:, 0], (M, N)), rtol=1e-13)
+    words = rng.integers(0, 2 ** 32, size=(N, K // 8), dtype=np.uint32)
+    zr = rng.integers(0, 16, size=(N, K // g), dtype=np.uint8)
+    sr = O.decode_bits(to_bits(rng.uniform(0.002, 0.02, size=(N, K // g)).astype(np.float32), "f16"), "f16")
+    A = O.decode_bits(to_bits((0.5 * rng.standard_normal((M, K))).astype(np.float32), "f16"), "f16")
+    W = np.empty((N, K))
+    for n in range(N):
+        for j in range(K // 8):
+            digits = f"{int(words[n, j]):08x}"[::-1]      # least significant nibble first
+            for i in range(8):
+                k = 8 * j + i
+                W[n, k] = (int(digits[i], 16) - int(zr[n, k // g])) * sr[n, k // g]
+    want = np.array([[sum(A[m, k] * W[n, k] for k in range(K)) for n in range(N)] for m in range(M)])
+    np.testing.assert_allclose(O.dense_gemm(A, words.view(np.int32), sr, zr, g), want, rtol=1e-12, atol=1e-12)
+    # the grouped GEMM with one expert is the same product
+    Cg = O.grouped_gemm(A, 1, words.view(np.int32)[None], sr[None], zr[None], np.zeros(M, np.int32), g)
+    np.testing.assert_array_equal(Cg, O.dense_gemm(A, words.view(np.int32), sr, zr, g))
+
+
 def test_skew_bias_formula():
     b = skew_bias(8)
     np.testing.assert_allclose(b, [2 * np.log(1 / (r ** 1.2)) for r in range(1, 9)], rtol=1e-6)
