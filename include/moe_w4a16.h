@@ -102,6 +102,28 @@ int moe_w4a16_grouped_gemm(const void* A, int row_div,
                            moe_dtype dt, void* C, void* stream);
 
 /*
+ * The plain FP16xINT4 GEMM the paper's mixed-type dataflow is introduced with (Section II-C,
+ * Fig. 4(b)): C[m, n] = sum_k A[m, k] * W[n, k], one weight matrix, no routing.
+ *   A [M, K_in] dt, qweight [N_out, K_in/8], scales / zeros [N_out, K_in/g], C [M, N_out] dt.
+ * Same kernels, requirements and rounding as moe_w4a16_grouped_gemm (it is that product with
+ * one expert and slot m = row m).
+ */
+int moe_w4a16_dense_gemm(const void* A, const int32_t* qweight, const void* scales, const uint8_t* zeros,
+                         int M, int N_out, int K_in, int group_size, moe_dtype dt, void* C, void* stream);
+
+/*
+ * Router in front of the layer (the benchmark statement's routing rule; the paper is silent):
+ * for every token the topk largest of logits[t, :] + bias[:], in descending order, ties to
+ * the lower expert index, and the softmax over those topk values.
+ *   logits [T, E] float32; bias [E] float32 or NULL (added in float32, one rounding);
+ *   topk_ids [T, topk] int32; topk_weights [T, topk] float32 (float32 arithmetic).
+ * 1 <= topk <= min(E, 64), E <= 1024.  Logits must be finite (-inf is allowed for all but the
+ * largest of a row).
+ */
+int moe_route_topk(const float* logits, const float* bias, int T, int E, int topk,
+                   int32_t* topk_ids, float* topk_weights, void* stream);
+
+/*
  * act[s, n] = silu(H[s, n]) * H[s, N + n],  silu(x) = x / (1 + exp(-x)).
  * H [S, 2N] dt (columns [0,N) gate, [N,2N) up), act [S, N] dt; fp32 math.
  * The gated activation between the two projections of each expert.
@@ -166,6 +188,20 @@ int moe_w4a16_layer(const void* X, const int32_t* topk_ids, const float* topk_we
  * moe_layer_block_m: the bucketing block size the layer picks for these sizes.
  */
 int moe_set_stage_events(void* const* events, int n);
+
+/*
+ * Achievable-roof probes for the benchmark (not part of the operator): what this chip sustains
+ * on the two resources the layer is priced against, measured by the caller with events around
+ * the call.
+ *
+ * moe_probe_stream_read: reads `bytes` (multiple of 16) from src once with the same
+ * non-temporal 128-bit loads the GEMM streams weights with.  sink: >= 16 KiB of device scratch.
+ *
+ * moe_probe_mfma: 512 workgroups x 4 waves each issue iters x 16 register-resident
+ * v_mfma_f32_16x16x32_f16 (16384 flop each).  sink: >= 512 KiB of device scratch.
+ */
+int moe_probe_stream_read(const void* src, size_t bytes, void* sink, void* stream);
+int moe_probe_mfma(void* sink, int iters, void* stream);
 int moe_set_tile_override(int mt, int nt);
 int moe_set_scale_path(int mode);
 int moe_set_tiles_per_workgroup(int n);

@@ -17,6 +17,7 @@ EXPORTS = [
     "moe_last_error", "moe_align_capacity", "moe_align_by_expert", "moe_w4a16_grouped_gemm",
     "moe_silu_mul", "moe_combine", "moe_w4a16_layer_workspace_bytes", "moe_w4a16_layer",
     "moe_set_stage_events", "moe_set_tile_override", "moe_set_scale_path", "moe_set_tiles_per_workgroup", "moe_set_reduction_splits", "moe_layer_block_m",
+    "moe_w4a16_dense_gemm", "moe_route_topk", "moe_probe_stream_read", "moe_probe_mfma",
 ]
 
 
@@ -49,6 +50,14 @@ def load_library() -> ctypes.CDLL:
     lib.moe_align_by_expert.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp]
     lib.moe_w4a16_grouped_gemm.restype = i32
     lib.moe_w4a16_grouped_gemm.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, vp, vp]
+    lib.moe_w4a16_dense_gemm.restype = i32
+    lib.moe_w4a16_dense_gemm.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, vp, vp]
+    lib.moe_route_topk.restype = i32
+    lib.moe_route_topk.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp]
+    lib.moe_probe_stream_read.restype = i32
+    lib.moe_probe_stream_read.argtypes = [vp, sz, vp, vp]
+    lib.moe_probe_mfma.restype = i32
+    lib.moe_probe_mfma.argtypes = [vp, i32, vp]
     lib.moe_silu_mul.restype = i32
     lib.moe_silu_mul.argtypes = [vp, vp, i32, i32, i32, vp]
     lib.moe_combine.restype = i32
@@ -130,6 +139,29 @@ def moe_w4a16_grouped_gemm(A, row_div, qweight, scales, zeros, sorted_slot_ids, 
         _ptr(A), row_div, _ptr(qweight), _ptr(scales), _ptr(zeros), _ptr(sorted_slot_ids),
         _ptr(block_expert_ids), _ptr(num_padded), num_slots, E, N_out, kw * 8, group_size, block_m,
         _dt(A), _ptr(C), _stream(stream)))
+
+
+def moe_w4a16_dense_gemm(A, qweight, scales, zeros, group_size, C, stream=None) -> None:
+    """A [M, K] fp16/bf16, qweight [N, K/8] int32, scales [N, K/g], zeros [N, K/g] uint8, C [M, N]."""
+    N_out, kw = qweight.shape
+    _check(load_library().moe_w4a16_dense_gemm(_ptr(A), _ptr(qweight), _ptr(scales), _ptr(zeros), A.shape[0],
+                                               N_out, kw * 8, group_size, _dt(A), _ptr(C), _stream(stream)))
+
+
+def moe_route_topk(logits, bias, topk_ids, topk_weights, stream=None) -> None:
+    """logits [T, E] float32, bias [E] float32 or None; outputs [T, topk] int32 / float32."""
+    T, E = logits.shape
+    _check(load_library().moe_route_topk(_ptr(logits), _ptr(bias), T, E, topk_ids.shape[1], _ptr(topk_ids),
+                                         _ptr(topk_weights), _stream(stream)))
+
+
+def moe_probe_stream_read(src, sink, stream=None) -> None:
+    _check(load_library().moe_probe_stream_read(_ptr(src), src.numel() * src.element_size(), _ptr(sink),
+                                                _stream(stream)))
+
+
+def moe_probe_mfma(sink, iters: int, stream=None) -> None:
+    _check(load_library().moe_probe_mfma(_ptr(sink), iters, _stream(stream)))
 
 
 def moe_silu_mul(H, act, stream=None) -> None:

@@ -28,7 +28,7 @@ def _units():
     for dt in (0, 1):
         for kw in (1, 2, 4):
             units.append(("gemm_inst.hip", f"gemm_inst_dt{dt}_kw{kw}.o", [f"-DMOE_DT={dt}", f"-DMOE_KW={kw}"]))
-    for src in ("align.hip", "elementwise.hip", "api.hip"):
+    for src in ("align.hip", "elementwise.hip", "router.hip", "api.hip"):
         units.append((src, src.replace(".hip", ".o"), []))
     return units
 

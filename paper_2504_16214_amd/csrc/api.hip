@@ -13,6 +13,9 @@ namespace moe {
 int launch_align(const int32_t*, int, int, int, int, int32_t*, int32_t*, int32_t*, int32_t*, int32_t*,
                  hipStream_t);
 int launch_silu_mul(const void*, void*, long long, int, int, hipStream_t);
+int launch_route_topk(const float*, const float*, int, int, int, int32_t*, float*, hipStream_t);
+int launch_stream_read(const void*, size_t, uint32_t*, int, hipStream_t);
+int launch_mfma_loop(float*, int, int, hipStream_t);
 int launch_combine(const void*, int, int, const float*, const int32_t*, int, void*, long long, int, int, int,
                    hipStream_t);
 
@@ -127,6 +130,7 @@ struct GemmArgs {
   const int32_t* sorted_slot_ids; const int32_t* block_expert_ids; const int32_t* num_padded;
   int num_slots, E, N_out, K_in, group, block_m, dt;
   void* C; int ldc; int fuse_half_n; int out_f32;
+  int dense = 0;             // 1: plain GEMM, no routing tables (the three table pointers are null)
   int k_splits = 1;          // wanted reduction splits (float32 output planes num_slots*ldc apart)
   int* used_splits = nullptr;  // out: the number of planes the launch really wrote
 };
@@ -142,8 +146,8 @@ static int run_gemm(const GemmArgs& a, hipStream_t stream) {
   const int G = a.K_in / a.group;
   if (G > kMaxGroups) return fail(MOE_UNSUPPORTED_SHAPE, "K_in/group_size = %d exceeds %d", G, kMaxGroups);
   if (a.num_slots == 0) return MOE_OK;
-  if (!a.A || !a.qweight || !a.scales || !a.zeros || !a.sorted_slot_ids || !a.block_expert_ids ||
-      !a.num_padded || !a.C)
+  if (!a.A || !a.qweight || !a.scales || !a.zeros || !a.C ||
+      (!a.dense && (!a.sorted_slot_ids || !a.block_expert_ids || !a.num_padded)))
     return fail(MOE_INVALID_ARGUMENT, "null pointer argument");
   if (((uintptr_t)a.A | (uintptr_t)a.qweight) % 16 != 0)
     return fail(MOE_INVALID_ARGUMENT, "A and qweight must be 16-byte aligned");
@@ -180,6 +184,7 @@ static int run_gemm(const GemmArgs& a, hipStream_t stream) {
   p.half_n = a.fuse_half_n;
   p.out_f32 = a.out_f32;
   p.sz_vec = sz_vec;
+  p.dense = a.dense;
   // Split reduction: whole scale panels (4 pipeline stages) per range, every range non-empty.
   int ksp = 1, kspan = a.K_in;
   if (a.k_splits > 1 && szr && a.out_f32 && !fuse) {
@@ -290,6 +295,43 @@ int moe_w4a16_grouped_gemm(const void* A, int row_div, const int32_t* qweight, c
   GemmArgs a{A, row_div, qweight, scales, zeros, sorted_slot_ids, block_expert_ids, num_padded,
              num_slots, E, N_out, K_in, group_size, block_m, (int)dt, C, N_out, 0, 0};
   return run_gemm(a, (hipStream_t)stream);
+}
+
+int moe_w4a16_dense_gemm(const void* A, const int32_t* qweight, const void* scales, const uint8_t* zeros,
+                         int M, int N_out, int K_in, int group_size, moe_dtype dt, void* C, void* stream) {
+  if (M < 0) return fail(MOE_INVALID_ARGUMENT, "need M >= 0");
+  const int block_m = M <= 16 ? 16 : (M <= 32 ? 32 : 64);
+  GemmArgs a{A, 1, qweight, scales, zeros, nullptr, nullptr, nullptr,
+             M, 1, N_out, K_in, group_size, block_m, (int)dt, C, N_out, 0, 0};
+  a.dense = 1;
+  return run_gemm(a, (hipStream_t)stream);
+}
+
+int moe_route_topk(const float* logits, const float* bias, int T, int E, int topk,
+                   int32_t* topk_ids, float* topk_weights, void* stream) {
+  if (T < 0 || E < 1 || topk < 1) return fail(MOE_INVALID_ARGUMENT, "need T >= 0, E >= 1, topk >= 1");
+  if (E > 1024) return fail(MOE_UNSUPPORTED_SHAPE, "E = %d exceeds 1024", E);
+  if (topk > E || topk > 64) return fail(MOE_UNSUPPORTED_SHAPE, "topk = %d exceeds min(E, 64)", topk);
+  if (T == 0) return MOE_OK;
+  if (!logits || !topk_ids || !topk_weights) return fail(MOE_INVALID_ARGUMENT, "null pointer argument");
+  const int err = launch_route_topk(logits, bias, T, E, topk, topk_ids, topk_weights, (hipStream_t)stream);
+  if (err != 0) return hip_fail(err, "router launch");
+  return MOE_OK;
+}
+
+int moe_probe_stream_read(const void* src, size_t bytes, void* sink, void* stream) {
+  if (!src || !sink || bytes < 16 || ((uintptr_t)src % 16) != 0)
+    return fail(MOE_INVALID_ARGUMENT, "probe needs a 16-byte aligned source of at least 16 bytes and a sink");
+  const int err = launch_stream_read(src, bytes, (uint32_t*)sink, 256 * 16, (hipStream_t)stream);
+  if (err != 0) return hip_fail(err, "stream-read probe launch");
+  return MOE_OK;
+}
+
+int moe_probe_mfma(void* sink, int iters, void* stream) {
+  if (!sink || iters < 1) return fail(MOE_INVALID_ARGUMENT, "probe needs a sink and iters >= 1");
+  const int err = launch_mfma_loop((float*)sink, 512, iters, (hipStream_t)stream);
+  if (err != 0) return hip_fail(err, "MFMA probe launch");
+  return MOE_OK;
 }
 
 int moe_silu_mul(const void* H, void* act, int S, int N, moe_dtype dt, void* stream) {

@@ -58,6 +58,7 @@ struct GemmParams {
   int k_splits;   // > 1: the reduction is cut into k_splits ranges of k_span indices, one workgroup each;
   int k_span;     //      split i writes its partial sums to the float32 plane C + i * split_stride
   long long split_stride;   // elements between planes (register-scale kernels with out_f32 only)
+  int dense;      // 1: no routing tables (all three pointers null): one expert, slot s = row s of A and C
   int tiles_per_wg;  // consecutive feature tiles one workgroup walks (1 unless SZR)
 };
 
@@ -372,14 +373,17 @@ w4a16_gemm_kernel(const GemmParams p) {
   const int tpw = SZR ? p.tiles_per_wg : 1;
   const int tgroups = (p.n_tiles + tpw - 1) / tpw;
   const int ksp = SZR ? p.k_splits : 1;
-  int L = xcd_contiguous_index(blockIdx.x, (*p.num_padded / M_T) * tgroups * ksp);
+  const int rows_padded = p.dense ? (p.num_slots + M_T - 1) / M_T * M_T : *p.num_padded;
+  int L = xcd_contiguous_index(blockIdx.x, (rows_padded / M_T) * tgroups * ksp);
   if (L < 0) return;
   const int split = L % ksp;        // neighbouring workgroups take the ranges of one tile
   L /= ksp;
   const int tile0 = (L % tgroups) * tpw;
   const int ntl = p.n_tiles - tile0 < tpw ? p.n_tiles - tile0 : tpw;     // tiles this workgroup walks
   const int row0 = (L / tgroups) * M_T;
-  const int e = p.block_expert_ids[row0 / p.block_m];
+  const int e = p.dense ? 0 : p.block_expert_ids[row0 / p.block_m];
+  // slot id of a tile row: from the bucketing table, or the row itself for the plain GEMM
+  auto slot_at = [&](int r) { return p.dense ? (r < p.num_slots ? r : p.num_slots) : p.sorted_slot_ids[r]; };
   if (e < 0 || e >= p.E) return;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -407,7 +411,7 @@ w4a16_gemm_kernel(const GemmParams p) {
   const int xw_pos = (xr_chunk / (4 * KW)) * (4 * KW) + (xr_chunk % (4 * KW)) / KW + 4 * (xr_chunk % KW);
 #pragma unroll
   for (int ps = 0; ps < XPASS; ++ps) {
-    const int slot = p.sorted_slot_ids[row0 + ps * RPP + xr_row];
+    const int slot = slot_at(row0 + ps * RPP + xr_row);
     const uint32_t arow = (slot >= 0 && slot < p.num_slots) ? (uint32_t)(slot / p.row_div) : 0u;
     xoff[ps] = arow * (uint32_t)(K_in * 2) + (uint32_t)(xr_chunk * 16);
   }
@@ -581,7 +585,7 @@ w4a16_gemm_kernel(const GemmParams p) {
   }
 
   // ---- stage scales / zero points of this tile's rows into LDS ---------------------
-  if (tid < M_T) slot_s[tid] = p.sorted_slot_ids[row0 + tid];
+  if (tid < M_T) slot_s[tid] = slot_at(row0 + tid);
   if constexpr (!SZR) {
     const uint16_t* sc = reinterpret_cast<const uint16_t*>(p.scales);
     const int G = p.G, G8 = (G + 7) >> 3;

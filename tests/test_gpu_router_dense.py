@@ -1,0 +1,179 @@
+"""GPU parity of the router and of the plain (one weight matrix, no routing) W4A16 GEMM.
+
+Router: expert ids bit-exact against the oracle's selection; weights within 2e-6 absolute
+(float32 exp / divide / k-term sum against float64: a few float32 ulps of values <= 1).
+Dense GEMM: the floating-point bound of the benchmark statement."""
+from __future__ import annotations
+
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+from moe_workloads import CONFIGS, MoEConfig, make_inputs, skew_bias
+from oracle import moe_oracle as O
+
+pytestmark = pytest.mark.gpu
+
+if torch.cuda.is_available():
+    import paper_2504_16214_amd as M
+    import gpu_util as U
+
+W_ATOL = 2e-6
+
+
+def say(msg):
+    print(f"[gpu-case] {msg}", flush=True)
+    sys.stdout.flush()
+
+
+def run_router(logits: np.ndarray, bias, topk: int):
+    T, E = logits.shape
+    ld = torch.from_numpy(np.ascontiguousarray(logits, dtype=np.float32)).cuda()
+    bd = None if bias is None else torch.from_numpy(np.ascontiguousarray(bias, dtype=np.float32)).cuda()
+    ids = torch.full((T, topk), -7, dtype=torch.int32, device="cuda")
+    w = torch.full((T, topk), float("nan"), dtype=torch.float32, device="cuda")
+    M.moe_route_topk(ld, bd, ids, w)
+    torch.cuda.synchronize()
+    return ids.cpu().numpy(), w.cpu().numpy()
+
+
+@pytest.mark.parametrize("T,E,topk,with_bias", [
+    (16, 8, 2, False), (64, 8, 2, False), (128, 256, 8, False), (1024, 64, 6, True), (37, 100, 5, True),
+    (5, 1024, 64, False), (9, 1, 1, False), (3, 70, 70 - 6, True), (4096, 256, 8, False), (1, 65, 3, False),
+])
+def test_router_matches_oracle(T, E, topk, with_bias):
+    say(f"router T={T} E={E} topk={topk} bias={with_bias}")
+    rng = np.random.default_rng(1000 + T + 7 * E + topk)
+    logits = rng.standard_normal((T, E)).astype(np.float32)
+    bias = skew_bias(E) if with_bias else None
+    ids, w = run_router(logits, bias, topk)
+    ids_o, w_o = O.route_topk(logits, topk, bias=bias)
+    np.testing.assert_array_equal(ids, ids_o)
+    assert np.max(np.abs(w.astype(np.float64) - w_o)) <= W_ATOL
+    assert np.all(np.abs(w.astype(np.float64).sum(axis=1) - 1.0) <= 1e-5)
+
+
+def test_router_ties_signed_zeros_and_infinities():
+    say("router ties")
+    E, topk = 40, 4
+    logits = np.random.default_rng(3).standard_normal((6, E)).astype(np.float32)
+    logits[0, :] = 1.5                                     # all equal: ids 0..3
+    logits[1, [30, 2, 17]] = 8.0                           # three-way tie for the top
+    logits[2, :] = -1.0; logits[2, 11] = -0.0; logits[2, 12] = 0.0
+    logits[3, :] = -np.inf; logits[3, [5, 9, 33, 34]] = [0.5, 0.25, 0.125, 1.0]   # -inf never beats a finite value
+    logits[4, 39] = logits[4, 0] = 3.0                     # first and last index
+    ids, w = run_router(logits, None, topk)
+    ids_o, w_o = O.route_topk(logits, topk)
+    np.testing.assert_array_equal(ids, ids_o)
+    assert list(ids[0]) == [0, 1, 2, 3] and list(ids[1][:3]) == [2, 17, 30] and list(ids[2][:2]) == [11, 12]
+    assert list(ids[3]) == [34, 5, 9, 33] and list(ids[4][:2]) == [0, 39]
+    assert np.max(np.abs(w.astype(np.float64) - w_o)) <= W_ATOL
+
+
+@pytest.mark.parametrize("name", ["mixtral_decode", "skewed_bf16"])
+def test_router_reproduces_the_workload_routing(name):
+    """The seeded configurations' stored logits give back the ids the layer inputs were built
+    from (the generator's own routing), bit for bit."""
+    cfg = CONFIGS[name]
+    say(f"router on {name}")
+    # only the logits are needed: a tiny stand-in shape with the same T, E, topk and seed draw order
+    rng = np.random.default_rng(cfg.seed)
+    rng.standard_normal((cfg.T, cfg.K))                    # X is drawn first
+    logits = rng.standard_normal((cfg.T, cfg.E)).astype(np.float32)
+    bias = skew_bias(cfg.E) if name == "skewed_bf16" else None
+    ids, w = run_router(logits, bias, cfg.topk)
+    ids_o, w_o = O.route_topk(logits, cfg.topk, bias=bias)
+    np.testing.assert_array_equal(ids, ids_o)
+    assert np.max(np.abs(w.astype(np.float64) - w_o)) <= W_ATOL
+
+
+def test_router_error_paths():
+    say("router errors")
+    ld = torch.zeros((4, 8), dtype=torch.float32, device="cuda")
+    with pytest.raises(M.MoEError) as e:                   # topk > E
+        M.moe_route_topk(ld, None, torch.zeros((4, 9), dtype=torch.int32, device="cuda"),
+                         torch.zeros((4, 9), dtype=torch.float32, device="cuda"))
+    assert e.value.status == 2
+    with pytest.raises(M.MoEError) as e:                   # topk == 0
+        M.moe_route_topk(ld, None, torch.zeros((4, 0), dtype=torch.int32, device="cuda"),
+                         torch.zeros((4, 0), dtype=torch.float32, device="cuda"))
+    assert e.value.status == 1
+    big = torch.zeros((1, 1025), dtype=torch.float32, device="cuda")
+    with pytest.raises(M.MoEError) as e:                   # E > 1024
+        M.moe_route_topk(big, None, torch.zeros((1, 2), dtype=torch.int32, device="cuda"),
+                         torch.zeros((1, 2), dtype=torch.float32, device="cuda"))
+    assert e.value.status == 2
+
+
+def test_router_feeds_the_layer():
+    """Router output used directly as the layer's routing input equals the oracle chain."""
+    cfg = MoEConfig("routed", T=40, K=256, N=128, E=12, topk=3, group=128, dtype="f16", seed=31)
+    say(f"router + layer {cfg}")
+    inp = make_inputs(cfg)
+    d = U.DevInputs(inp)
+    ld = torch.from_numpy(inp.logits).cuda()
+    ids = torch.empty((cfg.T, cfg.topk), dtype=torch.int32, device="cuda")
+    w = torch.empty((cfg.T, cfg.topk), dtype=torch.float32, device="cuda")
+    M.moe_route_topk(ld, None, ids, w)
+    d.ids, d.w = ids, w
+    out = U.run_layer(d)
+    ids_o, w_o = O.route_topk(inp.logits, cfg.topk)
+    want = O.layer(O.decode_bits(inp.x_bits, "f16"), ids_o, w_o.astype(np.float32), inp.qw1,
+                   O.decode_bits(inp.s1_bits, "f16"), inp.z1, inp.qw2, O.decode_bits(inp.s2_bits, "f16"), inp.z2,
+                   cfg.group, "f16")
+    U.assert_close(U.dev_to_f64(out), want, "routed layer")
+
+
+# ------------------------------------------------------------------ dense GEMM
+@pytest.mark.parametrize("M_rows,N,K,group,dtype", [
+    (1, 256, 128, 128, "f16"), (16, 320, 224, 32, "f16"), (17, 256, 1024, 128, "f16"), (50, 768, 1024, 128, "bf16"),
+    (200, 512, 2048, 128, "f16"), (33, 128, 512, 64, "bf16"), (128, 1024, 1024, 128, "f16"),
+])
+def test_dense_gemm_matches_oracle(M_rows, N, K, group, dtype):
+    say(f"dense gemm M={M_rows} N={N} K={K} g={group} {dtype}")
+    cfg = MoEConfig("dense", T=M_rows, K=K, N=N // 2, E=1, topk=1, group=group, dtype=dtype, seed=40 + M_rows)
+    inp = make_inputs(cfg)                                  # W1 of the single expert is [N, K]
+    d = U.DevInputs(inp)
+    C = torch.full((M_rows, N), float("nan"), dtype=U.TORCH_DT[dtype], device="cuda")
+    M.moe_w4a16_dense_gemm(d.X, d.qw1[0], d.s1[0], d.z1[0], group, C)
+    torch.cuda.synchronize()
+    want = O.dense_gemm(O.decode_bits(inp.x_bits, dtype), inp.qw1[0], O.decode_bits(inp.s1_bits[0], dtype),
+                        inp.z1[0], group, dtype)
+    U.assert_close(U.dev_to_f64(C), want, "dense gemm")
+
+
+def test_dense_gemm_equals_grouped_gemm_with_one_expert_bitwise():
+    cfg = MoEConfig("dense_eq", T=70, K=1024, N=384, E=1, topk=1, group=128, dtype="f16", seed=44)
+    say(f"dense vs grouped {cfg}")
+    inp = make_inputs(cfg)
+    d = U.DevInputs(inp)
+    C1 = torch.zeros((cfg.T, 2 * cfg.N), dtype=torch.float16, device="cuda")
+    C2 = torch.zeros_like(C1)
+    M.moe_w4a16_dense_gemm(d.X, d.qw1[0], d.s1[0], d.z1[0], cfg.group, C1)
+    al = U.run_align(d.ids, 1, 64)
+    M.moe_w4a16_grouped_gemm(d.X, 1, d.qw1, d.s1, d.z1, al["sorted_slot_ids"], al["block_expert_ids"],
+                             al["num_padded"], cfg.T, cfg.group, 64, C2)
+    torch.cuda.synchronize()
+    assert torch.equal(C1, C2)
+
+
+def test_dense_gemm_empty_and_errors():
+    say("dense gemm M=0 / bad shape")
+    cfg = MoEConfig("dense0", T=4, K=128, N=128, E=1, topk=1, group=128, dtype="f16", seed=45)
+    d = U.DevInputs(make_inputs(cfg))
+    C = torch.zeros((0, 256), dtype=torch.float16, device="cuda")
+    M.moe_w4a16_dense_gemm(d.X[:0], d.qw1[0], d.s1[0], d.z1[0], 128, C)
+    with pytest.raises(M.MoEError) as e:
+        M.moe_w4a16_dense_gemm(d.X, d.qw1[0], d.s1[0], d.z1[0], 48, torch.zeros((4, 256), dtype=torch.float16, device="cuda"))
+    assert e.value.status == 2
+
+
+def test_roof_probes_run():
+    say("roof probes")
+    src = torch.ones(1 << 24, dtype=torch.int32, device="cuda")       # 64 MiB
+    sink = torch.zeros(1 << 18, dtype=torch.int32, device="cuda")     # 1 MiB
+    M.moe_probe_stream_read(src, sink)
+    M.moe_probe_mfma(sink, 100)
+    torch.cuda.synchronize()
