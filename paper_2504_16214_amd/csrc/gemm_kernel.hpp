@@ -88,12 +88,12 @@ __device__ __forceinline__ floatx4_t mfma16x16x32(const u32x4& a, const u32x4& b
 // ---- int4 -> 16-bit float, in registers ---------------------------------------------------
 // The MFMA never sees a rounded weight.  Two ways of removing the zero point, chosen by ZM:
 //
-//   ZM = 1 (small token tiles, VALU is the scarce resource): the B operand holds the BIASED
-//     integers bias + q, produced by one AND-OR per nibble pair; a second MFMA with the constant
-//     operand -(bias + z) subtracts bias and zero point inside the fp32 accumulation.
-//   ZM = 0 (large token tiles, MFMA is the scarce resource): one packed subtract per nibble
-//     pair yields the exact integers q - z.
-// Either way the group scale multiplies the fp32 partial sum of each chunk-step.
+//   ZM = 1 (bf16, which has no packed arithmetic): the B operand holds the BIASED integers
+//     bias + q, produced by one AND-OR per nibble pair; a second MFMA with the constant operand
+//     -(bias + z) subtracts bias and zero point inside the fp32 accumulation.
+//   ZM = 0 (fp16): one packed subtract per nibble pair yields the exact integers q - z.
+// Either way the group scale is applied in fp32 (to the partial sum of a chunk-step, or by
+// keeping the accumulator in units of the current group's scale: see RS in the kernel).
 //
 // fp16: nibbles 0/4 of a word are ORed into the mantissa of 1024.0 (ulp 1: value 1024 + q);
 //       nibbles 1/5 sit four bits higher and are ORed into the mantissa of 64.0 (ulp 1/16,
