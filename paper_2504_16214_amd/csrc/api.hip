@@ -196,14 +196,19 @@ static int run_gemm(const GemmArgs& a, hipStream_t stream) {
   p.k_splits = ksp; p.k_span = kspan; p.split_stride = (long long)a.num_slots * a.ldc;
   if (a.used_splits) *a.used_splits = ksp;
   const size_t cap = align_capacity(a.num_slots, a.E, a.block_m);
-  // Register-scale kernels can walk several feature tiles per workgroup: aim for at least ~24
-  // pipeline stages per workgroup while keeping a few thousand workgroups in the launch.
+  // Register-scale kernels can walk several feature tiles per workgroup: aim for about 48
+  // pipeline stages per workgroup at small token tiles (the start-up of a workgroup costs about
+  // as much as ten of their stages) while keeping a few thousand workgroups in the launch.
   int tpw = 1;
   if (szr) {
     const int nst = kspan / ks;
-    tpw = (24 + nst - 1) / nst;
+    const int target = mt <= 2 ? 48 : 24;       // large token tiles: stages are long, start-up matters less
+    tpw = (target + nst - 1) / nst;
     if (tpw > 8) tpw = 8;
     if (tpw > p.n_tiles) tpw = p.n_tiles;
+    // prefer a count that divides the tiles of a block evenly (no short last group)
+    for (int t = tpw; t <= tpw + 2 && t <= 8 && t <= p.n_tiles; ++t)
+      if (p.n_tiles % t == 0) { tpw = t; break; }
     const long long est_blocks = (a.num_slots + 16 * mt - 1) / (16 * mt) + (a.num_slots < a.E ? a.num_slots : a.E) / 2;
     while (tpw > 1 && est_blocks * ((p.n_tiles + tpw - 1) / tpw) * ksp < 2048) --tpw;
   }
