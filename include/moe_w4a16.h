@@ -89,8 +89,8 @@ int moe_align_by_expert(const int32_t* topk_ids, int T, int topk, int E, int blo
  *   A   [rows_A, K_in] dt; rows_A >= ceil(num_slots / row_div).
  *       row_div = topk for the gate/up projection (A = token activations),
  *       1 for the down projection (A is already per slot).
- *   C   [num_slots, N_out] dt, written at row = slot id.  Rows of slots that
- *       were not bucketed are left untouched.
+ *   C   [num_slots, N_out] dt, 4-byte aligned, written at row = slot id.  Rows of
+ *       slots that were not bucketed are left untouched.
  *   sorted_slot_ids / block_expert_ids / num_padded: as produced by
  *       moe_align_by_expert with the same block_m and num_slots = T*topk.
  */

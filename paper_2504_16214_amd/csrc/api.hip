@@ -151,8 +151,8 @@ static int run_gemm(const GemmArgs& a, hipStream_t stream) {
     return fail(MOE_INVALID_ARGUMENT, "null pointer argument");
   if (((uintptr_t)a.A | (uintptr_t)a.qweight) % 16 != 0)
     return fail(MOE_INVALID_ARGUMENT, "A and qweight must be 16-byte aligned");
-  if (((uintptr_t)a.C | (uintptr_t)a.scales) % 2 != 0)
-    return fail(MOE_INVALID_ARGUMENT, "C and scales must be 2-byte aligned");
+  if ((uintptr_t)a.scales % 2 != 0 || (uintptr_t)a.C % (a.out_f32 ? 8 : 4) != 0)
+    return fail(MOE_INVALID_ARGUMENT, "scales must be 2-byte aligned and C 4-byte aligned");
 
   // kernels address with 32-bit per-lane byte offsets from a per-expert / per-matrix base
   if ((long long)a.N_out * (a.K_in / 2) >= (1LL << 31))

@@ -313,7 +313,10 @@ struct TileGeom {
 };
 
 // Local feature index of a workgroup tile -> weight row / output column.
-//   plain : feature f = tile*N_T + lf, weight row = output column = f.
+//   plain : weight row = output column = feature f of the tile.  A wave's sub-tiles are
+//           interleaved in pairs (sub-tile 2p takes the even, 2p+1 the odd features of a run of
+//           32), so a lane owns two ADJACENT output columns per pair and stores them with one
+//           instruction: full 128-byte lines per row for float32 output.
 //   fused SiLU-and-multiply: wave-local sub-tiles alternate gate, up; the pair (2p, 2p+1)
 //   covers act columns c..c+15 with weight rows c (gate) and N + c (up).
 template <int NT, int FUSE>
@@ -321,7 +324,8 @@ __device__ __forceinline__ void feature_of(int n_tile, int wave, int sub, int n,
                                            int& wrow, int& ocol, bool& valid) {
   constexpr int NW = 16 * NT, N_T = 4 * NW;
   if constexpr (FUSE == 0) {
-    const int f = n_tile * N_T + wave * NW + sub * 16 + n;
+    const int f = NT == 1 ? n_tile * N_T + wave * NW + n
+                          : n_tile * N_T + wave * NW + (sub >> 1) * 32 + 2 * n + (sub & 1);
     wrow = f; ocol = f; valid = f < p.N_out;
   } else {
     const int c = n_tile * (N_T / 2) + wave * (NW / 2) + (sub >> 1) * 16 + n;
@@ -761,14 +765,27 @@ w4a16_gemm_kernel(const GemmParams p) {
         const int slot = slot_s[mt * 16 + lj * 4 + i];
         if (slot < 0 || slot >= p.num_slots) continue;
         uint16_t* crow = C16 + (size_t)slot * p.ldc;
-        if constexpr (FUSE == 0) {
+        if constexpr (FUSE == 0 && NT == 1) {
+          int wrow, ocol; bool ok;
+          feature_of<NT, FUSE>(tile, wave, 0, ln, p, wrow, ocol, ok);
+          if (ok) {
+            if (p.out_f32) (reinterpret_cast<float*>(p.C) + (size_t)split * p.split_stride)[(size_t)slot * p.ldc + ocol] = acc[mt][0][i];
+            else crow[ocol] = to_bits16<DT>(acc[mt][0][i]);
+          }
+        } else if constexpr (FUSE == 0) {
 #pragma unroll
-          for (int s = 0; s < NT; ++s) {
+          for (int s = 0; s < NT; s += 2) {
+            // columns ocol (even) and ocol + 1 belong to this lane: one 8-byte / 4-byte store
             int wrow, ocol; bool ok;
             feature_of<NT, FUSE>(tile, wave, s, ln, p, wrow, ocol, ok);
             if (ok) {
-              if (p.out_f32) (reinterpret_cast<float*>(p.C) + (size_t)split * p.split_stride)[(size_t)slot * p.ldc + ocol] = acc[mt][s][i];
-              else crow[ocol] = to_bits16<DT>(acc[mt][s][i]);
+              if (p.out_f32) {
+                float* dst = reinterpret_cast<float*>(p.C) + (size_t)split * p.split_stride + (size_t)slot * p.ldc + ocol;
+                *reinterpret_cast<floatx2_t*>(dst) = floatx2_t{acc[mt][s][i], acc[mt][s + 1][i]};
+              } else {
+                *reinterpret_cast<uint32_t*>(crow + ocol) =
+                    (uint32_t)to_bits16<DT>(acc[mt][s][i]) | ((uint32_t)to_bits16<DT>(acc[mt][s + 1][i]) << 16);
+              }
             }
           }
         } else {
