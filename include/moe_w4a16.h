@@ -158,6 +158,18 @@ int moe_w4a16_layer(const void* X, const int32_t* topk_ids, const float* topk_we
                     moe_dtype dt, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Router + layer on one stream: moe_route_topk into tables held in the workspace, then
+ * moe_w4a16_layer.  Arguments as for the two; `workspace` of at least
+ * moe_w4a16_routed_layer_workspace_bytes(...) bytes, 256-byte aligned.
+ */
+size_t moe_w4a16_routed_layer_workspace_bytes(int T, int K, int N, int E, int topk, moe_dtype dt);
+int moe_w4a16_routed_layer(const void* X, const float* logits, const float* bias,
+                           const int32_t* qw1, const void* s1, const uint8_t* z1,
+                           const int32_t* qw2, const void* s2, const uint8_t* z2,
+                           void* out, int T, int K, int N, int E, int topk, int group_size,
+                           moe_dtype dt, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Measurement hooks (not part of the operator).
  *
  * moe_set_stage_events: while set (n == 5), moe_w4a16_layer records the given

@@ -18,6 +18,7 @@ EXPORTS = [
     "moe_silu_mul", "moe_combine", "moe_w4a16_layer_workspace_bytes", "moe_w4a16_layer",
     "moe_set_stage_events", "moe_set_tile_override", "moe_set_scale_path", "moe_set_tiles_per_workgroup", "moe_set_reduction_splits", "moe_layer_block_m",
     "moe_w4a16_dense_gemm", "moe_route_topk", "moe_probe_stream_read", "moe_probe_mfma",
+    "moe_w4a16_routed_layer_workspace_bytes", "moe_w4a16_routed_layer",
 ]
 
 
@@ -58,6 +59,10 @@ def load_library() -> ctypes.CDLL:
     lib.moe_probe_stream_read.argtypes = [vp, sz, vp, vp]
     lib.moe_probe_mfma.restype = i32
     lib.moe_probe_mfma.argtypes = [vp, i32, vp]
+    lib.moe_w4a16_routed_layer_workspace_bytes.restype = sz
+    lib.moe_w4a16_routed_layer_workspace_bytes.argtypes = [i32] * 6
+    lib.moe_w4a16_routed_layer.restype = i32
+    lib.moe_w4a16_routed_layer.argtypes = [vp] * 10 + [i32] * 7 + [vp, sz, vp]
     lib.moe_silu_mul.restype = i32
     lib.moe_silu_mul.argtypes = [vp, vp, i32, i32, i32, vp]
     lib.moe_combine.restype = i32
@@ -187,6 +192,20 @@ def moe_w4a16_layer(X, topk_ids, topk_weights, qw1, s1, z1, qw2, s2, z2, out, gr
     _check(load_library().moe_w4a16_layer(
         _ptr(X), _ptr(topk_ids), _ptr(topk_weights), _ptr(qw1), _ptr(s1), _ptr(z1), _ptr(qw2), _ptr(s2),
         _ptr(z2), _ptr(out), T, K, N2 // 2, E, topk, group_size, _dt(X), _ptr(workspace),
+        workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+def moe_w4a16_routed_layer_workspace_bytes(T, K, N, E, topk, dt) -> int:
+    return int(load_library().moe_w4a16_routed_layer_workspace_bytes(T, K, N, E, topk, dt))
+
+
+def moe_w4a16_routed_layer(X, logits, bias, qw1, s1, z1, qw2, s2, z2, out, topk, group_size, workspace,
+                           stream=None) -> None:
+    T, K = X.shape
+    E, N2, _ = qw1.shape
+    _check(load_library().moe_w4a16_routed_layer(
+        _ptr(X), _ptr(logits), _ptr(bias), _ptr(qw1), _ptr(s1), _ptr(z1), _ptr(qw2), _ptr(s2), _ptr(z2),
+        _ptr(out), T, K, N2 // 2, E, topk, group_size, _dt(X), _ptr(workspace),
         workspace.numel() * workspace.element_size(), _stream(stream)))
 
 

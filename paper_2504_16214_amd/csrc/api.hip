@@ -445,6 +445,36 @@ int moe_w4a16_layer(const void* X, const int32_t* topk_ids, const float* topk_we
   return MOE_OK;
 }
 
+size_t moe_w4a16_routed_layer_workspace_bytes(int T, int K, int N, int E, int topk, moe_dtype dt) {
+  const size_t layer = moe_w4a16_layer_workspace_bytes(T, K, N, E, topk, dt);
+  if (layer == 0 && T != 0) return 0;
+  if (T < 0 || topk < 1) return 0;
+  // routing tables in front of the layer's own workspace: ids int32 [S], weights float32 [S]
+  return 2 * round_up((size_t)T * topk * 4, 256) + layer;
+}
+
+int moe_w4a16_routed_layer(const void* X, const float* logits, const float* bias,
+                           const int32_t* qw1, const void* s1, const uint8_t* z1,
+                           const int32_t* qw2, const void* s2, const uint8_t* z2,
+                           void* out, int T, int K, int N, int E, int topk, int group_size, moe_dtype dt,
+                           void* workspace, size_t workspace_bytes, void* stream) {
+  if (T < 0 || topk < 1 || E < 1) return fail(MOE_INVALID_ARGUMENT, "need T >= 0, topk >= 1, E >= 1");
+  if (T == 0) return MOE_OK;
+  if (!workspace) return fail(MOE_INVALID_ARGUMENT, "null pointer argument");
+  if (((uintptr_t)workspace % 256) != 0) return fail(MOE_INVALID_ARGUMENT, "workspace must be 256-byte aligned");
+  const size_t table = round_up((size_t)T * topk * 4, 256);
+  if (workspace_bytes < 2 * table)
+    return fail(MOE_WORKSPACE_TOO_SMALL, "workspace has %zu bytes, %zu needed", workspace_bytes,
+                moe_w4a16_routed_layer_workspace_bytes(T, K, N, E, topk, dt));
+  unsigned char* base = (unsigned char*)workspace;
+  int32_t* ids = (int32_t*)base;
+  float* weights = (float*)(base + table);
+  const int st = moe_route_topk(logits, bias, T, E, topk, ids, weights, stream);
+  if (st != MOE_OK) return st;
+  return moe_w4a16_layer(X, ids, weights, qw1, s1, z1, qw2, s2, z2, out, T, K, N, E, topk, group_size, dt,
+                         base + 2 * table, workspace_bytes - 2 * table, stream);
+}
+
 int moe_set_stage_events(void* const* events, int n) {
   if (n == 0 || events == nullptr) { g_nevents = 0; return MOE_OK; }
   if (n != 5) return fail(MOE_INVALID_ARGUMENT, "expected 5 events");

@@ -15,12 +15,20 @@ template <int DT, int MT, int NT, int KS, int KW, int FUSE, int SZR>
 int launch_w4a16_gemm(const GemmParams& p, int grid, hipStream_t stream) {
   auto kern = w4a16_gemm_kernel<DT, MT, NT, KS, KW, FUSE, SZR>;
   const size_t lds = TileGeom<MT, NT, KS>::lds_bytes(p.G, SZR);
-  static size_t lds_allowed = 64 * 1024;   // raise the dynamic LDS limit once per size class
-  if (lds > lds_allowed) {
-    hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  if (lds > 64 * 1024) {
+    // Raise the dynamic LDS limit of this kernel, once per device and size (the attribute is
+    // per device; remembering it per device keeps a second GPU of the process correct).
+    constexpr int kMaxDev = 64;
+    static size_t lds_allowed[kMaxDev] = {};
+    int dev = 0;
+    hipError_t err = hipGetDevice(&dev);
     if (err != hipSuccess) return (int)err;
-    lds_allowed = lds;
+    if (dev < 0 || dev >= kMaxDev || lds > lds_allowed[dev]) {
+      err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+      if (err != hipSuccess) return (int)err;
+      if (dev >= 0 && dev < kMaxDev) lds_allowed[dev] = lds;
+    }
   }
   hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, stream, p);
   return (int)hipGetLastError();

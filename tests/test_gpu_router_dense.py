@@ -126,6 +126,33 @@ def test_router_feeds_the_layer():
     U.assert_close(U.dev_to_f64(out), want, "routed layer")
 
 
+@pytest.mark.parametrize("name,dtype,with_bias", [("a", "f16", False), ("b", "bf16", True)])
+def test_routed_layer_entry_point(name, dtype, with_bias):
+    """Router and layer behind one call (routing tables in the workspace) against the oracle chain."""
+    cfg = MoEConfig("routed_" + name, T=33, K=256, N=256, E=10, topk=4, group=64, dtype=dtype, seed=51)
+    say(f"routed layer {cfg} bias={with_bias}")
+    inp = make_inputs(cfg)
+    d = U.DevInputs(inp)
+    bias = skew_bias(cfg.E) if with_bias else None
+    ld = torch.from_numpy(inp.logits).cuda()
+    bd = None if bias is None else torch.from_numpy(bias).cuda()
+    mdt = M.MOE_F16 if dtype == "f16" else M.MOE_BF16
+    ws = torch.empty(M.moe_w4a16_routed_layer_workspace_bytes(cfg.T, cfg.K, cfg.N, cfg.E, cfg.topk, mdt),
+                     dtype=torch.uint8, device="cuda")
+    out = torch.full((cfg.T, cfg.K), float("nan"), dtype=U.TORCH_DT[dtype], device="cuda")
+    M.moe_w4a16_routed_layer(d.X, ld, bd, d.qw1, d.s1, d.z1, d.qw2, d.s2, d.z2, out, cfg.topk, cfg.group, ws)
+    torch.cuda.synchronize()
+    ids_o, w_o = O.route_topk(inp.logits, cfg.topk, bias=bias)
+    want = O.layer(O.decode_bits(inp.x_bits, dtype), ids_o, w_o.astype(np.float32), inp.qw1,
+                   O.decode_bits(inp.s1_bits, dtype), inp.z1, inp.qw2, O.decode_bits(inp.s2_bits, dtype), inp.z2,
+                   cfg.group, dtype)
+    U.assert_close(U.dev_to_f64(out), want, "routed layer entry point")
+    small = torch.empty(256, dtype=torch.uint8, device="cuda")
+    with pytest.raises(M.MoEError) as e:
+        M.moe_w4a16_routed_layer(d.X, ld, bd, d.qw1, d.s1, d.z1, d.qw2, d.s2, d.z2, out, cfg.topk, cfg.group, small)
+    assert e.value.status == 3
+
+
 # ------------------------------------------------------------------ dense GEMM
 @pytest.mark.parametrize("M_rows,N,K,group,dtype", [
     (1, 256, 128, 128, "f16"), (16, 320, 224, 32, "f16"), (17, 256, 1024, 128, "f16"), (50, 768, 1024, 128, "bf16"),
