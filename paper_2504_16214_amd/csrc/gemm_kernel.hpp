@@ -688,15 +688,30 @@ w4a16_gemm_kernel(const GemmParams p) {
             for (int i = 0; i < KW; ++i) wv[s].w[i] = zero_scale[s] ? zword : wv[s].w[i];
           }
         }
+        // activation fragments one packed word ahead of the MFMAs that use them (the reads of
+        // word i+1 are in flight while word i multiplies), so the LDS latency is not exposed
+        // MT times per word
+        u32x4 a_nxt[MT];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+          a_nxt[mt] = *reinterpret_cast<const u32x4*>(xbuf + (mt * 16 + ln) * XP + 16 * (4 * KW * u + lj));
 #pragma unroll
         for (int i = 0; i < KW; ++i) {
+          u32x4 a_cur[MT];
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt) a_cur[mt] = a_nxt[mt];
+          if (i + 1 < KW) {
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+              a_nxt[mt] = *reinterpret_cast<const u32x4*>(
+                  xbuf + (mt * 16 + ln) * XP + 16 * (4 * KW * u + lj + 4 * (i + 1)));
+          }
           u32x4 b[NT];
 #pragma unroll
           for (int s = 0; s < NT; ++s) b[s] = dequant_word<DT, ZM>(wv[s].w[i], ctx[s], uk);
 #pragma unroll
           for (int mt = 0; mt < MT; ++mt) {
-            const u32x4 a = *reinterpret_cast<const u32x4*>(
-                xbuf + (mt * 16 + ln) * XP + 16 * (4 * KW * u + lj + 4 * i));
+            const u32x4 a = a_cur[mt];
 #pragma unroll
             for (int s = 0; s < NT; ++s) {
               // the rescale of each accumulator tile sits right before its first MFMA of the
