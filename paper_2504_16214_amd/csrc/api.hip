@@ -235,8 +235,8 @@ static int pick_k_splits(long long S, int E, int K, int N, int block_m) {
   if (block_m > 32) return 1;
   const long long est_blocks = (S + block_m - 1) / block_m + (S < E ? S : E) / 2;
   const long long wgs = est_blocks * ((K + 127) / 128);
-  if (wgs <= 0 || wgs >= 1024) return 1;
-  long long want = (1536 + wgs - 1) / wgs;
+  if (wgs <= 0 || wgs >= 768) return 1;
+  long long want = (768 + wgs - 1) / wgs;      // about one workgroup per resident slot (3 per CU)
   const int npan = N / 1024;
   if (want > npan) want = npan;
   if (want > 8) want = 8;
