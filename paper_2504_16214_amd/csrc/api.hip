@@ -81,7 +81,7 @@ constexpr int kMaxGroups = 512;
 
 static size_t gemm_lds_bytes(int mt, int nt, int ks, int G, int szr) {
   const size_t M_T = 16 * mt, NW = 16 * nt;
-  return 2 * M_T * (ks * 2 + kXRowPad) + 4 * NW * (ks / 2 + kWRowPad) + (szr ? 0 : (size_t)G * 64 * nt * 4) + M_T * 4;
+  return kXBufs(mt) * M_T * (ks * 2 + kXRowPad) + 4 * NW * (ks / 2 + kWRowPad) + (szr ? 0 : (size_t)G * 64 * nt * 4) + M_T * 4;
 }
 
 // Tile choice.  Tokens per tile follow the bucketing block; the feature width per workgroup is

@@ -292,6 +292,8 @@ __device__ __forceinline__ WordVec<KW> lds_read_words(const unsigned char* p) {
 // few percent of the kernel.)
 constexpr int kXRowPad = 32;
 constexpr int kWRowPad = 32;
+// activation tile buffers in LDS per token-tile size (see TileGeom::XBUFS)
+constexpr int kXBufs(int mt) { return mt == 2 ? 1 : 2; }
 
 template <int MT, int NT, int KS>
 struct TileGeom {
@@ -307,8 +309,11 @@ struct TileGeom {
   static constexpr int RPI = 64 / LPR;       // weight rows per wave load instruction
   static constexpr int WPASS = NW / RPI;     // weight load instructions per stage per wave
   static_assert(XPASS >= 1 && WPASS >= 1, "tile too small for the load mapping");
+  // Activation tile buffers: two (one barrier per stage) except for 32-slot tiles, where a single
+  // buffer (two barriers per stage) is what lets a third workgroup fit on a CU.
+  static constexpr int XBUFS = kXBufs(MT);
   static size_t lds_bytes(int G, int szr) {
-    return (size_t)2 * M_T * XP + (size_t)4 * NW * WP + (szr ? 0 : (size_t)G * N_T * 4) + (size_t)M_T * 4;
+    return (size_t)XBUFS * M_T * XP + (size_t)4 * NW * WP + (szr ? 0 : (size_t)G * N_T * 4) + (size_t)M_T * 4;
   }
 };
 
@@ -367,7 +372,8 @@ w4a16_gemm_kernel(const GemmParams p) {
 
   extern __shared__ __align__(16) unsigned char smem[];
   unsigned char* xs = smem;                                        // [2][M_T][XP]
-  unsigned char* ws_all = xs + 2 * M_T * XP;                       // [4][NW][WP]
+  constexpr int XBUFS = G_::XBUFS;
+  unsigned char* ws_all = xs + XBUFS * M_T * XP;                   // [4][NW][WP]
   uint32_t* sz = reinterpret_cast<uint32_t*>(ws_all + 4 * NW * WP);  // [G][N_T] (absent when SZR)
   int* slot_s = reinterpret_cast<int*>(sz + (SZR ? 0 : p.G * N_T));  // [M_T]
 
@@ -458,7 +464,7 @@ w4a16_gemm_kernel(const GemmParams p) {
   // and the registers are worth more to the compiler (no spills at 64x256).
   constexpr int UNR = SZR ? 4 : 2;      // steps per loop trip (one 1024-k scale panel when SZR)
   constexpr int PDW = MT >= 4 ? 1 : 2;
-  constexpr int PDX = MT >= 4 ? 1 : 2;
+  constexpr int PDX = (MT >= 4 || XBUFS == 1) ? 1 : 2;
   static_assert(UNR % PDW == 0 && UNR % PDX == 0, "ring slots must repeat with the unrolled trip");
   u32x4 xr[PDX][XPASS], wr[PDW][WPASS];
   // A stage past the end still issues its loads (onto the last stage, which was just fetched) so
@@ -852,8 +858,9 @@ w4a16_gemm_kernel(const GemmParams p) {
          MOE_ADVANCE_X_CURSOR()
          MOE_LOAD_W(ld_st, wr[r % PDW])
          MOE_ADVANCE_W_CURSOR()
-         compute_stage(c_st + r, xs + (r % 2) * (M_T * XP), std::integral_constant<int, r>{});
-         MOE_STORE_STAGE(xr[(r + 1) % PDX], wr[(r + 1) % PDW], xs + ((r + 1) % 2) * (M_T * XP))
+         compute_stage(c_st + r, xs + (r % XBUFS) * (M_T * XP), std::integral_constant<int, r>{});
+         if constexpr (XBUFS == 1) __syncthreads();      // everyone is done reading the single buffer
+         MOE_STORE_STAGE(xr[(r + 1) % PDX], wr[(r + 1) % PDW], xs + ((r + 1) % XBUFS) * (M_T * XP))
          __syncthreads();
        }()),
        ...);
