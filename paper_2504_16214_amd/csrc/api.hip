@@ -81,7 +81,7 @@ constexpr int kMaxGroups = 512;
 
 static size_t gemm_lds_bytes(int mt, int nt, int ks, int G, int szr) {
   const size_t M_T = 16 * mt, NW = 16 * nt;
-  return kXBufs(mt) * M_T * (ks * 2 + kXRowPad) + 4 * NW * (ks / 2 + kWRowPad) + (szr ? 0 : (size_t)G * 64 * nt * 4) + M_T * 4;
+  return kXBufs(mt, ks) * M_T * (ks * 2 + kXRowPad) + 4 * NW * (ks / 2 + kWRowPad(ks)) + (szr ? 0 : (size_t)G * 64 * nt * 4) + M_T * 4;
 }
 
 // Tile choice.  Tokens per tile follow the bucketing block; the feature width per workgroup is
@@ -188,7 +188,7 @@ static int run_gemm(const GemmArgs& a, hipStream_t stream) {
   // Split reduction: whole scale panels (4 pipeline stages) per range, every range non-empty.
   int ksp = 1, kspan = a.K_in;
   if (a.k_splits > 1 && szr && a.out_f32 && !fuse) {
-    const int pan = 4 * ks, npan = a.K_in / pan;
+    const int pan = ks >= 256 ? 1024 : 512, npan = a.K_in / pan;   // one scale panel of the kernel
     const int pps = (npan + a.k_splits - 1) / a.k_splits;
     ksp = (npan + pps - 1) / pps;
     kspan = pps * pan;

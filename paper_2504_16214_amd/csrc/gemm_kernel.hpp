@@ -291,9 +291,9 @@ __device__ __forceinline__ WordVec<KW> lds_read_words(const unsigned char* p) {
 // pitch gets rid of the 1.35x.  (End to end the effect is within run-to-run noise: LDS time is a
 // few percent of the kernel.)
 constexpr int kXRowPad = 32;
-constexpr int kWRowPad = 32;
+constexpr int kWRowPad(int ks) { return ks >= 512 ? 16 : 32; }   // 512-k stages: LDS room for three workgroups
 // activation tile buffers in LDS per token-tile size (see TileGeom::XBUFS)
-constexpr int kXBufs(int mt) { return mt == 2 ? 1 : 2; }
+constexpr int kXBufs(int mt, int ks) { return (mt == 2 || ks >= 512) ? 1 : 2; }
 
 template <int MT, int NT, int KS>
 struct TileGeom {
@@ -301,7 +301,7 @@ struct TileGeom {
   static constexpr int NW = 16 * NT;         // features per wave
   static constexpr int N_T = 4 * NW;         // features per workgroup
   static constexpr int XP = KS * 2 + kXRowPad;   // LDS bytes per activation row (padded)
-  static constexpr int WP = KS / 2 + kWRowPad;   // LDS bytes per packed weight row (padded)
+  static constexpr int WP = KS / 2 + kWRowPad(KS);   // LDS bytes per packed weight row (padded)
   static constexpr int CPR = KS / 8;         // 16-byte chunks per activation row
   static constexpr int RPP = 256 / CPR;      // activation rows per cooperative pass
   static constexpr int XPASS = M_T / RPP;    // passes per stage
@@ -311,7 +311,7 @@ struct TileGeom {
   static_assert(XPASS >= 1 && WPASS >= 1, "tile too small for the load mapping");
   // Activation tile buffers: two (one barrier per stage) except for 32-slot tiles, where a single
   // buffer (two barriers per stage) is what lets a third workgroup fit on a CU.
-  static constexpr int XBUFS = kXBufs(MT);
+  static constexpr int XBUFS = kXBufs(MT, KS);
   static size_t lds_bytes(int G, int szr) {
     return (size_t)XBUFS * M_T * XP + (size_t)4 * NW * WP + (szr ? 0 : (size_t)G * N_T * 4) + (size_t)M_T * 4;
   }
@@ -393,7 +393,7 @@ w4a16_gemm_kernel(const GemmParams p) {
   const int row0 = (L / tgroups) * M_T;
   const int e = p.dense ? 0 : p.block_expert_ids[row0 / p.block_m];
   // slot id of a tile row: from the bucketing table, or the row itself for the plain GEMM
-  auto slot_at = [&](int r) { return p.dense ? (r < p.num_slots ? r : p.num_slots) : p.sorted_slot_ids[r]; };
+  auto slot_at = [&](int r) __attribute__((always_inline)) { return p.dense ? (r < p.num_slots ? r : p.num_slots) : p.sorted_slot_ids[r]; };
   if (e < 0 || e >= p.E) return;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -429,7 +429,7 @@ w4a16_gemm_kernel(const GemmParams p) {
       reinterpret_cast<const unsigned char*>(p.qweight) + (size_t)e * p.N_out * (size_t)(K_in >> 1) + (size_t)(k0 >> 1);
   uint32_t woff[WPASS];      // rows of the tile the LOAD cursor is in
   const int wl_row = lane / LPR, wl_chunk = lane % LPR;
-  auto set_w_rows = [&](int tile) {
+  auto set_w_rows = [&](int tile) __attribute__((always_inline)) {
 #pragma unroll
     for (int q = 0; q < WPASS; ++q) {
       const int rw = q * RPI + wl_row;
@@ -462,8 +462,12 @@ w4a16_gemm_kernel(const GemmParams p) {
   // cost a workgroup per CU at 16x128 tiles and buy nothing at 32x128, where occupancy is the same.
   // Large token tiles spend several microseconds per stage, one stage of flight time is enough
   // and the registers are worth more to the compiler (no spills at 64x256).
-  constexpr int UNR = SZR ? 4 : 2;      // steps per loop trip (one 1024-k scale panel when SZR)
-  constexpr int PDW = MT >= 4 ? 1 : 2;
+  // steps per loop trip; with register scales one scale panel: 1024 k (512 k for 128-k stages)
+  constexpr int UNR = SZR ? (KS >= 256 ? 1024 / KS : 4) : 2;
+  // (512-k stages -- 256-byte row segments, one stage ahead, single activation buffer, three
+  // workgroups per CU -- were measured 3-5 % slower than 256-k stages on the decode shapes; the
+  // geometry below still covers them)
+  constexpr int PDW = (MT >= 4 || KS >= 512) ? 1 : 2;
   constexpr int PDX = (MT >= 4 || XBUFS == 1) ? 1 : 2;
   static_assert(UNR % PDW == 0 && UNR % PDX == 0, "ring slots must repeat with the unrolled trip");
   u32x4 xr[PDX][XPASS], wr[PDW][WPASS];
@@ -546,7 +550,7 @@ w4a16_gemm_kernel(const GemmParams p) {
   uint32_t s_cur[NT][PG / 2], s_nxt[NT][PG / 2];
   uint32_t z_cur[NT][(PG + 3) / 4], z_nxt[NT][(PG + 3) / 4];
   uint32_t z4_cur[NT][(PG + 3) / 4];               // z_cur with every byte shifted left by four
-  auto adopt_zero_points = [&](const uint32_t(&zv)[NT][(PG + 3) / 4]) {
+  auto adopt_zero_points = [&](const uint32_t(&zv)[NT][(PG + 3) / 4]) __attribute__((always_inline)) {
 #pragma unroll
     for (int s = 0; s < NT; ++s)
 #pragma unroll
@@ -557,7 +561,7 @@ w4a16_gemm_kernel(const GemmParams p) {
   };
   uint32_t sz_row[NT];                             // element offset of the lane's row (host checks the range)
   const int G_ext = ksp > 1 ? K_ext / 128 : p.G;   // groups in the reduction range (SZR: group 128)
-  auto load_sz = [&](int g0, uint32_t(&sv)[NT][PG / 2], uint32_t(&zv)[NT][(PG + 3) / 4]) {
+  auto load_sz = [&](int g0, uint32_t(&sv)[NT][PG / 2], uint32_t(&zv)[NT][(PG + 3) / 4]) __attribute__((always_inline)) {
     if (g0 > G_ext - PG) g0 = G_ext - PG;           // clamp onto the last panel of the range
 #pragma unroll
     for (int s = 0; s < NT; ++s) {
@@ -575,7 +579,7 @@ w4a16_gemm_kernel(const GemmParams p) {
       }
     }
   };
-  auto set_sz_rows = [&](int tile) {
+  auto set_sz_rows = [&](int tile) __attribute__((always_inline)) {
 #pragma unroll
     for (int s = 0; s < NT; ++s) {
       int wrow, ocol;
@@ -641,7 +645,7 @@ w4a16_gemm_kernel(const GemmParams p) {
 #pragma unroll
   for (int s = 0; s < NT; ++s) unit[s] = 1.f;
 
-  auto compute_stage = [&](int st, const unsigned char* xbuf, auto rc) {
+  auto compute_stage = [&](int st, const unsigned char* xbuf, auto rc) __attribute__((always_inline)) {
     constexpr int R = decltype(rc)::value;       // step index inside the unrolled trip
     const int left = (K_ext - st * KS) / CK;     // <= 0 for a stage past the end
     // (the run-time bound also keeps the chunk-steps apart for the scheduler: with a constant bound
@@ -769,7 +773,7 @@ w4a16_gemm_kernel(const GemmParams p) {
   __syncthreads();
 
   // ---- store one finished feature tile: one rounding to the 16-bit type, rows by slot id ----
-  auto store_tile = [&](int tile) {
+  auto store_tile = [&](int tile) __attribute__((always_inline)) {
     if constexpr (RS) {
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt)
