@@ -131,6 +131,40 @@ def dequant(qweight, scales, zeros, group: int) -> np.ndarray:
 
 
 # --------------------------------------------------------------------------
+# offline weight repack (a permutation of 16-byte chunks, no arithmetic)
+# --------------------------------------------------------------------------
+def repack_qweight(qweight, paired: bool) -> np.ndarray:
+    """Packed weights [E, N_out, K_in/8] int32 -> the operand-order layout
+    [E, N_out/16, K_in/128, 64, 4] int32 the prepacked kernels stream.
+
+    The matrix is cut into blocks of 16 feature rows x 128 reduction indices (64 packed bytes per
+    row).  Block (b, c) of an expert is stored as 64 consecutive 16-byte chunks; chunk 16*j + n
+    holds bytes [64*c + 16*j, 64*c + 16*j + 16) of the block's row n (j = 0..3, n = 0..15), which
+    is what lane 16*j + n of a wave feeds to its four matrix instructions of that step.  Blocks
+    of one row set follow each other along the reduction, row sets follow each other.
+
+    paired = False: row set b is rows 16*b .. 16*b + 15 (gate/up weights).
+    paired = True : row sets come in pairs over runs of 32 rows, set 2*q taking the even and
+    set 2*q + 1 the odd rows of rows 32*q .. 32*q + 31 (down-projection weights: a lane then owns
+    two adjacent output columns).  Needs N_out % 32 == 0."""
+    q = np.ascontiguousarray(qweight)
+    E, N_out, KW = q.shape
+    K_in = 8 * KW
+    assert K_in % 128 == 0 and N_out % (32 if paired else 16) == 0
+    out = np.empty((E, N_out // 16, K_in // 128, 64, 4), dtype=np.int32)
+    for b in range(N_out // 16):
+        if paired:
+            rows = [32 * (b // 2) + 2 * n + (b & 1) for n in range(16)]
+        else:
+            rows = [16 * b + n for n in range(16)]
+        for c in range(K_in // 128):
+            for j in range(4):
+                for n in range(16):
+                    out[:, b, c, 16 * j + n, :] = q[:, rows[n], 16 * c + 4 * j: 16 * c + 4 * j + 4]
+    return out
+
+
+# --------------------------------------------------------------------------
 # routing weights (input preparation; kept here to pin the generator's router)
 # --------------------------------------------------------------------------
 def route_topk(logits, topk: int, bias=None):

@@ -256,6 +256,36 @@ def test_dense_gemm_closed_form_and_independent_dequant():
     np.testing.assert_array_equal(Cg, O.dense_gemm(A, words.view(np.int32), sr, zr, g))
 
 
+@pytest.mark.parametrize("paired", [False, True])
+def test_repack_is_the_documented_permutation(paired):
+    """Every packed word lands exactly once; lane (n, j), word i of block (b, c) carries the eight
+    weights of row r(b, n) at reduction indices 128c + 8(4j + i) .. + 7 (checked through the
+    oracle's own nibble unpack of the ORIGINAL tensor); undoing the permutation with a scalar loop
+    gives the original back."""
+    E, N, K = 2, 64, 256
+    q = np.arange(E * N * (K // 8), dtype=np.int64).reshape(E, N, K // 8).astype(np.int32)   # all words distinct
+    r = O.repack_qweight(q, paired)
+    assert r.shape == (E, N // 16, K // 128, 64, 4)
+    assert np.array_equal(np.sort(r.reshape(-1)), np.sort(q.reshape(-1)))
+    rng = np.random.default_rng(9)
+    qr = rng.integers(0, 2 ** 32, size=(E, N, K // 8), dtype=np.uint32).view(np.int32)
+    rr = O.repack_qweight(qr, paired)
+    W = O.unpack_int4(qr)                                     # [E, N, K] nibbles of the original
+    back = np.empty_like(qr)
+    for e in range(E):
+        for b in range(N // 16):
+            for c in range(K // 128):
+                for j in range(4):
+                    for n in range(16):
+                        row = 32 * (b // 2) + 2 * n + (b & 1) if paired else 16 * b + n
+                        for i in range(4):
+                            word = int(rr[e, b, c, 16 * j + n, i]) & 0xFFFFFFFF
+                            k0 = 128 * c + 8 * (4 * j + i)
+                            assert [(word >> (4 * t)) & 15 for t in range(8)] == list(W[e, row, k0:k0 + 8])
+                            back[e, row, (k0 // 8)] = rr[e, b, c, 16 * j + n, i]
+    assert np.array_equal(back, qr)
+
+
 def test_skew_bias_formula():
     b = skew_bias(8)
     np.testing.assert_allclose(b, [2 * np.log(1 / (r ** 1.2)) for r in range(1, 9)], rtol=1e-6)
