@@ -158,6 +158,29 @@ int moe_w4a16_layer(const void* X, const int32_t* topk_ids, const float* topk_we
                     moe_dtype dt, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Offline weight repack and the layer on repacked weights (the "offline repack into the matrix
+ * unit's operand order" that weight-only kernels of this kind use; the paper's kernels move packed
+ * weights in their consumption order as well, Fig. 5 / Table III).
+ *
+ * moe_repack_qweight: qweight [E, N_out, K_in/8] -> out (same size, must not alias): blocks of
+ * 16 rows x 128 reduction indices stored as 64 consecutive 16-byte chunks, chunk 16*j + n =
+ * bytes [64c + 16j, 64c + 16j + 16) of the block's row n; blocks of a row set consecutive along
+ * the reduction.  paired = 0: row set b = rows 16b .. 16b+15 (use for W1).  paired = 1: row sets
+ * 2q / 2q+1 = even / odd rows of rows 32q .. 32q+31 (use for W2).  K_in % 128 == 0,
+ * N_out % 16 == 0 (32 if paired), both pointers 16-byte aligned.  A pure permutation.
+ *
+ * moe_w4a16_layer_prepacked: moe_w4a16_layer with qw1p = repack(W1, paired 0) and
+ * qw2p = repack(W2, paired 1); scales and zero points stay in their original layout.
+ * Needs group_size == 128, K % 1024 == 0, N % 1024 == 0.  Same results bit for bit.
+ */
+int moe_repack_qweight(const int32_t* qweight, int E, int N_out, int K_in, int paired, int32_t* out, void* stream);
+int moe_w4a16_layer_prepacked(const void* X, const int32_t* topk_ids, const float* topk_weights,
+                              const int32_t* qw1p, const void* s1, const uint8_t* z1,
+                              const int32_t* qw2p, const void* s2, const uint8_t* z2,
+                              void* out, int T, int K, int N, int E, int topk, int group_size,
+                              moe_dtype dt, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Router + layer on one stream: moe_route_topk into tables held in the workspace, then
  * moe_w4a16_layer.  Arguments as for the two; `workspace` of at least
  * moe_w4a16_routed_layer_workspace_bytes(...) bytes, 256-byte aligned.

@@ -19,6 +19,7 @@ EXPORTS = [
     "moe_set_stage_events", "moe_set_tile_override", "moe_set_scale_path", "moe_set_tiles_per_workgroup", "moe_set_reduction_splits", "moe_layer_block_m",
     "moe_w4a16_dense_gemm", "moe_route_topk", "moe_probe_stream_read", "moe_probe_mfma",
     "moe_w4a16_routed_layer_workspace_bytes", "moe_w4a16_routed_layer",
+    "moe_repack_qweight", "moe_w4a16_layer_prepacked",
 ]
 
 
@@ -63,6 +64,10 @@ def load_library() -> ctypes.CDLL:
     lib.moe_w4a16_routed_layer_workspace_bytes.argtypes = [i32] * 6
     lib.moe_w4a16_routed_layer.restype = i32
     lib.moe_w4a16_routed_layer.argtypes = [vp] * 10 + [i32] * 7 + [vp, sz, vp]
+    lib.moe_repack_qweight.restype = i32
+    lib.moe_repack_qweight.argtypes = [vp, i32, i32, i32, i32, vp, vp]
+    lib.moe_w4a16_layer_prepacked.restype = i32
+    lib.moe_w4a16_layer_prepacked.argtypes = [vp] * 10 + [i32] * 7 + [vp, sz, vp]
     lib.moe_silu_mul.restype = i32
     lib.moe_silu_mul.argtypes = [vp, vp, i32, i32, i32, vp]
     lib.moe_combine.restype = i32
@@ -206,6 +211,24 @@ def moe_w4a16_routed_layer(X, logits, bias, qw1, s1, z1, qw2, s2, z2, out, topk,
     _check(load_library().moe_w4a16_routed_layer(
         _ptr(X), _ptr(logits), _ptr(bias), _ptr(qw1), _ptr(s1), _ptr(z1), _ptr(qw2), _ptr(s2), _ptr(z2),
         _ptr(out), T, K, N2 // 2, E, topk, group_size, _dt(X), _ptr(workspace),
+        workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+def moe_repack_qweight(qweight, paired: bool, out, stream=None) -> None:
+    """qweight [E, N_out, K/8] int32 -> out (same shape / size), operand-order layout."""
+    E, N_out, kw = qweight.shape
+    _check(load_library().moe_repack_qweight(_ptr(qweight), E, N_out, kw * 8, 1 if paired else 0, _ptr(out),
+                                             _stream(stream)))
+
+
+def moe_w4a16_layer_prepacked(X, topk_ids, topk_weights, qw1p, s1, z1, qw2p, s2, z2, out, group_size, workspace,
+                              stream=None) -> None:
+    T, K = X.shape
+    E, N2 = s1.shape[0], s1.shape[1]      # s1 is [E, 2N, K/g]; the repacked weight tensors carry no shape
+    topk = topk_ids.shape[1]
+    _check(load_library().moe_w4a16_layer_prepacked(
+        _ptr(X), _ptr(topk_ids), _ptr(topk_weights), _ptr(qw1p), _ptr(s1), _ptr(z1), _ptr(qw2p), _ptr(s2),
+        _ptr(z2), _ptr(out), T, K, N2 // 2, E, topk, group_size, _dt(X), _ptr(workspace),
         workspace.numel() * workspace.element_size(), _stream(stream)))
 
 

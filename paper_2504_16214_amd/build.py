@@ -28,6 +28,8 @@ def _units():
     for dt in (0, 1):
         for kw in (1, 2, 4):
             units.append(("gemm_inst.hip", f"gemm_inst_dt{dt}_kw{kw}.o", [f"-DMOE_DT={dt}", f"-DMOE_KW={kw}"]))
+    for dt in (0, 1):      # operand-order (prepacked) weight variants, group 128 only
+        units.append(("gemm_inst.hip", f"gemm_inst_pre_dt{dt}.o", [f"-DMOE_DT={dt}", "-DMOE_KW=4", "-DMOE_PRE=1"]))
     for src in ("align.hip", "elementwise.hip", "router.hip", "api.hip"):
         units.append((src, src.replace(".hip", ".o"), []))
     return units

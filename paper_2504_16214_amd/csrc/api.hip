@@ -13,6 +13,7 @@ namespace moe {
 int launch_align(const int32_t*, int, int, int, int, int32_t*, int32_t*, int32_t*, int32_t*, int32_t*,
                  hipStream_t);
 int launch_silu_mul(const void*, void*, long long, int, int, hipStream_t);
+int launch_repack(const int32_t*, int, int, int, int, int32_t*, hipStream_t);
 int launch_route_topk(const float*, const float*, int, int, int, int32_t*, float*, hipStream_t);
 int launch_stream_read(const void*, size_t, uint32_t*, int, hipStream_t);
 int launch_mfma_loop(float*, int, int, hipStream_t);
@@ -21,7 +22,9 @@ int launch_combine(const void*, int, int, const float*, const int32_t*, int, voi
 
 // ---- table of compiled GEMM variants ------------------------------------------------------
 #define MOE_DECL(DT, MT, NT, KS, KW, F, Z) \
-  extern template int launch_w4a16_gemm<DT, MT, NT, KS, KW, F, Z>(const GemmParams&, int, hipStream_t);
+  extern template int launch_w4a16_gemm<DT, MT, NT, KS, KW, F, Z, 0>(const GemmParams&, int, hipStream_t);
+#define MOE_DECL_PRE(DT, MT, NT, KS, F) \
+  extern template int launch_w4a16_gemm<DT, MT, NT, KS, 4, F, 1, 1>(const GemmParams&, int, hipStream_t);
 #define MOE_ALL_DT_KW(M, MT, NT, KS, F) \
   M(0, MT, NT, KS, 1, F, 0) M(0, MT, NT, KS, 2, F, 0) M(0, MT, NT, KS, 4, F, 0) \
   M(1, MT, NT, KS, 1, F, 0) M(1, MT, NT, KS, 2, F, 0) M(1, MT, NT, KS, 4, F, 0)
@@ -31,10 +34,14 @@ int launch_combine(const void*, int, int, const float*, const int32_t*, int, voi
 #define MOE_TILE_SZR(MT, NT, KS) MOE_DECL(0, MT, NT, KS, 4, 0, 1) MOE_DECL(1, MT, NT, KS, 4, 0, 1)
 #define MOE_TILE_SZR_FUSE(MT, NT, KS) MOE_DECL(0, MT, NT, KS, 4, 1, 1) MOE_DECL(1, MT, NT, KS, 4, 1, 1)
 #include "gemm_variants_szr.def"
+#define MOE_TILE_PRE(MT, NT, KS) MOE_DECL_PRE(0, MT, NT, KS, 0) MOE_DECL_PRE(1, MT, NT, KS, 0)
+#define MOE_TILE_PRE_FUSE(MT, NT, KS) MOE_DECL_PRE(0, MT, NT, KS, 1) MOE_DECL_PRE(1, MT, NT, KS, 1)
+#include "gemm_variants_pre.def"
 
 typedef int (*GemmLaunchFn)(const GemmParams&, int, hipStream_t);
-struct GemmVariant { int dt, mt, nt, ks, kw, fuse, szr; GemmLaunchFn fn; };
-#define MOE_ENTRY(DT, MT, NT, KS, KW, F, Z) {DT, MT, NT, KS, KW, F, Z, &launch_w4a16_gemm<DT, MT, NT, KS, KW, F, Z>},
+struct GemmVariant { int dt, mt, nt, ks, kw, fuse, szr, pre; GemmLaunchFn fn; };
+#define MOE_ENTRY(DT, MT, NT, KS, KW, F, Z) {DT, MT, NT, KS, KW, F, Z, 0, &launch_w4a16_gemm<DT, MT, NT, KS, KW, F, Z, 0>},
+#define MOE_ENTRY_PRE(DT, MT, NT, KS, F) {DT, MT, NT, KS, 4, F, 1, 1, &launch_w4a16_gemm<DT, MT, NT, KS, 4, F, 1, 1>},
 static const GemmVariant kVariants[] = {
 #define MOE_TILE(MT, NT, KS) MOE_ALL_DT_KW(MOE_ENTRY, MT, NT, KS, 0)
 #define MOE_TILE_FUSE(MT, NT, KS) MOE_ALL_DT_KW(MOE_ENTRY, MT, NT, KS, 1)
@@ -42,11 +49,15 @@ static const GemmVariant kVariants[] = {
 #define MOE_TILE_SZR(MT, NT, KS) MOE_ENTRY(0, MT, NT, KS, 4, 0, 1) MOE_ENTRY(1, MT, NT, KS, 4, 0, 1)
 #define MOE_TILE_SZR_FUSE(MT, NT, KS) MOE_ENTRY(0, MT, NT, KS, 4, 1, 1) MOE_ENTRY(1, MT, NT, KS, 4, 1, 1)
 #include "gemm_variants_szr.def"
+#define MOE_TILE_PRE(MT, NT, KS) MOE_ENTRY_PRE(0, MT, NT, KS, 0) MOE_ENTRY_PRE(1, MT, NT, KS, 0)
+#define MOE_TILE_PRE_FUSE(MT, NT, KS) MOE_ENTRY_PRE(0, MT, NT, KS, 1) MOE_ENTRY_PRE(1, MT, NT, KS, 1)
+#include "gemm_variants_pre.def"
 };
 
-static const GemmVariant* find_variant(int dt, int mt, int nt, int kw, int fuse, int szr) {
+static const GemmVariant* find_variant(int dt, int mt, int nt, int kw, int fuse, int szr, int pre = 0) {
   for (const GemmVariant& v : kVariants)
-    if (v.dt == dt && v.mt == mt && v.nt == nt && v.kw == kw && v.fuse == fuse && v.szr == szr) return &v;
+    if (v.dt == dt && v.mt == mt && v.nt == nt && v.kw == kw && v.fuse == fuse && v.szr == szr && v.pre == pre)
+      return &v;
   return nullptr;
 }
 
@@ -86,7 +97,7 @@ static size_t gemm_lds_bytes(int mt, int nt, int ks, int G, int szr) {
 
 // Tile choice.  Tokens per tile follow the bucketing block; the feature width per workgroup is
 // as wide as LDS allows while still giving every CU a couple of workgroups (256 CUs).
-static int choose_tile(int num_slots, int E, int feat, int G, int block_m, int fuse, int szr_ok, int dt,
+static int choose_tile(int num_slots, int E, int feat, int G, int block_m, int fuse, int szr_ok, int dt, int pre,
                        int& mt, int& nt, int& ks, int& szr) {
   mt = block_m / 16;
   if (mt > 8) mt = 8;
@@ -98,13 +109,13 @@ static int choose_tile(int num_slots, int E, int feat, int G, int block_m, int f
   const int min_nt = (fuse || mt >= 4) ? 2 : 1;
   // register-resident scales when the shape allows it and such a variant is compiled
   auto pick_szr = [&](int nt_) {
-    if (g_scale_path == 1 || !szr_ok) return 0;
-    return find_variant(dt, mt, nt_, 4, fuse, 1) ? 1 : 0;
+    if ((g_scale_path == 1 && !pre) || !szr_ok) return 0;
+    return find_variant(dt, mt, nt_, 4, fuse, 1, pre) ? 1 : 0;
   };
   if (g_force_nt > 0) {
     nt = g_force_nt;
     szr = pick_szr(nt);
-    if (g_scale_path == 2 && !szr) return -1;
+    if ((g_scale_path == 2 || pre) && !szr) return -1;
     return (nt >= min_nt && (nt == 1 || nt == 2 || nt == 4) && gemm_lds_bytes(mt, nt, ks, G, szr) <= kLdsLimit) ? 0 : -1;
   }
   const long long est_blocks = (num_slots + 16 * mt - 1) / (16 * mt) + (num_slots < E ? num_slots : E) / 2;
@@ -114,7 +125,7 @@ static int choose_tile(int num_slots, int E, int feat, int G, int block_m, int f
     const int fpw = fuse ? 32 * nt : 64 * nt;
     const long long wgs = est_blocks * ((feat + fpw - 1) / fpw);
     szr = pick_szr(nt);
-    if (g_scale_path == 2 && !szr) { if (nt == min_nt) return -1; nt >>= 1; continue; }
+    if ((g_scale_path == 2 || pre) && !szr) { if (nt == min_nt) return -1; nt >>= 1; continue; }
     const bool fits = gemm_lds_bytes(mt, nt, ks, G, szr) <= kLdsLimit;
     // 128-feature tiles stay even when they leave fewer than two workgroups per CU: measured
     // faster than twice as many 64-feature tiles (same bytes in flight, less activation staging)
@@ -131,6 +142,7 @@ struct GemmArgs {
   int num_slots, E, N_out, K_in, group, block_m, dt;
   void* C; int ldc; int fuse_half_n; int out_f32;
   int dense = 0;             // 1: plain GEMM, no routing tables (the three table pointers are null)
+  int pre = 0;               // 1: qweight is in the operand-order layout of moe_repack_qweight
   int k_splits = 1;          // wanted reduction splits (float32 output planes num_slots*ldc apart)
   int* used_splits = nullptr;  // out: the number of planes the launch really wrote
 };
@@ -165,10 +177,13 @@ static int run_gemm(const GemmArgs& a, hipStream_t stream) {
   int mt, nt, ks, szr;
   const int sz_vec = (G % 8 == 0 && (uintptr_t)a.scales % 16 == 0 && (uintptr_t)a.zeros % 8 == 0) ? 1 : 0;
   const int szr_ok = sz_vec && a.group == 128 && (long long)a.E * a.N_out * G < (1LL << 31);
-  if (choose_tile(a.num_slots, a.E, feat, G, a.block_m, fuse, szr_ok, a.dt, mt, nt, ks, szr) != 0)
+  if (a.pre && (!szr_ok || (!fuse && a.N_out % 32 != 0)))
+    return fail(MOE_UNSUPPORTED_SHAPE, "operand-order weights need group_size 128, K_in %% 1024 == 0, 16-byte aligned "
+                "scale rows and (down projection) N_out %% 32 == 0");
+  if (choose_tile(a.num_slots, a.E, feat, G, a.block_m, fuse, szr_ok, a.dt, a.pre, mt, nt, ks, szr) != 0)
     return fail(MOE_UNSUPPORTED_SHAPE, "no GEMM tile fits (K_in/group_size = %d, block_m = %d, override %d/%d)",
                 G, a.block_m, g_force_mt, g_force_nt);
-  const GemmVariant* v = find_variant(a.dt, mt, nt, kw, fuse, szr);
+  const GemmVariant* v = find_variant(a.dt, mt, nt, kw, fuse, szr, a.pre);
   if (!v) return fail(MOE_UNSUPPORTED_SHAPE, "GEMM variant mt=%d nt=%d kw=%d fuse=%d szr=%d is not compiled", mt, nt, kw, fuse, szr);
 
   GemmParams p;
@@ -375,11 +390,13 @@ int moe_layer_block_m(int T, int E, int topk) {
   return pick_block_m((long long)T * topk, E);
 }
 
-int moe_w4a16_layer(const void* X, const int32_t* topk_ids, const float* topk_weights,
-                    const int32_t* qw1, const void* s1, const uint8_t* z1,
-                    const int32_t* qw2, const void* s2, const uint8_t* z2,
-                    void* out, int T, int K, int N, int E, int topk, int group_size, moe_dtype dt,
-                    void* workspace, size_t workspace_bytes, void* stream_v) {
+}  // extern "C"
+
+static int layer_impl(const void* X, const int32_t* topk_ids, const float* topk_weights,
+                      const int32_t* qw1, const void* s1, const uint8_t* z1,
+                      const int32_t* qw2, const void* s2, const uint8_t* z2,
+                      void* out, int T, int K, int N, int E, int topk, int group_size, moe_dtype dt,
+                      void* workspace, size_t workspace_bytes, void* stream_v, int pre) {
   hipStream_t stream = (hipStream_t)stream_v;
   if (T < 0 || K < 1 || N < 1 || E < 1 || topk < 1 || group_size < 1)
     return fail(MOE_INVALID_ARGUMENT, "need T >= 0 and positive K, N, E, topk, group_size");
@@ -422,6 +439,7 @@ int moe_w4a16_layer(const void* X, const int32_t* topk_ids, const float* topk_we
   if (ev) (void)hipEventRecord((hipEvent_t)g_events[1], stream);
   GemmArgs g1{X, topk, qw1, s1, z1, sorted, blocks, num_padded, (int)S, E, 2 * N, K, group_size, block_m,
               (int)dt, act, N, N, 0};
+  g1.pre = pre;
   int st = run_gemm(g1, stream);
   if (st != MOE_OK) return st;
 
@@ -435,6 +453,7 @@ int moe_w4a16_layer(const void* X, const int32_t* topk_ids, const float* topk_we
   int planes = 1;
   g2.k_splits = want;
   g2.used_splits = &planes;
+  g2.pre = pre;
   st = run_gemm(g2, stream);
   if (st != MOE_OK) return st;
 
@@ -442,6 +461,38 @@ int moe_w4a16_layer(const void* X, const int32_t* topk_ids, const float* topk_we
   err = launch_combine(Y, 1, planes, topk_weights, topk_ids, E, out, T, topk, K, (int)dt, stream);
   if (err != 0) return hip_fail(err, "combine launch");
   if (ev) (void)hipEventRecord((hipEvent_t)g_events[4], stream);
+  return MOE_OK;
+}
+
+extern "C" {
+
+int moe_w4a16_layer(const void* X, const int32_t* topk_ids, const float* topk_weights,
+                    const int32_t* qw1, const void* s1, const uint8_t* z1,
+                    const int32_t* qw2, const void* s2, const uint8_t* z2,
+                    void* out, int T, int K, int N, int E, int topk, int group_size, moe_dtype dt,
+                    void* workspace, size_t workspace_bytes, void* stream) {
+  return layer_impl(X, topk_ids, topk_weights, qw1, s1, z1, qw2, s2, z2, out, T, K, N, E, topk, group_size, dt,
+                    workspace, workspace_bytes, stream, 0);
+}
+
+int moe_w4a16_layer_prepacked(const void* X, const int32_t* topk_ids, const float* topk_weights,
+                              const int32_t* qw1p, const void* s1, const uint8_t* z1,
+                              const int32_t* qw2p, const void* s2, const uint8_t* z2,
+                              void* out, int T, int K, int N, int E, int topk, int group_size, moe_dtype dt,
+                              void* workspace, size_t workspace_bytes, void* stream) {
+  return layer_impl(X, topk_ids, topk_weights, qw1p, s1, z1, qw2p, s2, z2, out, T, K, N, E, topk, group_size, dt,
+                    workspace, workspace_bytes, stream, 1);
+}
+
+int moe_repack_qweight(const int32_t* qweight, int E, int N_out, int K_in, int paired, int32_t* out, void* stream) {
+  if (E < 1 || N_out < 1 || K_in < 1) return fail(MOE_INVALID_ARGUMENT, "need positive E, N_out, K_in");
+  if (K_in % 128 != 0 || N_out % (paired ? 32 : 16) != 0)
+    return fail(MOE_UNSUPPORTED_SHAPE, "repack needs K_in %% 128 == 0 and N_out %% %d == 0", paired ? 32 : 16);
+  if (!qweight || !out || qweight == out) return fail(MOE_INVALID_ARGUMENT, "null or aliased pointer argument");
+  if ((((uintptr_t)qweight | (uintptr_t)out) % 16) != 0)
+    return fail(MOE_INVALID_ARGUMENT, "qweight and out must be 16-byte aligned");
+  const int err = launch_repack(qweight, E, N_out, K_in, paired ? 1 : 0, out, (hipStream_t)stream);
+  if (err != 0) return hip_fail(err, "repack launch");
   return MOE_OK;
 }
 

@@ -111,6 +111,33 @@ static int grid_for(long long work_items) {
   return (int)blocks;
 }
 
+// Offline repack of packed weights into operand order: a permutation of 16-byte chunks.
+// Output chunk (((e*NB + b)*NC + c)*64 + 16*j + n) = bytes [64c + 16j, +16) of row r(b, n) of
+// expert e; r = 16b + n, or (paired) 32*(b/2) + 2n + (b&1).
+typedef uint32_t rp_u32x4 __attribute__((ext_vector_type(4)));
+__global__ void __launch_bounds__(256)
+repack_qweight_kernel(const rp_u32x4* __restrict__ in, rp_u32x4* __restrict__ out, long long total,
+                      int N_out, int NB, int NC, int paired) {
+  for (long long o = (long long)blockIdx.x * 256 + threadIdx.x; o < total; o += (long long)gridDim.x * 256) {
+    const int l = (int)(o & 63);
+    long long t = o >> 6;
+    const int c = (int)(t % NC); t /= NC;
+    const int b = (int)(t % NB);
+    const long long e = t / NB;
+    const int n = l & 15, j = l >> 4;
+    const int row = paired ? 32 * (b >> 1) + 2 * n + (b & 1) : 16 * b + n;
+    out[o] = in[(e * N_out + row) * (long long)(4 * NC) + 4 * c + j];
+  }
+}
+
+int launch_repack(const int32_t* q, int E, int N_out, int K_in, int paired, int32_t* out, hipStream_t stream) {
+  const int NB = N_out / 16, NC = K_in / 128;
+  const long long total = (long long)E * NB * NC * 64;
+  hipLaunchKernelGGL(repack_qweight_kernel, dim3(grid_for(total)), dim3(256), 0, stream,
+                     (const rp_u32x4*)q, (rp_u32x4*)out, total, N_out, NB, NC, paired);
+  return (int)hipGetLastError();
+}
+
 int launch_silu_mul(const void* H, void* act, long long S, int N, int dt, hipStream_t stream) {
   const long long items = S * (((N & 7) == 0) ? (N >> 3) : N);
   if (items == 0) return 0;

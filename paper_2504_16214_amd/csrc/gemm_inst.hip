@@ -11,10 +11,10 @@
 
 namespace moe {
 
-template <int DT, int MT, int NT, int KS, int KW, int FUSE, int SZR>
+template <int DT, int MT, int NT, int KS, int KW, int FUSE, int SZR, int PRE>
 int launch_w4a16_gemm(const GemmParams& p, int grid, hipStream_t stream) {
-  auto kern = w4a16_gemm_kernel<DT, MT, NT, KS, KW, FUSE, SZR>;
-  const size_t lds = TileGeom<MT, NT, KS>::lds_bytes(p.G, SZR);
+  auto kern = w4a16_gemm_kernel<DT, MT, NT, KS, KW, FUSE, SZR, PRE>;
+  const size_t lds = TileGeom<MT, NT, KS>::lds_bytes(p.G, SZR, PRE);
   if (lds > 64 * 1024) {
     // Raise the dynamic LDS limit of this kernel, once per device and size (the attribute is
     // per device; remembering it per device keeps a second GPU of the process correct).
@@ -34,19 +34,30 @@ int launch_w4a16_gemm(const GemmParams& p, int grid, hipStream_t stream) {
   return (int)hipGetLastError();
 }
 
+#ifndef MOE_PRE
 #define MOE_TILE(MT, NT, KS) \
-  template int launch_w4a16_gemm<MOE_DT, MT, NT, KS, MOE_KW, 0, 0>(const GemmParams&, int, hipStream_t);
+  template int launch_w4a16_gemm<MOE_DT, MT, NT, KS, MOE_KW, 0, 0, 0>(const GemmParams&, int, hipStream_t);
 #define MOE_TILE_FUSE(MT, NT, KS) \
-  template int launch_w4a16_gemm<MOE_DT, MT, NT, KS, MOE_KW, 1, 0>(const GemmParams&, int, hipStream_t);
+  template int launch_w4a16_gemm<MOE_DT, MT, NT, KS, MOE_KW, 1, 0, 0>(const GemmParams&, int, hipStream_t);
 #include "gemm_variants.def"
 
 // register-resident scale variants: group 128 only (KW == 4), small token tiles
 #if MOE_KW == 4
 #define MOE_TILE_SZR(MT, NT, KS) \
-  template int launch_w4a16_gemm<MOE_DT, MT, NT, KS, 4, 0, 1>(const GemmParams&, int, hipStream_t);
+  template int launch_w4a16_gemm<MOE_DT, MT, NT, KS, 4, 0, 1, 0>(const GemmParams&, int, hipStream_t);
 #define MOE_TILE_SZR_FUSE(MT, NT, KS) \
-  template int launch_w4a16_gemm<MOE_DT, MT, NT, KS, 4, 1, 1>(const GemmParams&, int, hipStream_t);
+  template int launch_w4a16_gemm<MOE_DT, MT, NT, KS, 4, 1, 1, 0>(const GemmParams&, int, hipStream_t);
 #include "gemm_variants_szr.def"
+#endif
+#endif  // !MOE_PRE
+
+// operand-order (prepacked) weights: own translation unit (-DMOE_PRE) so it builds in parallel
+#if defined(MOE_PRE) && MOE_KW == 4
+#define MOE_TILE_PRE(MT, NT, KS) \
+  template int launch_w4a16_gemm<MOE_DT, MT, NT, KS, 4, 0, 1, 1>(const GemmParams&, int, hipStream_t);
+#define MOE_TILE_PRE_FUSE(MT, NT, KS) \
+  template int launch_w4a16_gemm<MOE_DT, MT, NT, KS, 4, 1, 1, 1>(const GemmParams&, int, hipStream_t);
+#include "gemm_variants_pre.def"
 #endif
 
 }  // namespace moe

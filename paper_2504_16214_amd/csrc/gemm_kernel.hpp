@@ -312,8 +312,9 @@ struct TileGeom {
   // Activation tile buffers: two (one barrier per stage) except for 32-slot tiles, where a single
   // buffer (two barriers per stage) is what lets a third workgroup fit on a CU.
   static constexpr int XBUFS = kXBufs(MT, KS);
-  static size_t lds_bytes(int G, int szr) {
-    return (size_t)XBUFS * M_T * XP + (size_t)4 * NW * WP + (szr ? 0 : (size_t)G * N_T * 4) + (size_t)M_T * 4;
+  static size_t lds_bytes(int G, int szr, int pre = 0) {
+    return (size_t)XBUFS * M_T * XP + (pre ? 0 : (size_t)4 * NW * WP) + (szr ? 0 : (size_t)G * N_T * 4) +
+           (size_t)M_T * 4;
   }
 };
 
@@ -344,10 +345,17 @@ __device__ __forceinline__ void feature_of(int n_tile, int wave, int sub, int n,
 // chunk-step, KW == 4) and 16-byte aligned scale rows (G % 8 == 0).
 // It frees the largest LDS consumer of the bandwidth-bound shapes, which is what bounds the
 // number of resident workgroups per CU there.
-template <int DT, int MT, int NT, int KS, int KW, int FUSE, int SZR>
+//
+// PRE = 1: `qweight` is in the operand-order layout (blocks of 16 rows x 128 k stored as the 64
+// lanes' 16-byte operand chunks, blocks of a row set consecutive along the reduction; row sets
+// contiguous for the fused gate/up GEMM, even/odd pairs of 32 rows otherwise).  A wave then loads
+// its operand words fully coalesced straight into registers: no weight tile in LDS, one per-lane
+// offset (lane * 16) for every weight load.  Register-scale kernels only.
+template <int DT, int MT, int NT, int KS, int KW, int FUSE, int SZR, int PRE = 0>
 __global__ void __launch_bounds__(256, ((MT * NT <= 4 || (SZR && MT <= 4)) ? 2 : 1))
 w4a16_gemm_kernel(const GemmParams p) {
   static_assert(SZR == 0 || KW == 4, "register-resident scales need 128-k chunk-steps (group 128)");
+  static_assert(PRE == 0 || (SZR == 1 && (FUSE == 1 || NT >= 2)), "operand-order weights: register-scale, paired tiles");
   using G_ = TileGeom<MT, NT, KS>;
   constexpr int M_T = G_::M_T, NW = G_::NW, N_T = G_::N_T, XP = G_::XP, WP = G_::WP;
   constexpr int CPR = G_::CPR, RPP = G_::RPP, XPASS = G_::XPASS;
@@ -373,8 +381,8 @@ w4a16_gemm_kernel(const GemmParams p) {
   extern __shared__ __align__(16) unsigned char smem[];
   unsigned char* xs = smem;                                        // [2][M_T][XP]
   constexpr int XBUFS = G_::XBUFS;
-  unsigned char* ws_all = xs + XBUFS * M_T * XP;                   // [4][NW][WP]
-  uint32_t* sz = reinterpret_cast<uint32_t*>(ws_all + 4 * NW * WP);  // [G][N_T] (absent when SZR)
+  unsigned char* ws_all = xs + XBUFS * M_T * XP;                   // [4][NW][WP] (absent when PRE)
+  uint32_t* sz = reinterpret_cast<uint32_t*>(ws_all + (PRE ? 0 : 4 * NW * WP));  // [G][N_T] (absent when SZR)
   int* slot_s = reinterpret_cast<int*>(sz + (SZR ? 0 : p.G * N_T));  // [M_T]
 
   // A workgroup owns one block of M_T slots and `tiles_per_wg` consecutive feature tiles; it
@@ -425,19 +433,36 @@ w4a16_gemm_kernel(const GemmParams p) {
     const uint32_t arow = (slot >= 0 && slot < p.num_slots) ? (uint32_t)(slot / p.row_div) : 0u;
     xoff[ps] = arow * (uint32_t)(K_in * 2) + (uint32_t)(xr_chunk * 16);
   }
-  const unsigned char* const wbase =
-      reinterpret_cast<const unsigned char*>(p.qweight) + (size_t)e * p.N_out * (size_t)(K_in >> 1) + (size_t)(k0 >> 1);
+  // (operand-order layout: the k0 / 128 leading blocks of a row set are 1 KiB each)
+  const unsigned char* const wbase = reinterpret_cast<const unsigned char*>(p.qweight) +
+                                     (size_t)e * p.N_out * (size_t)(K_in >> 1) +
+                                     (PRE ? (size_t)(k0 >> 7) * 1024 : (size_t)(k0 >> 1));
   uint32_t woff[WPASS];      // rows of the tile the LOAD cursor is in
   const int wl_row = lane / LPR, wl_chunk = lane % LPR;
   auto set_w_rows = [&](int tile) __attribute__((always_inline)) {
+    if constexpr (PRE) {
+      // load q = s * UCH + u fetches chunk-step u of the stage for sub-tile s: block of the
+      // sub-tile's row set, 1 KiB per chunk-step, the lane's own 16 bytes
 #pragma unroll
-    for (int q = 0; q < WPASS; ++q) {
-      const int rw = q * RPI + wl_row;
-      int wrow, ocol;
-      bool ok;
-      feature_of<NT, FUSE>(tile, wave, rw >> 4, rw & 15, p, wrow, ocol, ok);
-      if (!ok) wrow = 0;
-      woff[q] = (uint32_t)wrow * (uint32_t)(K_in >> 1) + (uint32_t)(wl_chunk * 16);
+      for (int q = 0; q < WPASS; ++q) {
+        const int sub = q / UCH;
+        int wrow, ocol;
+        bool ok;
+        feature_of<NT, FUSE>(tile, wave, sub, 0, p, wrow, ocol, ok);
+        if (!ok) wrow = 0;
+        const uint32_t blk = FUSE ? (uint32_t)wrow >> 4 : (((uint32_t)wrow >> 5) << 1) | (uint32_t)(sub & 1);
+        woff[q] = (blk * (uint32_t)(K_in >> 7) + (uint32_t)(q % UCH)) * 1024u + (uint32_t)(lane * 16);
+      }
+    } else {
+#pragma unroll
+      for (int q = 0; q < WPASS; ++q) {
+        const int rw = q * RPI + wl_row;
+        int wrow, ocol;
+        bool ok;
+        feature_of<NT, FUSE>(tile, wave, rw >> 4, rw & 15, p, wrow, ocol, ok);
+        if (!ok) wrow = 0;
+        woff[q] = (uint32_t)wrow * (uint32_t)(K_in >> 1) + (uint32_t)(wl_chunk * 16);
+      }
     }
   };
   set_w_rows(tile0);
@@ -479,7 +504,7 @@ w4a16_gemm_kernel(const GemmParams p) {
 #define MOE_LOAD_W(ST, WV)                                                                      \
   {                                                                                             \
     const int stc_ = (ST) < nst ? (ST) : nst - 1;                                               \
-    const unsigned char* wb_ = wbase + (size_t)stc_ * (KS / 2);                                 \
+    const unsigned char* wb_ = wbase + (size_t)stc_ * (PRE ? UCH * 1024 : KS / 2);              \
     uint32_t wsub_ = 0;                                                                         \
     if (has_tail && stc_ == nst - 1) wsub_ = wback;                                             \
     _Pragma("unroll") for (int q = 0; q < WPASS; ++q) {                                         \
@@ -500,10 +525,12 @@ w4a16_gemm_kernel(const GemmParams p) {
   }
 #define MOE_STORE_STAGE(XV, WV, XBUF)                                                           \
   {                                                                                             \
-    _Pragma("unroll") for (int q = 0; q < WPASS; ++q) {                                         \
-      const u32x4 t_ = WV[q];                                                                   \
-      *reinterpret_cast<u32x4*>(wsw + (q * RPI + wl_row) * WP + wl_chunk * 16) =                \
-          t_;                                                                                   \
+    if constexpr (!PRE) {                                                                       \
+      _Pragma("unroll") for (int q = 0; q < WPASS; ++q) {                                       \
+        const u32x4 t_ = WV[q];                                                                 \
+        *reinterpret_cast<u32x4*>(wsw + (q * RPI + wl_row) * WP + wl_chunk * 16) =              \
+            t_;                                                                                 \
+      }                                                                                         \
     }                                                                                           \
     _Pragma("unroll") for (int ps = 0; ps < XPASS; ++ps)                                        \
         *reinterpret_cast<u32x4*>((XBUF) + (ps * RPP + xr_row) * XP + xw_pos * 16) =            \
@@ -526,7 +553,8 @@ w4a16_gemm_kernel(const GemmParams p) {
         set_w_rows(tile0 + ld_t);                                   \
       } else { /* past the last tile: re-read row 0 of the expert; the lane keeps its own  */ \
                /* chunk offset so that subtracting wback (<= wl_chunk*16) cannot underflow  */ \
-        _Pragma("unroll") for (int q = 0; q < WPASS; ++q) woff[q] = (uint32_t)(wl_chunk * 16); \
+        _Pragma("unroll") for (int q = 0; q < WPASS; ++q)                                   \
+            woff[q] = PRE ? (uint32_t)((q % UCH) * 1024 + lane * 16) : (uint32_t)(wl_chunk * 16); \
       }                                                             \
     }                                                               \
   }
@@ -645,6 +673,7 @@ w4a16_gemm_kernel(const GemmParams p) {
 #pragma unroll
   for (int s = 0; s < NT; ++s) unit[s] = 1.f;
 
+  u32x4 wcur[WPASS];      // PRE: the weight words of the stage being computed (copied out of the ring)
   auto compute_stage = [&](int st, const unsigned char* xbuf, auto rc) __attribute__((always_inline)) {
     constexpr int R = decltype(rc)::value;       // step index inside the unrolled trip
     const int left = (K_ext - st * KS) / CK;     // <= 0 for a stage past the end
@@ -666,7 +695,12 @@ w4a16_gemm_kernel(const GemmParams p) {
         } else {
           ctx[s] = DeqCtx<DT, ZM>(sz[gi * N_T + wave * NW + s * 16 + ln]);
         }
-        wv[s] = lds_read_words<KW>(wsw + (s * 16 + ln) * WP + 16 * KW * u + 4 * KW * lj);
+        if constexpr (PRE) {
+          const u32x4 t = wcur[s * UCH + u];      // the lane's four operand words, straight from the ring
+          wv[s].w[0] = t.x; wv[s].w[1] = t.y; wv[s].w[2] = t.z; wv[s].w[3] = t.w;
+        } else {
+          wv[s] = lds_read_words<KW>(wsw + (s * 16 + ln) * WP + 16 * KW * u + 4 * KW * lj);
+        }
       }
       u32x4 zop[NT];
       float scl[NT];
@@ -858,6 +892,11 @@ w4a16_gemm_kernel(const GemmParams p) {
          constexpr int r = Rs;
          // activations first: the wait for them (loads complete in issue order) then leaves the
          // younger weight loads of PDW - PDX + 1 stages in flight
+         if constexpr (PRE) {
+           // the ring slot about to be refilled holds the stage computed in this step
+#pragma unroll
+           for (int q = 0; q < WPASS; ++q) wcur[q] = wr[r % PDW][q];
+         }
          MOE_LOAD_X(lx_st, xr[r % PDX])
          MOE_ADVANCE_X_CURSOR()
          MOE_LOAD_W(ld_st, wr[r % PDW])
@@ -892,7 +931,7 @@ w4a16_gemm_kernel(const GemmParams p) {
 }
 
 // Host-side launcher, one per instantiation.  Returns hipError_t as int.
-template <int DT, int MT, int NT, int KS, int KW, int FUSE, int SZR>
+template <int DT, int MT, int NT, int KS, int KW, int FUSE, int SZR, int PRE = 0>
 int launch_w4a16_gemm(const GemmParams& p, int grid, hipStream_t stream);
 
 }  // namespace moe

@@ -204,3 +204,86 @@ def test_roof_probes_run():
     M.moe_probe_stream_read(src, sink)
     M.moe_probe_mfma(sink, 100)
     torch.cuda.synchronize()
+
+
+# ------------------------------------------------------------------ operand-order (prepacked) weights
+@pytest.mark.parametrize("E,N_out,K,paired", [(1, 16, 128, False), (3, 96, 384, False), (2, 64, 1024, True),
+                                              (5, 352, 256, True), (2, 2048, 2048, False)])
+def test_repack_matches_oracle_permutation(E, N_out, K, paired):
+    say(f"repack E={E} N_out={N_out} K={K} paired={paired}")
+    rng = np.random.default_rng(60 + N_out)
+    q = rng.integers(0, 2 ** 32, size=(E, N_out, K // 8), dtype=np.uint32).view(np.int32)
+    qd = torch.from_numpy(q).cuda()
+    out = torch.full_like(qd, -1)
+    M.moe_repack_qweight(qd, paired, out)
+    torch.cuda.synchronize()
+    want = O.repack_qweight(q, paired).reshape(E, N_out, K // 8)
+    np.testing.assert_array_equal(out.cpu().numpy(), want)
+
+
+def _prepacked(d):
+    p1, p2 = torch.empty_like(d.qw1), torch.empty_like(d.qw2)
+    M.moe_repack_qweight(d.qw1, False, p1)
+    M.moe_repack_qweight(d.qw2, True, p2)
+    return p1, p2
+
+
+@pytest.mark.parametrize("tile", [(1, 2), (2, 2), (4, 2), (4, 4)])
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+def test_prepacked_layer_equals_layer_bitwise(tile, dtype):
+    """Same operand words in the same order: the layer on repacked weights must reproduce the
+    layer on the original tensors bit for bit, and both sit within the bound of the oracle."""
+    cfg = MoEConfig("pre", T=40, K=1024, N=1024, E=5, topk=2, group=128, dtype=dtype, seed=61)
+    say(f"prepacked layer tile={tile} {cfg}")
+    inp = make_inputs(cfg)
+    d = U.DevInputs(inp)
+    p1, p2 = _prepacked(d)
+    mdt = M.MOE_F16 if dtype == "f16" else M.MOE_BF16
+    ws = torch.empty(M.moe_w4a16_layer_workspace_bytes(cfg.T, cfg.K, cfg.N, cfg.E, cfg.topk, mdt),
+                     dtype=torch.uint8, device="cuda")
+    out_a = torch.full((cfg.T, cfg.K), float("nan"), dtype=U.TORCH_DT[dtype], device="cuda")
+    out_b = torch.full_like(out_a, float("nan"))
+    M.moe_set_tile_override(*tile)
+    try:
+        M.moe_w4a16_layer(d.X, d.ids, d.w, d.qw1, d.s1, d.z1, d.qw2, d.s2, d.z2, out_a, cfg.group, ws)
+        M.moe_w4a16_layer_prepacked(d.X, d.ids, d.w, p1, d.s1, d.z1, p2, d.s2, d.z2, out_b, cfg.group, ws)
+        torch.cuda.synchronize()
+    finally:
+        M.moe_set_tile_override(0, 0)
+    assert torch.equal(out_a.view(torch.int16), out_b.view(torch.int16))
+    want = O.layer(O.decode_bits(inp.x_bits, dtype), inp.topk_ids, inp.topk_weights, inp.qw1,
+                   O.decode_bits(inp.s1_bits, dtype), inp.z1, inp.qw2, O.decode_bits(inp.s2_bits, dtype), inp.z2,
+                   cfg.group, dtype)
+    U.assert_close(U.dev_to_f64(out_b), want, "prepacked layer")
+
+
+@pytest.mark.parametrize("T,K,N,E,topk,splits", [(20, 1024, 3072, 3, 2, 2), (130, 2048, 1024, 7, 3, 0), (9, 1024, 2048, 40, 4, 3)])
+def test_prepacked_layer_shapes_and_splits(T, K, N, E, topk, splits):
+    cfg = MoEConfig("pre_s", T=T, K=K, N=N, E=E, topk=topk, group=128, dtype="f16", seed=62)
+    say(f"prepacked layer shapes {cfg} splits={splits}")
+    inp = make_inputs(cfg)
+    d = U.DevInputs(inp)
+    p1, p2 = _prepacked(d)
+    ws = torch.empty(M.moe_w4a16_layer_workspace_bytes(T, K, N, E, topk, M.MOE_F16), dtype=torch.uint8, device="cuda")
+    out = torch.full((T, K), float("nan"), dtype=torch.float16, device="cuda")
+    M.moe_set_reduction_splits(splits)
+    try:
+        M.moe_w4a16_layer_prepacked(d.X, d.ids, d.w, p1, d.s1, d.z1, p2, d.s2, d.z2, out, cfg.group, ws)
+        torch.cuda.synchronize()
+    finally:
+        M.moe_set_reduction_splits(0)
+    want = O.layer(O.decode_bits(inp.x_bits, "f16"), inp.topk_ids, inp.topk_weights, inp.qw1,
+                   O.decode_bits(inp.s1_bits, "f16"), inp.z1, inp.qw2, O.decode_bits(inp.s2_bits, "f16"), inp.z2,
+                   cfg.group, "f16")
+    U.assert_close(U.dev_to_f64(out), want, "prepacked layer shapes")
+
+
+def test_prepacked_layer_rejects_other_group_sizes():
+    cfg = MoEConfig("pre_bad", T=8, K=1024, N=1024, E=2, topk=1, group=64, dtype="f16", seed=63)
+    say(f"prepacked layer unsupported {cfg}")
+    d = U.DevInputs(make_inputs(cfg))
+    ws = torch.empty(M.moe_w4a16_layer_workspace_bytes(8, 1024, 1024, 2, 1, M.MOE_F16), dtype=torch.uint8, device="cuda")
+    out = torch.zeros((8, 1024), dtype=torch.float16, device="cuda")
+    with pytest.raises(M.MoEError) as e:
+        M.moe_w4a16_layer_prepacked(d.X, d.ids, d.w, d.qw1, d.s1, d.z1, d.qw2, d.s2, d.z2, out, 64, ws)
+    assert e.value.status == 2
