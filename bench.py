@@ -144,7 +144,8 @@ def main():
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     if os.path.exists(tpath):
         try:
-            traffic = json.load(open(tpath)).get(cfg.name, {}).get("gemm1_bytes_per_launch")
+            key = cfg.name + ("_prepacked" if args.prepacked else "")
+            traffic = json.load(open(tpath)).get(key, {}).get("gemm1_bytes_per_launch")
         except Exception:
             traffic = None
     if hbm_bound:
