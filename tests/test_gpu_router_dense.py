@@ -287,3 +287,36 @@ def test_prepacked_layer_rejects_other_group_sizes():
     with pytest.raises(M.MoEError) as e:
         M.moe_w4a16_layer_prepacked(d.X, d.ids, d.w, d.qw1, d.s1, d.z1, d.qw2, d.s2, d.z2, out, 64, ws)
     assert e.value.status == 2
+
+
+def test_layer_is_graph_capturable_and_replays_identically():
+    """The layer allocates nothing, never synchronises and launches only on the given stream, so
+    it can be recorded into a HIP graph; every replay (with eager work and synchronisations in
+    between) must reproduce the eager result bit for bit."""
+    cfg = MoEConfig("graph", T=24, K=1024, N=1024, E=6, topk=2, group=128, dtype="f16", seed=71)
+    say(f"graph capture {cfg}")
+    inp = make_inputs(cfg)
+    d = U.DevInputs(inp)
+    ws = torch.empty(M.moe_w4a16_layer_workspace_bytes(cfg.T, cfg.K, cfg.N, cfg.E, cfg.topk, M.MOE_F16),
+                     dtype=torch.uint8, device="cuda")
+    eager = torch.full((cfg.T, cfg.K), float("nan"), dtype=torch.float16, device="cuda")
+    M.moe_w4a16_layer(d.X, d.ids, d.w, d.qw1, d.s1, d.z1, d.qw2, d.s2, d.z2, eager, cfg.group, ws)
+    torch.cuda.synchronize()
+    out = torch.zeros_like(eager)
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        M.moe_w4a16_layer(d.X, d.ids, d.w, d.qw1, d.s1, d.z1, d.qw2, d.s2, d.z2, out, cfg.group, ws)   # warm-up on the side stream
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            M.moe_w4a16_layer(d.X, d.ids, d.w, d.qw1, d.s1, d.z1, d.qw2, d.s2, d.z2, out, cfg.group, ws, stream=side)
+    for rep in range(3):
+        out.fill_(float("nan"))
+        ws.random_(0, 255)                      # scratch contents must not matter
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out.view(torch.int16), eager.view(torch.int16)), f"replay {rep}"
+        junk = torch.randn(1 << 16, device="cuda").sum().item()      # eager work between replays
+        assert junk == junk
