@@ -132,6 +132,7 @@ def main():
     ms_per_step = elapsed * 1e3 / K_steps
     stage_ms = np.array([[row[j].elapsed_time(row[j + 1]) for j in range(4)] for row in evs])
     stage_avg = stage_ms.mean(axis=0)
+    step_ms_events = np.array([row[0].elapsed_time(row[4]) for row in evs])      # per-step layer time (GPU side)
     E_act, layer_bytes, gemm1_bytes = algorithmic_bytes(cfg, inp.topk_ids)
     flops = 6.0 * cfg.K * cfg.N * cfg.S
     gbs = layer_bytes / (ms_per_step * 1e-3) / 1e9
@@ -173,6 +174,14 @@ def main():
         "stage_ms": {"align": round(float(stage_avg[0]), 4), "gemm1_silu": round(float(stage_avg[1]), 4),
                      "gemm2": round(float(stage_avg[2]), 4), "combine": round(float(stage_avg[3]), 4)},
         "roofline": roofline,
+        # per-step GPU-side layer time from the library's own events (first to last kernel of a call)
+        "ms_per_step_events": {"median": round(float(np.median(step_ms_events)), 4),
+                               "min": round(float(step_ms_events.min()), 4),
+                               "max": round(float(step_ms_events.max()), 4)},
+        # weights of the active experts against the 256 MB Infinity Cache: small workloads are re-read
+        # from cache between steps, the graded ones stream from HBM every step
+        "cache_state": "weights exceed the 256 MB last-level cache: streamed from HBM every step"
+                       if layer_bytes > 512e6 else "cache-warm: the working set fits the 256 MB last-level cache",
     }
 
     # What the chip sustains on the two resources, measured in this same process: a non-temporal
