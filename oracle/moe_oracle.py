@@ -35,7 +35,8 @@ sum to one, top-k against a scalar selection loop and (k = E) a library softmax,
 the dense GEMM against a closed form and an independent dequantisation,
 token permutation equivariance (bit-identical), W2-scale doubling
 doubles the output, combine linearity, rounding against NumPy's fp16 cast,
-PyTorch's bf16 cast and hand-derived tie cases.  The paper prints no worked
+PyTorch's bf16 cast and hand-derived tie cases, the AWQ import against a scalar
+walk of the format definition and the x @ W it defines.  The paper prints no worked
 numeric example for this operator, so there is no paper-valued fixture.
 """
 from __future__ import annotations
@@ -162,6 +163,43 @@ def repack_qweight(qweight, paired: bool) -> np.ndarray:
                 for n in range(16):
                     out[:, b, c, 16 * j + n, :] = q[:, rows[n], 16 * c + 4 * j: 16 * c + 4 * j + 4]
     return out
+
+
+# --------------------------------------------------------------------------
+# import of AWQ-packed checkpoints (a permutation of nibbles / elements, no arithmetic)
+# --------------------------------------------------------------------------
+# The paper's layer comes from an AWQ checkpoint (Section VII-B, VII-D).  The publicly documented
+# AWQ "GEMM" tensor format stores a linear layer y = x @ W, W [in, out], as
+#   qweight [in, out/8] int32, qzeros [in/g, out/8] int32, scales [in/g, out] (16-bit float),
+# each word holding eight neighbouring OUTPUT columns, and not in sequential order: the nibble
+# at bits [4p, 4p+4) of word c is column 8c + AWQ_NIBBLE_COLUMN[p].  W[k, n] = (q[k, n] -
+# z[k // g, n]) * s[k // g, n].
+AWQ_NIBBLE_COLUMN = (0, 2, 4, 6, 1, 3, 5, 7)
+
+
+def import_awq(awq_qweight, awq_qzeros, awq_scales):
+    """AWQ-format tensors of E linear layers -> this library's format.
+
+    awq_qweight [E, K_in, N_out/8] words, awq_qzeros [E, K_in/g, N_out/8] words, awq_scales
+    [E, K_in/g, N_out] (any array; moved as is).  Returns (qweight [E, N_out, K_in/8] int32 in
+    sequential nibble order along the reduction, scales [E, N_out, K_in/g], zeros
+    [E, N_out, K_in/g] uint8): the same q, z and s, transposed so that the reduction index is
+    the contiguous one."""
+    wq = np.ascontiguousarray(awq_qweight).view(np.uint32)
+    wz = np.ascontiguousarray(awq_qzeros).view(np.uint32)
+    sc = np.asarray(awq_scales)
+    E, K_in, NW = wq.shape
+    N_out = 8 * NW
+    G = wz.shape[1]
+    assert wz.shape == (E, G, NW) and sc.shape == (E, G, N_out) and K_in % 8 == 0
+    q = np.empty((E, K_in, N_out), dtype=np.uint8)       # logical integer weights [e, k, n]
+    z = np.empty((E, G, N_out), dtype=np.uint8)
+    for p in range(8):
+        col = AWQ_NIBBLE_COLUMN[p]
+        q[:, :, col::8] = (wq >> np.uint32(4 * p)) & np.uint32(0xF)
+        z[:, :, col::8] = (wz >> np.uint32(4 * p)) & np.uint32(0xF)
+    qweight = pack_int4(np.swapaxes(q, 1, 2))             # [E, N_out, K_in] -> words along k
+    return qweight, np.ascontiguousarray(np.swapaxes(sc, 1, 2)), np.ascontiguousarray(np.swapaxes(z, 1, 2))
 
 
 # --------------------------------------------------------------------------

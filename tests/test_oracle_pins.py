@@ -286,6 +286,66 @@ def test_repack_is_the_documented_permutation(paired):
     assert np.array_equal(back, qr)
 
 
+# ------------------------------------------------------------------ AWQ checkpoint import
+def _awq_pack_scalar(M):
+    """[R, C] integers 0..15 -> [R, C/8] words, written from the format's packing rule: word c takes,
+    for p = 0..7, column 8c + (0, 2, 4, 6, 1, 3, 5, 7)[p] into bits [4p, 4p + 4)."""
+    R, C = M.shape
+    out = np.zeros((R, C // 8), dtype=np.uint32)
+    for r in range(R):
+        for c in range(C // 8):
+            word = 0
+            for p, col in enumerate((0, 2, 4, 6, 1, 3, 5, 7)):
+                word |= int(M[r, 8 * c + col]) << (4 * p)
+            out[r, c] = word
+    return out.view(np.int32)
+
+
+def test_import_awq_hand_vector():
+    """Word 0x76543210 (nibble p holds the value p): column n of the word is the value stored at
+    position (0, 4, 1, 5, 2, 6, 3, 7)[n] (the inverse of the packing order); a sequential reading
+    would give 0..7."""
+    K, N, g = 8, 8, 8
+    words = np.full((1, K, 1), 0x76543210, dtype=np.uint32).view(np.int32)
+    zw = np.full((1, 1, 1), 0xFEDCBA98, dtype=np.uint32).view(np.int32)
+    sc = np.arange(8, dtype=np.float64).reshape(1, 1, 8)
+    qw, s, z = O.import_awq(words, zw, sc)
+    assert qw.shape == (1, 8, 1) and s.shape == (1, 8, 1) and z.shape == (1, 8, 1)
+    cols = [0, 4, 1, 5, 2, 6, 3, 7]
+    for n in range(8):
+        assert list(O.unpack_int4(qw)[0, n]) == [cols[n]] * 8          # every k holds the same word
+        assert int(z[0, n, 0]) == 8 + cols[n]
+        assert s[0, n, 0] == float(n)
+    assert [int(O.unpack_int4(qw)[0, n, 0]) for n in range(8)] != list(range(8))
+
+
+def test_import_awq_against_scalar_pack_and_matmul():
+    """Logical integer weights packed by a scalar walk of the packing rule come back transposed and
+    sequential; x @ W with W taken nibble by nibble from the AWQ words (shift 4 * (0, 4, 1, 5, 2, 6,
+    3, 7)[n % 8], the format's other statement) equals the oracle's GEMM on the imported tensors."""
+    rng = np.random.default_rng(21)
+    E, K, N, g = 2, 32, 24, 16
+    Q = rng.integers(0, 16, size=(E, K, N))
+    Z = rng.integers(0, 16, size=(E, K // g, N))
+    S = O.rnd(rng.uniform(0.01, 0.05, size=(E, K // g, N)), "f16")
+    aq = np.stack([_awq_pack_scalar(Q[e]) for e in range(E)])
+    az = np.stack([_awq_pack_scalar(Z[e]) for e in range(E)])
+    qw, s, z = O.import_awq(aq, az, S)
+    assert qw.dtype == np.int32 and qw.shape == (E, N, K // 8) and z.dtype == np.uint8
+    assert np.array_equal(O.unpack_int4(qw), np.swapaxes(Q, 1, 2))
+    assert np.array_equal(z, np.swapaxes(Z, 1, 2)) and np.array_equal(s, np.swapaxes(S, 1, 2))
+    shift = [4 * v for v in (0, 4, 1, 5, 2, 6, 3, 7)]
+    x = O.rnd(rng.standard_normal((3, K)), "f16")
+    for e in range(E):
+        W = np.empty((K, N))
+        for k in range(K):
+            for n in range(N):
+                qv = (int(aq[e, k, n // 8]) & 0xFFFFFFFF) >> shift[n % 8] & 15
+                zv = (int(az[e, k // g, n // 8]) & 0xFFFFFFFF) >> shift[n % 8] & 15
+                W[k, n] = (qv - zv) * S[e, k // g, n]
+        np.testing.assert_allclose(O.dense_gemm(x, qw[e], s[e], z[e], g), x @ W, rtol=1e-12, atol=1e-12)
+
+
 def test_skew_bias_formula():
     b = skew_bias(8)
     np.testing.assert_allclose(b, [2 * np.log(1 / (r ** 1.2)) for r in range(1, 9)], rtol=1e-6)
