@@ -181,6 +181,26 @@ int moe_w4a16_layer_prepacked(const void* X, const int32_t* topk_ids, const floa
                               moe_dtype dt, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Import of AWQ-packed checkpoints (the paper's layer comes from an AWQ checkpoint, Section
+ * VII-B / VII-D; the tensor format is the publicly documented AWQ "GEMM" one).  For E linear
+ * layers y = x W, W [K_in, N_out]:
+ *   awq_qweight [E, K_in, N_out/8] int32, awq_qzeros [E, K_in/g, N_out/8] int32: each word holds
+ *       eight neighbouring OUTPUT columns, bits [4p, 4p+4) = column 8c + (0,2,4,6,1,3,5,7)[p];
+ *   awq_scales  [E, K_in/g, N_out] 16-bit floats (either type; moved unchanged);
+ *   W[k, n] = (q[k, n] - z[k/g, n]) * s[k/g, n].
+ * Writes the same q, z, s in this library's layout: qweight [E, N_out, K_in/8] (sequential
+ * nibbles along the reduction), scales [E, N_out, K_in/g], zeros [E, N_out, K_in/g] bytes.
+ * For the layer, W1 = the gate projection's columns followed by the up projection's (concatenate
+ * the two checkpoints' tensors along N_out before or after the import), W2 = the down projection.
+ * All pointers device memory, caller-owned; outputs must not alias inputs; words 4-byte,
+ * scales 2-byte aligned; K_in % 8 == 0, N_out % 8 == 0, K_in % group_size == 0, E <= 65535.
+ * Two kernels on `stream`, no allocation.  Returns a moe_status.
+ */
+int moe_import_awq(const int32_t* awq_qweight, const int32_t* awq_qzeros, const void* awq_scales,
+                   int E, int K_in, int N_out, int group_size,
+                   int32_t* qweight, void* scales, uint8_t* zeros, void* stream);
+
+/*
  * Router + layer on one stream: moe_route_topk into tables held in the workspace, then
  * moe_w4a16_layer.  Arguments as for the two; `workspace` of at least
  * moe_w4a16_routed_layer_workspace_bytes(...) bytes, 256-byte aligned.

@@ -19,7 +19,7 @@ EXPORTS = [
     "moe_set_stage_events", "moe_set_tile_override", "moe_set_scale_path", "moe_set_tiles_per_workgroup", "moe_set_reduction_splits", "moe_layer_block_m",
     "moe_w4a16_dense_gemm", "moe_route_topk", "moe_probe_stream_read", "moe_probe_mfma",
     "moe_w4a16_routed_layer_workspace_bytes", "moe_w4a16_routed_layer",
-    "moe_repack_qweight", "moe_w4a16_layer_prepacked",
+    "moe_repack_qweight", "moe_w4a16_layer_prepacked", "moe_import_awq",
 ]
 
 
@@ -66,6 +66,8 @@ def load_library() -> ctypes.CDLL:
     lib.moe_w4a16_routed_layer.argtypes = [vp] * 10 + [i32] * 7 + [vp, sz, vp]
     lib.moe_repack_qweight.restype = i32
     lib.moe_repack_qweight.argtypes = [vp, i32, i32, i32, i32, vp, vp]
+    lib.moe_import_awq.restype = i32
+    lib.moe_import_awq.argtypes = [vp, vp, vp, i32, i32, i32, i32, vp, vp, vp, vp]
     lib.moe_w4a16_layer_prepacked.restype = i32
     lib.moe_w4a16_layer_prepacked.argtypes = [vp] * 10 + [i32] * 7 + [vp, sz, vp]
     lib.moe_silu_mul.restype = i32
@@ -219,6 +221,15 @@ def moe_repack_qweight(qweight, paired: bool, out, stream=None) -> None:
     E, N_out, kw = qweight.shape
     _check(load_library().moe_repack_qweight(_ptr(qweight), E, N_out, kw * 8, 1 if paired else 0, _ptr(out),
                                              _stream(stream)))
+
+
+def moe_import_awq(awq_qweight, awq_qzeros, awq_scales, qweight, scales, zeros, stream=None) -> None:
+    """AWQ tensors [E, K_in, N_out/8], [E, K_in/g, N_out/8], [E, K_in/g, N_out] -> qweight [E, N_out, K_in/8],
+    scales [E, N_out, K_in/g], zeros [E, N_out, K_in/g] uint8 (all preallocated)."""
+    E, K_in, nw = awq_qweight.shape
+    G = awq_qzeros.shape[1]
+    _check(load_library().moe_import_awq(_ptr(awq_qweight), _ptr(awq_qzeros), _ptr(awq_scales), E, K_in, nw * 8,
+                                         K_in // G, _ptr(qweight), _ptr(scales), _ptr(zeros), _stream(stream)))
 
 
 def moe_w4a16_layer_prepacked(X, topk_ids, topk_weights, qw1p, s1, z1, qw2p, s2, z2, out, group_size, workspace,

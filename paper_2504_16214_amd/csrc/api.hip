@@ -14,6 +14,8 @@ int launch_align(const int32_t*, int, int, int, int, int32_t*, int32_t*, int32_t
                  hipStream_t);
 int launch_silu_mul(const void*, void*, long long, int, int, hipStream_t);
 int launch_repack(const int32_t*, int, int, int, int, int32_t*, hipStream_t);
+int launch_awq_import(const int32_t*, const int32_t*, const void*, int, int, int, int, int32_t*, void*, uint8_t*,
+                      hipStream_t);
 int launch_route_topk(const float*, const float*, int, int, int, int32_t*, float*, hipStream_t);
 int launch_stream_read(const void*, size_t, uint32_t*, int, hipStream_t);
 int launch_mfma_loop(float*, int, int, hipStream_t);
@@ -493,6 +495,26 @@ int moe_repack_qweight(const int32_t* qweight, int E, int N_out, int K_in, int p
     return fail(MOE_INVALID_ARGUMENT, "qweight and out must be 16-byte aligned");
   const int err = launch_repack(qweight, E, N_out, K_in, paired ? 1 : 0, out, (hipStream_t)stream);
   if (err != 0) return hip_fail(err, "repack launch");
+  return MOE_OK;
+}
+
+int moe_import_awq(const int32_t* awq_qweight, const int32_t* awq_qzeros, const void* awq_scales, int E, int K_in,
+                   int N_out, int group_size, int32_t* qweight, void* scales, uint8_t* zeros, void* stream) {
+  if (E < 1 || K_in < 1 || N_out < 1 || group_size < 1)
+    return fail(MOE_INVALID_ARGUMENT, "need positive E, K_in, N_out, group_size");
+  if (E > 65535) return fail(MOE_UNSUPPORTED_SHAPE, "import handles at most 65535 experts per call");
+  if (K_in % 8 != 0 || N_out % 8 != 0 || K_in % group_size != 0)
+    return fail(MOE_UNSUPPORTED_SHAPE, "import needs K_in %% 8 == 0, N_out %% 8 == 0, K_in %% group_size == 0");
+  if (!awq_qweight || !awq_qzeros || !awq_scales || !qweight || !scales || !zeros)
+    return fail(MOE_INVALID_ARGUMENT, "null pointer argument");
+  if ((const void*)awq_qweight == (const void*)qweight || awq_scales == (const void*)scales)
+    return fail(MOE_INVALID_ARGUMENT, "the import does not work in place");
+  if (((uintptr_t)awq_qweight | (uintptr_t)awq_qzeros | (uintptr_t)qweight) % 4 != 0 ||
+      ((uintptr_t)awq_scales | (uintptr_t)scales) % 2 != 0)
+    return fail(MOE_INVALID_ARGUMENT, "word tensors must be 4-byte, scale tensors 2-byte aligned");
+  const int err = launch_awq_import(awq_qweight, awq_qzeros, awq_scales, E, K_in, N_out, group_size, qweight, scales,
+                                    zeros, (hipStream_t)stream);
+  if (err != 0) return hip_fail(err, "AWQ import launch");
   return MOE_OK;
 }
 

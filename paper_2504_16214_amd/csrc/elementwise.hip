@@ -138,6 +138,77 @@ int launch_repack(const int32_t* q, int E, int N_out, int K_in, int paired, int3
   return (int)hipGetLastError();
 }
 
+// Import of AWQ-packed tensors: qweight [E, K_in, N_out/8] words hold eight neighbouring output
+// columns each, column 8c + n' at bits [4 r(n'), 4 r(n') + 4) with r = (0, 4, 1, 5, 2, 6, 3, 7); the
+// result is this library's [E, N_out, K_in/8] words, sequential along the reduction.  A wave
+// covers 64 output columns (so the eight lanes of a column group read the same word and a row's
+// reads are contiguous); a lane gathers 32 reduction rows into four output words (16 bytes).
+__device__ __forceinline__ uint32_t awq_nibble(uint32_t word, int col_in_word) {
+  const int pos = ((col_in_word & 1) << 2) | (col_in_word >> 1);      // 0,4,1,5,2,6,3,7
+  return (word >> (4 * pos)) & 0xFu;
+}
+
+__global__ void __launch_bounds__(256)
+awq_import_qweight_kernel(const uint32_t* __restrict__ in, uint32_t* __restrict__ out, int K_in, int N_out,
+                          int vec_ok) {
+  const int NW = N_out >> 3, KW = K_in >> 3;
+  const int n = blockIdx.x * 64 + (threadIdx.x & 63);
+  const int kj0 = blockIdx.y * 16 + (threadIdx.x >> 6) * 4;
+  const long long e = blockIdx.z;
+  if (n >= N_out || kj0 >= KW) return;
+  const uint32_t* src = in + e * (long long)K_in * NW + (n >> 3);
+  uint32_t w[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    if (kj0 + j < KW) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const uint32_t word = src[(long long)(8 * (kj0 + j) + i) * NW];
+        w[j] |= awq_nibble(word, n & 7) << (4 * i);
+      }
+    }
+  }
+  uint32_t* dst = out + (e * N_out + n) * (long long)KW + kj0;
+  if (vec_ok && kj0 + 3 < KW) {
+    rp_u32x4 v = {w[0], w[1], w[2], w[3]};
+    *reinterpret_cast<rp_u32x4*>(dst) = v;
+  } else {
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      if (kj0 + j < KW) dst[j] = w[j];
+  }
+}
+
+// scales [E, G, N_out] 16-bit -> [E, N_out, G]; qzeros [E, G, N_out/8] words -> zeros [E, N_out, G] bytes
+__global__ void __launch_bounds__(256)
+awq_import_scale_zero_kernel(const uint32_t* __restrict__ qzeros, const uint16_t* __restrict__ scales_in,
+                             uint16_t* __restrict__ scales_out, uint8_t* __restrict__ zeros_out, long long total,
+                             int G, int N_out) {
+  for (long long o = (long long)blockIdx.x * 256 + threadIdx.x; o < total; o += (long long)gridDim.x * 256) {
+    const int n = (int)(o % N_out);
+    long long t = o / N_out;
+    const int gi = (int)(t % G);
+    const long long e = t / G;
+    const long long dst = (e * N_out + n) * (long long)G + gi;
+    scales_out[dst] = scales_in[o];
+    zeros_out[dst] = (uint8_t)awq_nibble(qzeros[(e * G + gi) * (long long)(N_out >> 3) + (n >> 3)], n & 7);
+  }
+}
+
+int launch_awq_import(const int32_t* aq, const int32_t* az, const void* as, int E, int K_in, int N_out, int group,
+                      int32_t* q, void* s, uint8_t* z, hipStream_t stream) {
+  const int KW = K_in / 8, G = K_in / group;
+  const int vec_ok = (KW % 4 == 0 && ((uintptr_t)q % 16) == 0) ? 1 : 0;
+  hipLaunchKernelGGL(awq_import_qweight_kernel, dim3((N_out + 63) / 64, (KW + 15) / 16, E), dim3(256), 0, stream,
+                     (const uint32_t*)aq, (uint32_t*)q, K_in, N_out, vec_ok);
+  int err = (int)hipGetLastError();
+  if (err != 0) return err;
+  const long long total = (long long)E * G * N_out;
+  hipLaunchKernelGGL(awq_import_scale_zero_kernel, dim3(grid_for(total)), dim3(256), 0, stream,
+                     (const uint32_t*)az, (const uint16_t*)as, (uint16_t*)s, z, total, G, N_out);
+  return (int)hipGetLastError();
+}
+
 int launch_silu_mul(const void* H, void* act, long long S, int N, int dt, hipStream_t stream) {
   const long long items = S * (((N & 7) == 0) ? (N >> 3) : N);
   if (items == 0) return 0;
