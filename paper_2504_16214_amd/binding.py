@@ -20,6 +20,7 @@ EXPORTS = [
     "moe_w4a16_dense_gemm", "moe_route_topk", "moe_probe_stream_read", "moe_probe_mfma",
     "moe_w4a16_routed_layer_workspace_bytes", "moe_w4a16_routed_layer",
     "moe_repack_qweight", "moe_w4a16_layer_prepacked", "moe_import_awq",
+    "fp8_blockwise_gemm_workspace_bytes", "fp8_blockwise_gemm", "fp8_set_plan_override", "fp8_probe_mfma",
 ]
 
 
@@ -66,6 +67,14 @@ def load_library() -> ctypes.CDLL:
     lib.moe_w4a16_routed_layer.argtypes = [vp] * 10 + [i32] * 7 + [vp, sz, vp]
     lib.moe_repack_qweight.restype = i32
     lib.moe_repack_qweight.argtypes = [vp, i32, i32, i32, i32, vp, vp]
+    lib.fp8_blockwise_gemm_workspace_bytes.restype = sz
+    lib.fp8_blockwise_gemm_workspace_bytes.argtypes = [i32, i32, i32]
+    lib.fp8_blockwise_gemm.restype = i32
+    lib.fp8_blockwise_gemm.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, vp, sz, vp]
+    lib.fp8_set_plan_override.restype = i32
+    lib.fp8_set_plan_override.argtypes = [i32, i32, i32]
+    lib.fp8_probe_mfma.restype = i32
+    lib.fp8_probe_mfma.argtypes = [vp, i32, vp]
     lib.moe_import_awq.restype = i32
     lib.moe_import_awq.argtypes = [vp, vp, vp, i32, i32, i32, i32, vp, vp, vp, vp]
     lib.moe_w4a16_layer_prepacked.restype = i32
@@ -241,6 +250,32 @@ def moe_w4a16_layer_prepacked(X, topk_ids, topk_weights, qw1p, s1, z1, qw2p, s2,
         _ptr(X), _ptr(topk_ids), _ptr(topk_weights), _ptr(qw1p), _ptr(s1), _ptr(z1), _ptr(qw2p), _ptr(s2),
         _ptr(z2), _ptr(out), T, K, N2 // 2, E, topk, group_size, _dt(X), _ptr(workspace),
         workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+def fp8_blockwise_gemm_workspace_bytes(M: int, N: int, K: int) -> int:
+    return int(load_library().fp8_blockwise_gemm_workspace_bytes(M, N, K))
+
+
+def fp8_blockwise_gemm(A, a_scale, B, b_scale, C, workspace=None, stream=None) -> None:
+    """A [M, K] uint8 e4m3 codes, a_scale [M, K/128] float32, B [N, K] uint8, b_scale [ceil(N/128), K/128]
+    float32, C [M, N] float16 / bfloat16 (preallocated); workspace: uint8 tensor of at least
+    fp8_blockwise_gemm_workspace_bytes(M, N, K) bytes (None when that is 0)."""
+    import torch
+    M, K = A.shape
+    N = B.shape[0]
+    out_dtype = 1 if C.dtype == torch.bfloat16 else 0
+    wb = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(load_library().fp8_blockwise_gemm(_ptr(A), _ptr(a_scale), _ptr(B), _ptr(b_scale), _ptr(C), M, N, K,
+                                             out_dtype, None if workspace is None else _ptr(workspace), wb,
+                                             _stream(stream)))
+
+
+def fp8_set_plan_override(mt: int, nt: int, k_splits: int) -> None:
+    _check(load_library().fp8_set_plan_override(mt, nt, k_splits))
+
+
+def fp8_probe_mfma(sink, iters: int, stream=None) -> None:
+    _check(load_library().fp8_probe_mfma(_ptr(sink), iters, _stream(stream)))
 
 
 def moe_set_tile_override(mt: int, nt: int) -> None:

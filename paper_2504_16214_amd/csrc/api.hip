@@ -5,7 +5,9 @@
 #include <stdint.h>
 #include <stdio.h>
 
+#include "../../include/fp8_blockwise_gemm.h"
 #include "../../include/moe_w4a16.h"
+#include "fp8_gemm.hpp"
 #include "gemm_kernel.hpp"
 
 namespace moe {
@@ -282,6 +284,41 @@ static Workspace carve(long long T, int K, int N, int E, int topk) {
 }  // namespace moe
 
 using namespace moe;
+
+// ---- blockwise-scaled FP8 GEMM: tile and split choice --------------------------------------
+static thread_local int g_fp8_mt = 0, g_fp8_nt = 0, g_fp8_splits = 0;
+
+struct Fp8Plan { int mt, nt, splits, kb_per_split; };
+
+// false: the (forced) plan does not fit the shape
+static bool fp8_plan(int M, int N, int K, Fp8Plan& pl) {
+  const int KB = K / 128;
+  int mt = M <= 16 ? 1 : M <= 32 ? 2 : M <= 64 ? 4 : 8;
+  if (g_fp8_mt) mt = g_fp8_mt;
+  if (mt != 1 && mt != 2 && mt != 4 && mt != 8) return false;
+  const long long m_blocks = (M + 16 * mt - 1) / (16 * mt);
+  int nt = 4;
+  while (nt > 1 && N % (64 * nt) != 0) nt >>= 1;
+  // small problems: narrower feature tiles first (more workgroups streaming weights) ...
+  while (nt > 1 && m_blocks * (N / (64 * nt)) < 512) nt >>= 1;
+  if (g_fp8_nt) nt = g_fp8_nt;
+  if ((nt != 1 && nt != 2 && nt != 4) || N % (64 * nt) != 0) return false;
+  const long long wgs = m_blocks * (N / (64 * nt));
+  // ... then a split of the reduction, each split at least four blocks long
+  int splits = 1;
+  if (wgs < 512) {
+    splits = (int)((768 + wgs - 1) / wgs);
+    if (splits > KB / 4) splits = KB / 4;
+    if (splits > 16) splits = 16;
+    if (splits < 1) splits = 1;
+  }
+  if (g_fp8_splits) splits = g_fp8_splits;
+  if (splits < 1 || splits > KB) return false;
+  const int per = (KB + splits - 1) / splits;
+  splits = (KB + per - 1) / per;                       // no empty split
+  pl = Fp8Plan{mt, nt, splits, per};
+  return true;
+}
 
 extern "C" {
 
@@ -577,6 +614,69 @@ int moe_set_reduction_splits(int n) {
 int moe_set_tile_override(int mt, int nt) {
   if (mt < 0 || nt < 0) return fail(MOE_INVALID_ARGUMENT, "negative tile override");
   g_force_mt = mt; g_force_nt = nt;
+  return MOE_OK;
+}
+
+// ---- blockwise-scaled FP8 GEMM (include/fp8_blockwise_gemm.h) -------------------------------
+size_t fp8_blockwise_gemm_workspace_bytes(int M, int N, int K) {
+  if (M < 1 || N < 64 || K < 128 || K % 128 != 0 || N % 64 != 0) return 0;
+  Fp8Plan pl;
+  if (!fp8_plan(M, N, K, pl)) return 0;
+  return pl.splits > 1 ? round_up((size_t)pl.splits * (size_t)M * (size_t)N * sizeof(float), 256) : 0;
+}
+
+int fp8_blockwise_gemm(const uint8_t* A, const float* a_scale, const uint8_t* B, const float* b_scale, void* C,
+                       int M, int N, int K, int out_dtype, void* workspace, size_t workspace_bytes, void* stream) {
+  if (M < 0 || N < 1 || K < 1) return fail(MOE_INVALID_ARGUMENT, "need M >= 0, N >= 1, K >= 1");
+  if (out_dtype != 0 && out_dtype != 1) return fail(MOE_INVALID_ARGUMENT, "out_dtype must be 0 (fp16) or 1 (bf16)");
+  if (K % 128 != 0 || N % 64 != 0)
+    return fail(MOE_UNSUPPORTED_SHAPE, "the FP8 GEMM needs K %% 128 == 0 and N %% 64 == 0 (got N=%d K=%d)", N, K);
+  if (M == 0) return MOE_OK;
+  if (!A || !a_scale || !B || !b_scale || !C) return fail(MOE_INVALID_ARGUMENT, "null pointer argument");
+  if (((uintptr_t)A | (uintptr_t)B | (uintptr_t)C) % 16 != 0 || ((uintptr_t)a_scale | (uintptr_t)b_scale) % 4 != 0)
+    return fail(MOE_INVALID_ARGUMENT, "A, B, C must be 16-byte aligned, the scales 4-byte aligned");
+  if (C == (const void*)A || C == (const void*)B) return fail(MOE_INVALID_ARGUMENT, "C must not alias an input");
+  Fp8Plan pl;
+  if (!fp8_plan(M, N, K, pl)) return fail(MOE_UNSUPPORTED_SHAPE, "the forced FP8 plan does not fit M=%d N=%d K=%d", M, N, K);
+  const long long m_blocks = (M + 16 * pl.mt - 1) / (16 * pl.mt);
+  const long long grid = m_blocks * (N / (64 * pl.nt)) * pl.splits;
+  if (grid > 0x7fffffffLL) return fail(MOE_UNSUPPORTED_SHAPE, "too many workgroups");
+  fp8::GemmParams p;
+  p.A = A; p.a_scale = a_scale; p.B = B; p.b_scale = b_scale;
+  p.M = M; p.N = N; p.K = K;
+  p.k_splits = pl.splits; p.kb_per_split = pl.kb_per_split; p.out_bf16 = out_dtype;
+  if (pl.splits > 1) {
+    const size_t need = round_up((size_t)pl.splits * (size_t)M * (size_t)N * sizeof(float), 256);
+    if (!workspace || workspace_bytes < need)
+      return fail(MOE_WORKSPACE_TOO_SMALL, "FP8 GEMM workspace: need %zu bytes, got %zu", need, workspace_bytes);
+    if ((uintptr_t)workspace % 256 != 0) return fail(MOE_INVALID_ARGUMENT, "workspace must be 256-byte aligned");
+    p.C = workspace;
+  } else {
+    p.C = C;
+  }
+  // every weight byte is used once per launch when one row block covers M: stream past the caches
+  const int ntl = (m_blocks == 1 && pl.mt <= 4) ? 1 : 0;
+  int err = fp8::launch_fp8_gemm(p, pl.mt, pl.nt, ntl, (hipStream_t)stream);
+  if (err == -1) return fail(MOE_UNSUPPORTED_SHAPE, "no FP8 GEMM variant for tile (%d, %d)", pl.mt, pl.nt);
+  if (err != 0) return hip_fail(err, "FP8 GEMM launch");
+  if (pl.splits > 1) {
+    err = fp8::launch_fp8_split_reduce((const float*)workspace, pl.splits, (long long)M * N, C, out_dtype,
+                                       (hipStream_t)stream);
+    if (err != 0) return hip_fail(err, "FP8 split reduction launch");
+  }
+  return MOE_OK;
+}
+
+int fp8_set_plan_override(int mt, int nt, int k_splits) {
+  if (mt < 0 || nt < 0 || k_splits < 0) return fail(MOE_INVALID_ARGUMENT, "negative plan override");
+  g_fp8_mt = mt; g_fp8_nt = nt; g_fp8_splits = k_splits;
+  return MOE_OK;
+}
+
+int fp8_probe_mfma(void* sink, int iters, void* stream) {
+  if (!sink || iters < 1) return fail(MOE_INVALID_ARGUMENT, "probe needs a sink and iters >= 1");
+  const int err = fp8::launch_fp8_mfma_loop((float*)sink, 512, iters, (hipStream_t)stream);
+  if (err != 0) return hip_fail(err, "FP8 MFMA probe launch");
   return MOE_OK;
 }
 

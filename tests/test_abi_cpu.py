@@ -12,7 +12,7 @@ import pytest
 from oracle import moe_oracle as O
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-HEADER = os.path.join(ROOT, "include", "moe_w4a16.h")
+HEADERS = [os.path.join(ROOT, "include", n) for n in ("moe_w4a16.h", "fp8_blockwise_gemm.h")]
 
 
 @pytest.fixture(scope="module")
@@ -26,9 +26,9 @@ def binding():
 
 
 def declared_functions():
-    text = open(HEADER).read()
+    text = "".join(open(h).read() for h in HEADERS)
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(moe_[a-z0-9_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b((?:moe|fp8)_[a-z0-9_]+)\s*\(", text)))
 
 
 def test_header_declares_the_five_entry_points():

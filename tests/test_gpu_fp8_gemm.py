@@ -1,0 +1,168 @@
+"""GPU parity of the blockwise-scaled FP8 GEMM against the CPU oracle.
+
+Bound, per output element (derived from the arithmetic, not tuned to pass):
+    |gpu - oracle| <= 2^-7 |oracle|  +  2^-10 * sum_kb a_scale[m,kb] b_scale[n/128,kb] amaxA[m,kb] amaxB[n,kb]
+* first term: one unit in the last place of the 16-bit result (8 significant bits for bf16; fp16
+  is finer) -- a near-tie that the float32 and the float64 sums round to different neighbours;
+* second term: the matrix instruction sums the 128 exact products of a block with its own
+  internal alignment, not in full float32: measured on uniformly random codes, the error of one
+  block sum reaches 2^-13.2 of the block's largest product; 2^-10 of the largest possible product
+  of the block (amaxA * amaxB) bounds it with room, and the float32 scale product and the
+  K/128-term float32 accumulation (2^-24 each) vanish next to it.
+For the benchmark's inputs the second term is about half a bf16 ulp of a typical output."""
+from __future__ import annotations
+
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+from moe_workloads.fp8 import FP8_CONFIGS, Fp8GemmConfig, make_fp8_inputs
+from oracle import fp8_oracle as F
+
+pytestmark = pytest.mark.gpu
+
+if torch.cuda.is_available():
+    import paper_2504_16214_amd as M_
+
+
+def say(msg):
+    print(f"[gpu-case] {msg}", flush=True)
+    sys.stdout.flush()
+
+
+def error_bound(want, a_codes, a_scale, b_codes, b_scale):
+    A = np.abs(F.decode_e4m3(a_codes))
+    B = np.abs(F.decode_e4m3(b_codes))
+    Mr, K = A.shape
+    N = B.shape[0]
+    KB = K // 128
+    amaxA = A.reshape(Mr, KB, 128).max(axis=2) * a_scale.astype(np.float64)            # [M, KB]
+    sb_rows = np.repeat(b_scale.astype(np.float64), 128, axis=0)[:N]                     # [N, KB]
+    amaxB = B.reshape(N, KB, 128).max(axis=2) * sb_rows                                  # [N, KB]
+    return 2.0 ** -7 * np.abs(want) + 2.0 ** -10 * (amaxA @ amaxB.T)
+
+
+def run_gemm(a_codes, a_scale, b_codes, b_scale, dtype=torch.bfloat16):
+    Mr, K = a_codes.shape
+    N = b_codes.shape[0]
+    A = torch.from_numpy(a_codes).cuda()
+    B = torch.from_numpy(b_codes).cuda()
+    sa = torch.from_numpy(a_scale).cuda()
+    sb = torch.from_numpy(b_scale).cuda()
+    C = torch.full((Mr, N), float("nan"), dtype=dtype, device="cuda")
+    nbytes = M_.fp8_blockwise_gemm_workspace_bytes(Mr, N, K)
+    ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device="cuda") if nbytes else None
+    M_.fp8_blockwise_gemm(A, sa, B, sb, C, ws)
+    torch.cuda.synchronize()
+    return C.to(torch.float64).cpu().numpy()
+
+
+def check(inp, dtype=torch.bfloat16, what=""):
+    got = run_gemm(inp.a_codes, inp.a_scale, inp.b_codes, inp.b_scale, dtype)
+    want = F.blockwise_gemm(inp.a_codes, inp.a_scale, inp.b_codes, inp.b_scale,
+                            "bf16" if dtype == torch.bfloat16 else "f16")
+    bound = error_bound(want, inp.a_codes, inp.a_scale, inp.b_codes, inp.b_scale)
+    err = np.abs(got - want)
+    assert not np.isnan(got).any(), f"{what}: NaN in the output"
+    worst = float((err / bound).max())
+    say(f"{what}: max err / bound = {worst:.3f}, max |want| = {np.abs(want).max():.3g}")
+    assert worst <= 1.0, f"{what}: {int((err > bound).sum())} of {err.size} outside the bound"
+
+
+@pytest.mark.parametrize("mt,nt,splits", [(mt, nt, sp) for mt in (1, 2, 4, 8) for nt in (1, 2, 4) for sp in (1, 3)])
+def test_every_tile_variant_matches_oracle(mt, nt, splits):
+    """Each compiled tile, with and without a split reduction, on a shape with two row blocks (the
+    second one ragged), two feature blocks and an odd number of reduction blocks."""
+    Mr = 16 * mt + 5
+    cfg = Fp8GemmConfig(f"v{mt}{nt}{splits}", M=Mr, N=2 * 64 * nt, K=128 * 7, seed=100 + 10 * mt + nt)
+    say(f"fp8 gemm tile ({mt},{nt}) splits {splits} M={cfg.M} N={cfg.N} K={cfg.K}")
+    inp = make_fp8_inputs(cfg)
+    M_.fp8_set_plan_override(mt, nt, splits)
+    try:
+        check(inp, what=f"tile ({mt},{nt}) splits {splits}")
+    finally:
+        M_.fp8_set_plan_override(0, 0, 0)
+
+
+@pytest.mark.parametrize("Mr,N,K", [(1, 64, 128), (16, 192, 384), (17, 576, 256), (37, 192, 384), (64, 1024, 1024),
+                                    (100, 320, 640), (130, 2048, 512), (300, 1280, 1152)])
+def test_default_plan_matches_oracle(Mr, N, K):
+    say(f"fp8 gemm default plan M={Mr} N={N} K={K}")
+    check(make_fp8_inputs(Fp8GemmConfig("d", M=Mr, N=N, K=K, seed=Mr + N)), what=f"M={Mr} N={N} K={K}")
+
+
+def test_fp16_output():
+    say("fp8 gemm fp16 output")
+    check(make_fp8_inputs(Fp8GemmConfig("h", M=40, N=256, K=512, seed=9)), dtype=torch.float16, what="fp16 out")
+
+
+def test_uniform_random_codes_and_wide_scales():
+    """Every non-NaN code equally likely (the widest dynamic range a block can have) and scales
+    over four decades."""
+    rng = np.random.default_rng(12)
+    Mr, N, K = 33, 256, 640
+    a = rng.integers(0, 256, size=(Mr, K), dtype=np.uint8); a[(a & 0x7F) == 0x7F] = 0x38
+    b = rng.integers(0, 256, size=(N, K), dtype=np.uint8); b[(b & 0x7F) == 0x7F] = 0xB8
+    sa = np.exp(rng.uniform(np.log(1e-4), np.log(1.0), size=(Mr, K // 128))).astype(np.float32)
+    sb = np.exp(rng.uniform(np.log(1e-4), np.log(1.0), size=(N // 128, K // 128))).astype(np.float32)
+    say(f"fp8 gemm uniform codes M={Mr} N={N} K={K}")
+    got = run_gemm(a, sa, b, sb)
+    want = F.blockwise_gemm(a, sa, b, sb)
+    bound = error_bound(want, a, sa, b, sb)
+    worst = float((np.abs(got - want) / bound).max())
+    say(f"uniform codes: max err / bound = {worst:.3f}")
+    assert worst <= 1.0
+
+
+@pytest.mark.parametrize("name", ["fp8_qkv_decode", "fp8_down_decode", "fp8_qkv_prefill"])
+def test_benchmark_shapes_sampled(name):
+    """Full-size launches in the benchmark's configuration; the oracle recomputes sampled
+    128-row blocks of B (whole scale blocks) against sampled rows of A."""
+    cfg = FP8_CONFIGS[name]
+    say(f"fp8 gemm {name} M={cfg.M} N={cfg.N} K={cfg.K} (sampled)")
+    inp = make_fp8_inputs(cfg)
+    got = run_gemm(inp.a_codes, inp.a_scale, inp.b_codes, inp.b_scale)
+    rng = np.random.default_rng(1)
+    rows = np.sort(rng.choice(cfg.M, size=min(cfg.M, 24), replace=False))
+    rows[-1] = cfg.M - 1
+    blocks = np.sort(rng.choice(cfg.N // 128, size=3, replace=False))
+    blocks[-1] = cfg.N // 128 - 1
+    cols = np.concatenate([np.arange(128 * b, 128 * b + 128) for b in blocks])
+    want = F.blockwise_gemm(inp.a_codes[rows], inp.a_scale[rows], inp.b_codes[cols], inp.b_scale[blocks])
+    bound = error_bound(want, inp.a_codes[rows], inp.a_scale[rows], inp.b_codes[cols], inp.b_scale[blocks])
+    sub = got[np.ix_(rows, cols)]
+    assert not np.isnan(got).any()
+    worst = float((np.abs(sub - want) / bound).max())
+    say(f"{name}: max err / bound = {worst:.3f} on {sub.size} sampled outputs")
+    assert worst <= 1.0
+
+
+def test_empty_and_error_paths():
+    say("fp8 gemm M=0 / errors")
+    inp = make_fp8_inputs(Fp8GemmConfig("e", M=4, N=128, K=256, seed=2))
+    A, B = torch.from_numpy(inp.a_codes).cuda(), torch.from_numpy(inp.b_codes).cuda()
+    sa, sb = torch.from_numpy(inp.a_scale).cuda(), torch.from_numpy(inp.b_scale).cuda()
+    M_.fp8_blockwise_gemm(A[:0], sa[:0], B, sb, torch.empty((0, 128), dtype=torch.bfloat16, device="cuda"))
+    lib = M_.load_library()
+    C = torch.empty((4, 128), dtype=torch.bfloat16, device="cuda")
+    p = lambda t: t.data_ptr()
+    assert lib.fp8_blockwise_gemm(p(A), p(sa), p(B), p(sb), p(C), 4, 128, 200, 1, None, 0, None) == 2     # K % 128
+    assert lib.fp8_blockwise_gemm(p(A), p(sa), p(B), p(sb), p(C), 4, 100, 256, 1, None, 0, None) == 2     # N % 64
+    assert lib.fp8_blockwise_gemm(None, p(sa), p(B), p(sb), p(C), 4, 128, 256, 1, None, 0, None) == 1
+    assert lib.fp8_blockwise_gemm(p(A), p(sa), p(B), p(sb), p(C), 4, 128, 256, 7, None, 0, None) == 1      # dtype
+    M_.fp8_set_plan_override(1, 1, 2)
+    try:
+        assert M_.fp8_blockwise_gemm_workspace_bytes(4, 128, 256) == 2 * 4 * 128 * 4
+        assert lib.fp8_blockwise_gemm(p(A), p(sa), p(B), p(sb), p(C), 4, 128, 256, 1, None, 0, None) == 3  # workspace
+    finally:
+        M_.fp8_set_plan_override(0, 0, 0)
+
+
+def test_mfma_probe_runs():
+    say("fp8 mfma probe")
+    sink = torch.zeros(512 * 256, dtype=torch.float32, device="cuda")
+    M_.fp8_probe_mfma(sink, 64)
+    torch.cuda.synchronize()
+    assert torch.isfinite(sink).all()
