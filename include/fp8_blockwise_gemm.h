@@ -21,7 +21,8 @@
  * float32(a_scale * b_scale) and accumulated in float32.
  *
  * All pointers are caller-owned DEVICE memory; A, B and C 16-byte aligned, scales 4-byte
- * aligned; C must not alias an input.  K % 128 == 0, N % 64 == 0, M >= 0 (M == 0 is a no-op).
+ * aligned; C must not alias an input.  K % 128 == 0, N % 64 == 0, M >= 0 (M == 0 is a no-op),
+ * M * K and N * K below 2^32.
  * Nothing is allocated and nothing synchronises with the host: kernels go to `stream`
  * (a hipStream_t; NULL = the default stream).  `workspace`: at least
  * fp8_blockwise_gemm_workspace_bytes(M, N, K) bytes, 256-byte aligned (float32 partial planes
@@ -46,13 +47,15 @@ int fp8_blockwise_gemm(const uint8_t* A, const float* a_scale, const uint8_t* B,
                        void* workspace, size_t workspace_bytes, void* stream);
 
 /*
- * Tuning hook (thread-local, not part of the operator): force the tile (mt in {1,2,4,8} = rows
- * of A per workgroup / 16, nt in {1,2,4} = rows of B per workgroup / 64) and the number of
- * reduction splits; zeros restore the automatic choice.  A forced plan that does not fit the
+ * Tuning hook (thread-local, not part of the operator): force the tile (mt in {1,2,4,8,16} = rows
+ * of A per workgroup / 16, nt in {1,2,4} = rows of B per workgroup / 64; mt = 16 only with nt = 4)
+ * and the number of
+ * reduction splits, and group_m = how many row blocks form a group in the order tiles are handed
+ * to the XCDs (L2 reuse); zeros restore the automatic choice.  A forced plan that does not fit the
  * shape makes fp8_blockwise_gemm return "unsupported shape".  The workspace size query follows
  * the forced plan.
  */
-int fp8_set_plan_override(int mt, int nt, int k_splits);
+int fp8_set_plan_override(int mt, int nt, int k_splits, int group_m);
 
 /*
  * Achievable-roof probe for the benchmark: a register-resident loop of the FP8 matrix

@@ -72,7 +72,7 @@ def load_library() -> ctypes.CDLL:
     lib.fp8_blockwise_gemm.restype = i32
     lib.fp8_blockwise_gemm.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, vp, sz, vp]
     lib.fp8_set_plan_override.restype = i32
-    lib.fp8_set_plan_override.argtypes = [i32, i32, i32]
+    lib.fp8_set_plan_override.argtypes = [i32, i32, i32, i32]
     lib.fp8_probe_mfma.restype = i32
     lib.fp8_probe_mfma.argtypes = [vp, i32, vp]
     lib.moe_import_awq.restype = i32
@@ -270,8 +270,8 @@ def fp8_blockwise_gemm(A, a_scale, B, b_scale, C, workspace=None, stream=None) -
                                              _stream(stream)))
 
 
-def fp8_set_plan_override(mt: int, nt: int, k_splits: int) -> None:
-    _check(load_library().fp8_set_plan_override(mt, nt, k_splits))
+def fp8_set_plan_override(mt: int, nt: int, k_splits: int, group_m: int = 0) -> None:
+    _check(load_library().fp8_set_plan_override(mt, nt, k_splits, group_m))
 
 
 def fp8_probe_mfma(sink, iters: int, stream=None) -> None:

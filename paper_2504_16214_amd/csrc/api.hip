@@ -286,24 +286,25 @@ static Workspace carve(long long T, int K, int N, int E, int topk) {
 using namespace moe;
 
 // ---- blockwise-scaled FP8 GEMM: tile and split choice --------------------------------------
-static thread_local int g_fp8_mt = 0, g_fp8_nt = 0, g_fp8_splits = 0;
+static thread_local int g_fp8_mt = 0, g_fp8_nt = 0, g_fp8_splits = 0, g_fp8_group_m = 0;
 
-struct Fp8Plan { int mt, nt, splits, kb_per_split; };
+struct Fp8Plan { int bm, bn, splits, kb_per_split; };
 
 // false: the (forced) plan does not fit the shape
 static bool fp8_plan(int M, int N, int K, Fp8Plan& pl) {
   const int KB = K / 128;
-  int mt = M <= 16 ? 1 : M <= 32 ? 2 : M <= 64 ? 4 : 8;
-  if (g_fp8_mt) mt = g_fp8_mt;
-  if (mt != 1 && mt != 2 && mt != 4 && mt != 8) return false;
-  const long long m_blocks = (M + 16 * mt - 1) / (16 * mt);
-  int nt = 4;
-  while (nt > 1 && N % (64 * nt) != 0) nt >>= 1;
+  int bm = M <= 16 ? 16 : M <= 32 ? 32 : M <= 64 ? 64 : 128;
+  if (g_fp8_mt) bm = 16 * g_fp8_mt;
+  if (bm != 16 && bm != 32 && bm != 64 && bm != 128 && bm != 256) return false;
+  const long long m_blocks = (M + bm - 1) / bm;
+  // 128-token tiles run fastest 128 features wide (two workgroups per CU), smaller ones 256 wide
+  int bn = bm == 128 ? 128 : 256;
+  while (bn > 64 && N % bn != 0) bn >>= 1;
   // small problems: narrower feature tiles first (more workgroups streaming weights) ...
-  while (nt > 1 && m_blocks * (N / (64 * nt)) < 512) nt >>= 1;
-  if (g_fp8_nt) nt = g_fp8_nt;
-  if ((nt != 1 && nt != 2 && nt != 4) || N % (64 * nt) != 0) return false;
-  const long long wgs = m_blocks * (N / (64 * nt));
+  while (bn > 64 && m_blocks * (N / bn) < 512) bn >>= 1;
+  if (g_fp8_nt) bn = 64 * g_fp8_nt;
+  if ((bn != 64 && bn != 128 && bn != 256) || N % bn != 0 || (bm == 256 && bn != 256)) return false;
+  const long long wgs = m_blocks * (N / bn);
   // ... then a split of the reduction, each split at least four blocks long
   int splits = 1;
   if (wgs < 512) {
@@ -316,7 +317,7 @@ static bool fp8_plan(int M, int N, int K, Fp8Plan& pl) {
   if (splits < 1 || splits > KB) return false;
   const int per = (KB + splits - 1) / splits;
   splits = (KB + per - 1) / per;                       // no empty split
-  pl = Fp8Plan{mt, nt, splits, per};
+  pl = Fp8Plan{bm, bn, splits, per};
   return true;
 }
 
@@ -638,13 +639,17 @@ int fp8_blockwise_gemm(const uint8_t* A, const float* a_scale, const uint8_t* B,
   if (C == (const void*)A || C == (const void*)B) return fail(MOE_INVALID_ARGUMENT, "C must not alias an input");
   Fp8Plan pl;
   if (!fp8_plan(M, N, K, pl)) return fail(MOE_UNSUPPORTED_SHAPE, "the forced FP8 plan does not fit M=%d N=%d K=%d", M, N, K);
-  const long long m_blocks = (M + 16 * pl.mt - 1) / (16 * pl.mt);
-  const long long grid = m_blocks * (N / (64 * pl.nt)) * pl.splits;
+  if ((unsigned long long)M * (unsigned long long)K >= (1ull << 32) ||
+      (unsigned long long)N * (unsigned long long)K >= (1ull << 32))
+    return fail(MOE_UNSUPPORTED_SHAPE, "the FP8 GEMM addresses A and B with 32-bit offsets: M * K and N * K must be below 2^32");
+  const long long m_blocks = (M + pl.bm - 1) / pl.bm;
+  const long long grid = m_blocks * (N / pl.bn) * pl.splits;
   if (grid > 0x7fffffffLL) return fail(MOE_UNSUPPORTED_SHAPE, "too many workgroups");
   fp8::GemmParams p;
   p.A = A; p.a_scale = a_scale; p.B = B; p.b_scale = b_scale;
   p.M = M; p.N = N; p.K = K;
   p.k_splits = pl.splits; p.kb_per_split = pl.kb_per_split; p.out_bf16 = out_dtype;
+  p.group_m = g_fp8_group_m ? g_fp8_group_m : 8;
   if (pl.splits > 1) {
     const size_t need = round_up((size_t)pl.splits * (size_t)M * (size_t)N * sizeof(float), 256);
     if (!workspace || workspace_bytes < need)
@@ -655,9 +660,9 @@ int fp8_blockwise_gemm(const uint8_t* A, const float* a_scale, const uint8_t* B,
     p.C = C;
   }
   // every weight byte is used once per launch when one row block covers M: stream past the caches
-  const int ntl = (m_blocks == 1 && pl.mt <= 4) ? 1 : 0;
-  int err = fp8::launch_fp8_gemm(p, pl.mt, pl.nt, ntl, (hipStream_t)stream);
-  if (err == -1) return fail(MOE_UNSUPPORTED_SHAPE, "no FP8 GEMM variant for tile (%d, %d)", pl.mt, pl.nt);
+  const int ntl = m_blocks == 1 ? 1 : 0;
+  int err = fp8::launch_fp8_gemm(p, pl.bm, pl.bn, ntl, (hipStream_t)stream);
+  if (err == -1) return fail(MOE_UNSUPPORTED_SHAPE, "no FP8 GEMM variant for tile %d x %d", pl.bm, pl.bn);
   if (err != 0) return hip_fail(err, "FP8 GEMM launch");
   if (pl.splits > 1) {
     err = fp8::launch_fp8_split_reduce((const float*)workspace, pl.splits, (long long)M * N, C, out_dtype,
@@ -667,9 +672,9 @@ int fp8_blockwise_gemm(const uint8_t* A, const float* a_scale, const uint8_t* B,
   return MOE_OK;
 }
 
-int fp8_set_plan_override(int mt, int nt, int k_splits) {
-  if (mt < 0 || nt < 0 || k_splits < 0) return fail(MOE_INVALID_ARGUMENT, "negative plan override");
-  g_fp8_mt = mt; g_fp8_nt = nt; g_fp8_splits = k_splits;
+int fp8_set_plan_override(int mt, int nt, int k_splits, int group_m) {
+  if (mt < 0 || nt < 0 || k_splits < 0 || group_m < 0) return fail(MOE_INVALID_ARGUMENT, "negative plan override");
+  g_fp8_mt = mt; g_fp8_nt = nt; g_fp8_splits = k_splits; g_fp8_group_m = group_m;
   return MOE_OK;
 }
 

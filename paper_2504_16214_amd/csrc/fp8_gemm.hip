@@ -4,20 +4,24 @@
 // v_mfma_f32_16x16x128_f8f6f4, so every matrix instruction starts from a zero accumulator and its
 // result is folded into the float32 accumulator with one scaled FMA per register.
 //
-// Mapping.  A workgroup of four waves owns BM = 16 MT rows of A ("tokens") and BN = 4 * 16 NT rows
-// of B ("features"); wave w owns features [16 NT w, 16 NT (w + 1)) of the tile.  The features are
-// the matrix instruction's row operand and the tokens its column operand, so a lane ends up with
-// one token and 4 NT consecutive features: 16-byte stores, and one activation scale per lane.
-//   * B is never shared inside a workgroup: every wave streams its own rows straight from global
-//     memory in operand order (lane (n, j) reads bytes [16 j, 16 j + 16) and [64 + 16 j, +16) of its
-//     row's 128-byte block: full lines per row), one reduction block ahead, in registers.
-//   * A is shared by the four waves: global -> registers -> LDS (two buffers, one barrier per
-//     block), read back with the same byte permutation.  The order of the 128 reduction indices
-//     inside an instruction is free as long as both operands use the same one.
+// Mapping.  A workgroup of WM x WN waves owns BM rows of A ("tokens") and BN rows of B ("features").
+// The features are the matrix instruction's row operand and the tokens its column operand, so a
+// lane ends up with one token and 4 NT consecutive features: 16-byte stores, one activation scale
+// per lane and row block.
+//   * Both operands go global -> registers -> LDS -> operand registers.  The global loads are
+//     fully coalesced (eight lanes per 128-byte row block); operand-order loads straight from
+//     global memory (one row per lane) cost the texture path four times the cycles and were the
+//     bottleneck of a first version.  LDS rows are 128 bytes with their 16-byte chunks XOR-swizzled
+//     by the row index, two buffers, one barrier per reduction block.
+//   * The order of the 128 reduction indices inside an instruction is free as long as both
+//     operands use the same one: lane group j takes bytes [16 j, +16) and [64 + 16 j, +16) of a row.
+//   * The activation scales of a block travel through LDS with the tile (one load per token).
 //   * Split reduction: blockIdx also selects a range of reduction blocks; split i writes plane i
 //     of a float32 buffer and a second kernel adds the planes in order and rounds once.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+
+#include <type_traits>
 
 #include "fp8_gemm.hpp"
 
@@ -28,8 +32,6 @@ typedef int i32x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-
-constexpr int kPitch = 160;   // LDS bytes per activation row: 128 + 32 (10 chunks: conflict-free operand reads)
 
 __device__ __forceinline__ uint32_t to_bf16_bits(float x) {
   uint32_t u = __float_as_uint(x);
@@ -46,21 +48,35 @@ __device__ __forceinline__ uint32_t pack2(float lo, float hi) {
   return BF16 ? (to_bf16_bits(lo) | (to_bf16_bits(hi) << 16)) : (to_f16_bits(lo) | (to_f16_bits(hi) << 16));
 }
 
-// NTL: weights are read once per launch (one row block): non-temporal loads
-template <int MT, int NT, int NTL>
-__global__ void __launch_bounds__(256)
+// Workgroup = WM x WN waves; wave (wm, wn) owns tokens [16 MT wm, 16 MT (wm + 1)) and features
+// [16 NT wn, 16 NT (wn + 1)) of the BM x BN tile (BM = 16 MT WM, BN = 16 NT WN).
+// NTL: weights are read once per launch (one row block): non-temporal loads.
+template <int WM, int WN, int MT, int NT>
+struct Geom {
+  static constexpr int T = 64 * WM * WN;                 // threads
+  static constexpr int BM = 16 * MT * WM, BN = 16 * NT * WN;
+  static constexpr int RPP = T / 8;                      // tile rows one pass of the workgroup loads
+  static constexpr int AROWS = (BM + RPP - 1) / RPP * RPP;   // activation rows held in LDS (padded to whole passes)
+  static constexpr int CHA = AROWS / RPP, CHB = BN / RPP;    // 16-byte chunks per thread and block
+  static constexpr int STAGE = (AROWS + BN) * 128 + BM * 4;  // bytes: A rows, B rows, BM activation scales
+  static constexpr int LDS = 2 * STAGE;
+  static_assert(BN % RPP == 0, "feature tile must be whole passes");
+};
+
+template <int WM, int WN, int MT, int NT, int NTL>
+__global__ void __launch_bounds__(64 * WM * WN, (WM * WN == 4 && MT * NT <= 16 ? 2 : 1))
 fp8_blockwise_gemm_kernel(const GemmParams p) {
-  constexpr int BM = 16 * MT, WN = 16 * NT, BN = 4 * WN;
-  constexpr int ACH = (BM * 8 + 255) / 256;             // 16-byte chunks of the activation tile per thread
-  __shared__ __attribute__((aligned(16))) unsigned char xs[2][BM * kPitch];
+  using G = Geom<WM, WN, MT, NT>;
+  constexpr int T = G::T, BM = G::BM, BN = G::BN, RPP = G::RPP, AROWS = G::AROWS, CHA = G::CHA, CHB = G::CHB;
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave / WN, wn = wave - wm * WN;
   const int ln = lane & 15, lj = lane >> 4;
 
   // hardware block id -> logical tile: consecutive ids go round the 8 XCDs, so give every XCD a
-  // contiguous range of tiles; inside a range the row blocks of one feature block are neighbours
-  // (they share the weight rows through that XCD's L2)
+  // contiguous range of tiles
   const int total = gridDim.x;
   int L;
   {
@@ -70,42 +86,50 @@ fp8_blockwise_gemm_kernel(const GemmParams p) {
   const int m_blocks = (p.M + BM - 1) / BM, n_blocks = p.N / BN;
   const int split = L / (m_blocks * n_blocks);
   L -= split * (m_blocks * n_blocks);
-  const int nb = L / m_blocks, mb = L - nb * m_blocks;
+  // inside a split, tiles are walked in groups of group_m row blocks: feature block by feature block
+  // inside a group, so the workgroups that run together share both their A rows and their B rows
+  const int per_group = p.group_m * n_blocks;
+  const int grp = L / per_group;
+  const int rem = L - grp * per_group;
+  int m_in = m_blocks - grp * p.group_m;
+  if (m_in > p.group_m) m_in = p.group_m;
+  const int nb = rem / m_in, mb = grp * p.group_m + (rem - nb * m_in);
   const int row0 = mb * BM;                       // first token of the tile
-  const int n0w = nb * BN + wave * WN;            // first feature of this wave
+  const int n0 = nb * BN;                         // first feature of the tile
   const int KB = p.K >> 7;
   const int kb0 = split * p.kb_per_split;
   int kb1 = kb0 + p.kb_per_split;
   if (kb1 > KB) kb1 = KB;
   const int nkb = kb1 - kb0;                      // >= 1 by construction of the grid
 
-  // ---- per-lane source addresses ----
-  const uint8_t* bsrc[NT];
+  // ---- global -> LDS staging: thread t moves chunk (t & 7) of tile row (t >> 3) + RPP * pass ----
+  // LDS row r keeps its chunk c at position c ^ (r & 7): the operand reads below (16 rows, one
+  // chunk position per lane group) then touch every bank group once
+  const int srow = tid >> 3, sc = tid & 7;
+  uint32_t aoff[CHA], boff[CHB];                  // byte offsets from A / B (host checks they fit 32 bits)
 #pragma unroll
-  for (int nt = 0; nt < NT; ++nt) {
-    const int wrow = n0w + 4 * NT * (ln >> 2) + 4 * nt + (ln & 3);     // operand row ln of sub-tile nt
-    bsrc[nt] = p.B + (size_t)wrow * p.K + 16 * lj;
+  for (int i = 0; i < CHA; ++i) {
+    int g = row0 + srow + RPP * i;
+    if (g >= p.M) g = p.M - 1;                    // rows past the matrix repeat its last row (never stored to C)
+    aoff[i] = (uint32_t)g * (uint32_t)p.K + 16u * sc;
   }
-  const uint8_t* asrc[ACH];
-  int adst[ACH];
 #pragma unroll
-  for (int i = 0; i < ACH; ++i) {
-    const int c = tid + 256 * i;
-    int r = c >> 3;
-    if (r >= BM) r = BM - 1;                      // threads beyond the tile repeat its last row (not stored)
-    int g = row0 + r;
-    if (g >= p.M) g = p.M - 1;
-    asrc[i] = p.A + (size_t)g * p.K + 16 * (c & 7);
-    adst[i] = r * kPitch + 16 * (c & 7);
-  }
-  const float* assrc[MT];                         // activation scale of the lane's token in row block mt
-#pragma unroll
-  for (int mt = 0; mt < MT; ++mt) {
-    int g = row0 + 16 * mt + ln;
-    if (g >= p.M) g = p.M - 1;
-    assrc[mt] = p.a_scale + (size_t)g * KB;
-  }
-  const float* bssrc = p.b_scale + (size_t)(n0w >> 7) * KB;      // wave-uniform
+  for (int i = 0; i < CHB; ++i) boff[i] = (uint32_t)(n0 + srow + RPP * i) * (uint32_t)p.K + 16u * sc;
+  const int sdst = srow * 128 + 16 * (sc ^ (srow & 7));      // RPP is a multiple of 8: same swizzle every pass
+  int sg = row0 + tid;                            // activation scale of tile row tid (threads < BM)
+  if (sg >= p.M) sg = p.M - 1;
+  const float* assrc = p.a_scale + (size_t)sg * KB;
+  const float* bssrc = p.b_scale + (size_t)((n0 + wn * 16 * NT) >> 7) * KB;      // wave-uniform
+
+  // ---- operand read positions ----
+  // features: operand row ln of sub-tile nt is feature 4 NT (ln >> 2) + 4 nt + (ln & 3) of the wave's
+  // range, so that a lane ends up with 4 NT consecutive features of its token
+  const int xrow = wm * 16 * MT + ln;             // + 16 mt
+  const int xpos = 16 * (lj ^ (ln & 7));          // tile rows are multiples of 16 apart: (row & 7) == (ln & 7)
+  // sub-tile nt: rows 4 nt further down; (row & 7) changes by 4 (nt & 1), i.e. the position flips by 64
+  const int wr0 = wn * 16 * NT + 4 * NT * (ln >> 2) + (ln & 3);
+  const int wpos0 = (AROWS + wr0) * 128 + 16 * (lj ^ (wr0 & 7));
+  static_assert(NT == 1 || (4 * NT) % 8 == 0, "the swizzle of the feature rows assumes 4 NT % 8 == 0");
 
   f32x4 acc[MT][NT];
 #pragma unroll
@@ -113,80 +137,120 @@ fp8_blockwise_gemm_kernel(const GemmParams p) {
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  i32x4 bw[2][NT][2];          // weight operands, ring of two reduction blocks
-  i32x4 ar[ACH];               // activation chunks on their way to LDS
-  float sa[2][MT], sb[2];
+  // Chunks on their way to LDS.  SPLIT (large tiles): the weight chunks travel during the first
+  // half of a block's arithmetic and the activation chunks during the second, through the same
+  // registers.
+  constexpr bool SPLIT = (CHA + CHB >= 8) && (MT % 2 == 0);
+  constexpr int NSTG = SPLIT ? (CHA > CHB ? CHA : CHB) : CHA + CHB;
+  i32x4 rg[NSTG];
+  float rs = 0.f;              // activation scale on its way to LDS
+  float sb[2];
 
-  auto load_block = [&](int ring, int kb) __attribute__((always_inline)) {
-    const size_t off = (size_t)kb * 128;
+  auto load_b = [&](int kb) __attribute__((always_inline)) {
+    const uint8_t* bb = p.B + (size_t)kb * 128;
 #pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-      const i32x4* s = reinterpret_cast<const i32x4*>(bsrc[nt] + off);
-      if (NTL) {
-        bw[ring][nt][0] = __builtin_nontemporal_load(s);
-        bw[ring][nt][1] = __builtin_nontemporal_load(s + 4);
-      } else {
-        bw[ring][nt][0] = s[0];
-        bw[ring][nt][1] = s[4];
-      }
+    for (int i = 0; i < CHB; ++i) {
+      const i32x4* s = reinterpret_cast<const i32x4*>(bb + boff[i]);
+      rg[i] = NTL ? __builtin_nontemporal_load(s) : *s;
     }
+  };
+  auto load_a = [&](int ring, int kb) __attribute__((always_inline)) {
+    const uint8_t* ab = p.A + (size_t)kb * 128;
+    constexpr int o = SPLIT ? 0 : CHB;
 #pragma unroll
-    for (int i = 0; i < ACH; ++i) ar[i] = *reinterpret_cast<const i32x4*>(asrc[i] + off);
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt) sa[ring][mt] = assrc[mt][kb];
+    for (int i = 0; i < CHA; ++i) rg[o + i] = *reinterpret_cast<const i32x4*>(ab + aoff[i]);
+    if (BM >= T || tid < BM) rs = assrc[kb];
     sb[ring] = bssrc[kb];
   };
-  auto store_a = [&](int buf) __attribute__((always_inline)) {
+  auto store_b = [&](int buf) __attribute__((always_inline)) {
+    unsigned char* st = lds + buf * G::STAGE + AROWS * 128;
 #pragma unroll
-    for (int i = 0; i < ACH; ++i)
-      if (tid + 256 * i < BM * 8) *reinterpret_cast<i32x4*>(&xs[buf][adst[i]]) = ar[i];
+    for (int i = 0; i < CHB; ++i) *reinterpret_cast<i32x4*>(st + sdst + RPP * 128 * i) = rg[i];
   };
-  auto compute = [&](int ring) __attribute__((always_inline)) {
+  auto store_a = [&](int buf) __attribute__((always_inline)) {
+    unsigned char* st = lds + buf * G::STAGE;
+    constexpr int o = SPLIT ? 0 : CHB;
+#pragma unroll
+    for (int i = 0; i < CHA; ++i) *reinterpret_cast<i32x4*>(st + sdst + RPP * 128 * i) = rg[o + i];
+    if (BM >= T || tid < BM) *reinterpret_cast<float*>(st + (AROWS + BN) * 128 + 4 * tid) = rs;
+  };
+  auto read_op = [&](const unsigned char* st, int off) __attribute__((always_inline)) -> i32x8 {
+    // chunk positions c and c ^ 4 of the row: reduction indices [16 lj, +16) and [64 + 16 lj, +16)
+    const i32x4 lo = *reinterpret_cast<const i32x4*>(st + off);
+    const i32x4 hi = *reinterpret_cast<const i32x4*>(st + (off ^ 64));
+    return i32x8{lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+  };
+  i32x8 wa[NT];
+  auto read_w = [&](int ring) __attribute__((always_inline)) {
+    const unsigned char* st = lds + ring * G::STAGE;
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) wa[nt] = read_op(st, (wpos0 + 512 * nt) ^ (64 * (nt & 1)));
+  };
+  // row blocks [MLO, MHI) of the tile against the wave's NT weight operands
+  auto compute = [&](int ring, auto mlo, auto mhi) __attribute__((always_inline)) {
+    constexpr int MLO = decltype(mlo)::value, MHI = decltype(mhi)::value;
+    const unsigned char* st = lds + ring * G::STAGE;
     const float bs = sb[ring];
+    const float* ss = reinterpret_cast<const float*>(st + (AROWS + BN) * 128) + xrow;
+    // the activation operand of row block mt + 1 is read from LDS while row block mt is multiplied
+    i32x8 xa = read_op(st, (xrow + 16 * MLO) * 128 + xpos);
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-      const unsigned char* xp = &xs[ring][(16 * mt + ln) * kPitch + 16 * lj];
-      const i32x4 lo = *reinterpret_cast<const i32x4*>(xp);
-      const i32x4 hi = *reinterpret_cast<const i32x4*>(xp + 64);
-      const i32x8 xa = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
-      const float sp = sa[ring][mt] * bs;
+    for (int mt = MLO; mt < MHI; ++mt) {
+      i32x8 xn = xa;
+      if (mt + 1 < MHI) xn = read_op(st, (xrow + 16 * (mt + 1)) * 128 + xpos);
+      const float sp = ss[16 * mt] * bs;
+      f32x4 part[NT];
 #pragma unroll
-      for (int nt = 0; nt < NT; ++nt) {
-        const i32x4 w0 = bw[ring][nt][0], w1 = bw[ring][nt][1];
-        const i32x8 wa = {w0.x, w0.y, w0.z, w0.w, w1.x, w1.y, w1.z, w1.w};
-        const f32x4 part = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(
-            wa, xa, f32x4{0.f, 0.f, 0.f, 0.f}, 0, 0, 0, 0, 0, 0);       // e4m3 x e4m3, no block exponents
-        acc[mt][nt] += part * sp;
-      }
+      for (int nt = 0; nt < NT; ++nt)
+        part[nt] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(
+            wa[nt], xa, f32x4{0.f, 0.f, 0.f, 0.f}, 0, 0, 0, 0, 0, 0);   // e4m3 x e4m3, no block exponents
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) acc[mt][nt] += part[nt] * sp;
+      xa = xn;
     }
+  };
+  using std::integral_constant;
+  auto stage = [&](int cur, int kb_next) __attribute__((always_inline)) {
+    const int nxt = cur ^ 1;
+    if constexpr (SPLIT) {
+      load_b(kb_next);
+      __builtin_amdgcn_sched_barrier(0);     // the loads stay ahead of the arithmetic they overlap
+      read_w(cur);
+      compute(cur, integral_constant<int, 0>{}, integral_constant<int, MT / 2>{});
+      store_b(nxt);
+      load_a(nxt, kb_next);
+      __builtin_amdgcn_sched_barrier(0);
+      compute(cur, integral_constant<int, MT / 2>{}, integral_constant<int, MT>{});
+      store_a(nxt);
+    } else {
+      load_b(kb_next);
+      load_a(nxt, kb_next);
+      __builtin_amdgcn_sched_barrier(0);
+      read_w(cur);
+      compute(cur, integral_constant<int, 0>{}, integral_constant<int, MT>{});
+      store_b(nxt);
+      store_a(nxt);
+    }
+    __syncthreads();
   };
 
   // ---- pipeline: block i + 1 is in flight while block i is multiplied ----
-  load_block(0, kb0);
+  load_b(kb0);
+  if constexpr (SPLIT) { store_b(0); }
+  load_a(0, kb0);
+  if constexpr (!SPLIT) { store_b(0); }
   store_a(0);
   __syncthreads();
   for (int it = 0; it < nkb; it += 2) {
-    {
-      const int nx = it + 1 < nkb ? it + 1 : nkb - 1;      // past the end: a valid block, never consumed
-      load_block(1, kb0 + nx);
-      compute(0);
-      store_a(1);
-      __syncthreads();
-    }
-    if (it + 1 < nkb) {
-      const int nx = it + 2 < nkb ? it + 2 : nkb - 1;
-      load_block(0, kb0 + nx);
-      compute(1);
-      store_a(0);
-      __syncthreads();
-    }
+    stage(0, kb0 + (it + 1 < nkb ? it + 1 : nkb - 1));      // past the end: a valid block, never consumed
+    if (it + 1 < nkb) stage(1, kb0 + (it + 2 < nkb ? it + 2 : nkb - 1));
   }
 
   // ---- epilogue: the lane's token, 4 NT consecutive features ----
-  const int f0 = n0w + 4 * NT * lj;
+  const int f0 = n0 + wn * 16 * NT + 4 * NT * lj;
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {
-    const int t = row0 + 16 * mt + ln;
+    const int t = row0 + xrow + 16 * mt;
     if (t >= p.M) continue;
     if (p.k_splits > 1) {
       float* dst = reinterpret_cast<float*>(p.C) + ((size_t)split * p.M + t) * p.N + f0;
@@ -228,41 +292,42 @@ fp8_split_reduce_kernel(const f32x4* __restrict__ planes, int k_splits, long lon
   }
 }
 
-template <int MT, int NT, int NTL>
+template <int WM, int WN, int MT, int NT, int NTL>
 static int launch_one(const GemmParams& p, hipStream_t stream) {
-  constexpr int BM = 16 * MT, BN = 64 * NT;
-  const int grid = ((p.M + BM - 1) / BM) * (p.N / BN) * p.k_splits;
-  hipLaunchKernelGGL((fp8_blockwise_gemm_kernel<MT, NT, NTL>), dim3(grid), dim3(256), 0, stream, p);
+  using G = Geom<WM, WN, MT, NT>;
+  auto kern = fp8_blockwise_gemm_kernel<WM, WN, MT, NT, NTL>;
+  if (G::LDS > 64 * 1024) {
+    // raise the dynamic LDS limit of this kernel once per device
+    constexpr int kMaxDev = 64;
+    static bool allowed[kMaxDev] = {};
+    int dev = 0;
+    hipError_t err = hipGetDevice(&dev);
+    if (err != hipSuccess) return (int)err;
+    if (dev < 0 || dev >= kMaxDev || !allowed[dev]) {
+      err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                G::LDS);
+      if (err != hipSuccess) return (int)err;
+      if (dev >= 0 && dev < kMaxDev) allowed[dev] = true;
+    }
+  }
+  const int grid = ((p.M + G::BM - 1) / G::BM) * (p.N / G::BN) * p.k_splits;
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(G::T), G::LDS, stream, p);
   return (int)hipGetLastError();
 }
 
-template <int MT>
-static int launch_mt(const GemmParams& p, int nt, int ntl, hipStream_t stream) {
-  if (MT <= 4 && ntl) {
-    constexpr int NTLv = MT <= 4 ? 1 : 0;
-    switch (nt) {
-      case 1: return launch_one<MT, 1, NTLv>(p, stream);
-      case 2: return launch_one<MT, 2, NTLv>(p, stream);
-      case 4: return launch_one<MT, 4, NTLv>(p, stream);
-    }
-  } else {
-    switch (nt) {
-      case 1: return launch_one<MT, 1, 0>(p, stream);
-      case 2: return launch_one<MT, 2, 0>(p, stream);
-      case 4: return launch_one<MT, 4, 0>(p, stream);
-    }
-  }
-  return -1;
-}
-
-// mt in {1, 2, 4, 8}, nt in {1, 2, 4}; -1: no such variant
-int launch_fp8_gemm(const GemmParams& p, int mt, int nt, int ntl, hipStream_t stream) {
-  switch (mt) {
-    case 1: return launch_mt<1>(p, nt, ntl, stream);
-    case 2: return launch_mt<2>(p, nt, ntl, stream);
-    case 4: return launch_mt<4>(p, nt, ntl, stream);
-    case 8: return launch_mt<8>(p, nt, ntl, stream);
-  }
+// Tiles.  bm = tokens per workgroup in {16, 32, 64, 128, 256}, bn = features per workgroup in
+// {64, 128, 256}; 256 x 256 runs eight waves (2 x 4), everything else four (1 x 4).
+// ntl: non-temporal weight loads.  Returns a hipError_t, or -1 for an unknown tile.
+int launch_fp8_gemm(const GemmParams& p, int bm, int bn, int ntl, hipStream_t stream) {
+#define FP8_TILE(BMv, BNv, WMv, WNv, MTv, NTv)                                        \
+  if (bm == BMv && bn == BNv)                                                         \
+    return ntl ? launch_one<WMv, WNv, MTv, NTv, 1>(p, stream) : launch_one<WMv, WNv, MTv, NTv, 0>(p, stream);
+  FP8_TILE(16, 64, 1, 4, 1, 1)   FP8_TILE(16, 128, 1, 4, 1, 2)   FP8_TILE(16, 256, 1, 4, 1, 4)
+  FP8_TILE(32, 64, 1, 4, 2, 1)   FP8_TILE(32, 128, 1, 4, 2, 2)   FP8_TILE(32, 256, 1, 4, 2, 4)
+  FP8_TILE(64, 64, 1, 4, 4, 1)   FP8_TILE(64, 128, 1, 4, 4, 2)   FP8_TILE(64, 256, 1, 4, 4, 4)
+  FP8_TILE(128, 64, 1, 4, 8, 1)  FP8_TILE(128, 128, 1, 4, 8, 2)  FP8_TILE(128, 256, 1, 4, 8, 4)
+  FP8_TILE(256, 256, 2, 4, 8, 4)
+#undef FP8_TILE
   return -1;
 }
 

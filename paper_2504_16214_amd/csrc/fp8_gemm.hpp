@@ -15,11 +15,14 @@ struct GemmParams {
   int k_splits;        // >= 1
   int kb_per_split;    // reduction blocks per split (the last split may be shorter)
   int out_bf16;        // 16-bit output type when k_splits == 1: 1 bf16, 0 fp16
+  int group_m;         // row blocks per tile group (>= 1): the order in which tiles are handed out
 };
 
-// mt in {1, 2, 4, 8} (16 mt rows of A per workgroup), nt in {1, 2, 4} (64 nt rows of B per workgroup),
-// ntl: non-temporal weight loads (mt <= 4 only).  Returns a hipError_t, or -1 for an unknown variant.
-int launch_fp8_gemm(const GemmParams& p, int mt, int nt, int ntl, hipStream_t stream);
+// bm = tokens per workgroup in {16, 32, 64, 128, 256}, bn = features per workgroup in {64, 128, 256}
+// (256 x 256 and bm <= 128 with any bn), ntl: non-temporal weight loads.  A and B are addressed with
+// 32-bit byte offsets: M * K and N * K must be below 2^32.  Returns a hipError_t, or -1 for an
+// unknown tile.
+int launch_fp8_gemm(const GemmParams& p, int bm, int bn, int ntl, hipStream_t stream);
 int launch_fp8_split_reduce(const float* planes, int k_splits, long long mn, void* C, int out_bf16,
                             hipStream_t stream);
 

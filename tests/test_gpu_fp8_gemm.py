@@ -71,7 +71,8 @@ def check(inp, dtype=torch.bfloat16, what=""):
     assert worst <= 1.0, f"{what}: {int((err > bound).sum())} of {err.size} outside the bound"
 
 
-@pytest.mark.parametrize("mt,nt,splits", [(mt, nt, sp) for mt in (1, 2, 4, 8) for nt in (1, 2, 4) for sp in (1, 3)])
+@pytest.mark.parametrize("mt,nt,splits", [(mt, nt, sp) for mt in (1, 2, 4, 8) for nt in (1, 2, 4) for sp in (1, 3)]
+                         + [(16, 4, 1), (16, 4, 3)])
 def test_every_tile_variant_matches_oracle(mt, nt, splits):
     """Each compiled tile, with and without a split reduction, on a shape with two row blocks (the
     second one ragged), two feature blocks and an odd number of reduction blocks."""
@@ -79,11 +80,11 @@ def test_every_tile_variant_matches_oracle(mt, nt, splits):
     cfg = Fp8GemmConfig(f"v{mt}{nt}{splits}", M=Mr, N=2 * 64 * nt, K=128 * 7, seed=100 + 10 * mt + nt)
     say(f"fp8 gemm tile ({mt},{nt}) splits {splits} M={cfg.M} N={cfg.N} K={cfg.K}")
     inp = make_fp8_inputs(cfg)
-    M_.fp8_set_plan_override(mt, nt, splits)
+    M_.fp8_set_plan_override(mt, nt, splits, 3)
     try:
         check(inp, what=f"tile ({mt},{nt}) splits {splits}")
     finally:
-        M_.fp8_set_plan_override(0, 0, 0)
+        M_.fp8_set_plan_override(0, 0, 0, 0)
 
 
 @pytest.mark.parametrize("Mr,N,K", [(1, 64, 128), (16, 192, 384), (17, 576, 256), (37, 192, 384), (64, 1024, 1024),
@@ -152,12 +153,12 @@ def test_empty_and_error_paths():
     assert lib.fp8_blockwise_gemm(p(A), p(sa), p(B), p(sb), p(C), 4, 100, 256, 1, None, 0, None) == 2     # N % 64
     assert lib.fp8_blockwise_gemm(None, p(sa), p(B), p(sb), p(C), 4, 128, 256, 1, None, 0, None) == 1
     assert lib.fp8_blockwise_gemm(p(A), p(sa), p(B), p(sb), p(C), 4, 128, 256, 7, None, 0, None) == 1      # dtype
-    M_.fp8_set_plan_override(1, 1, 2)
+    M_.fp8_set_plan_override(1, 1, 2, 0)
     try:
         assert M_.fp8_blockwise_gemm_workspace_bytes(4, 128, 256) == 2 * 4 * 128 * 4
         assert lib.fp8_blockwise_gemm(p(A), p(sa), p(B), p(sb), p(C), 4, 128, 256, 1, None, 0, None) == 3  # workspace
     finally:
-        M_.fp8_set_plan_override(0, 0, 0)
+        M_.fp8_set_plan_override(0, 0, 0, 0)
 
 
 def test_mfma_probe_runs():
