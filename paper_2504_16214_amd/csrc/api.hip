@@ -297,8 +297,9 @@ static bool fp8_plan(int M, int N, int K, Fp8Plan& pl) {
   if (g_fp8_mt) bm = 16 * g_fp8_mt;
   if (bm != 16 && bm != 32 && bm != 64 && bm != 128 && bm != 256) return false;
   const long long m_blocks = (M + bm - 1) / bm;
-  // 128-token tiles run fastest 128 features wide (two workgroups per CU), smaller ones 256 wide
-  int bn = bm == 128 ? 128 : 256;
+  // 128 features per workgroup measured fastest at every token-tile height (two or more
+  // workgroups per CU; 256 wide costs occupancy, 64 wide LDS traffic per matrix instruction)
+  int bn = 128;
   while (bn > 64 && N % bn != 0) bn >>= 1;
   // small problems: narrower feature tiles first (more workgroups streaming weights) ...
   while (bn > 64 && m_blocks * (N / bn) < 512) bn >>= 1;

@@ -116,7 +116,7 @@ fp8_blockwise_gemm_kernel(const GemmParams p) {
 #pragma unroll
   for (int i = 0; i < CHB; ++i) boff[i] = (uint32_t)(n0 + srow + RPP * i) * (uint32_t)p.K + 16u * sc;
   const int sdst = srow * 128 + 16 * (sc ^ (srow & 7));      // RPP is a multiple of 8: same swizzle every pass
-  int sg = row0 + tid;                            // activation scale of tile row tid (threads < BM)
+  int sg = row0 + (tid < BM ? tid : BM - 1);      // activation scale of tile row tid (stored by threads < BM)
   if (sg >= p.M) sg = p.M - 1;
   const float* assrc = p.a_scale + (size_t)sg * KB;
   const float* bssrc = p.b_scale + (size_t)((n0 + wn * 16 * NT) >> 7) * KB;      // wave-uniform
@@ -147,6 +147,9 @@ fp8_blockwise_gemm_kernel(const GemmParams p) {
   float sb[2];
 
   auto load_b = [&](int kb) __attribute__((always_inline)) {
+#ifdef FP8_EXP_SAMEBLOCK
+    kb = kb0;
+#endif
     const uint8_t* bb = p.B + (size_t)kb * 128;
 #pragma unroll
     for (int i = 0; i < CHB; ++i) {
@@ -155,11 +158,14 @@ fp8_blockwise_gemm_kernel(const GemmParams p) {
     }
   };
   auto load_a = [&](int ring, int kb) __attribute__((always_inline)) {
+#ifdef FP8_EXP_SAMEBLOCK
+    kb = kb0;
+#endif
     const uint8_t* ab = p.A + (size_t)kb * 128;
     constexpr int o = SPLIT ? 0 : CHB;
 #pragma unroll
     for (int i = 0; i < CHA; ++i) rg[o + i] = *reinterpret_cast<const i32x4*>(ab + aoff[i]);
-    if (BM >= T || tid < BM) rs = assrc[kb];
+    rs = assrc[kb];
     sb[ring] = bssrc[kb];
   };
   auto store_b = [&](int buf) __attribute__((always_inline)) {
@@ -181,8 +187,13 @@ fp8_blockwise_gemm_kernel(const GemmParams p) {
     return i32x8{lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
   };
   i32x8 wa[NT];
+  float sp[MT];                // a_scale * b_scale of the lane's token in every row block
   auto read_w = [&](int ring) __attribute__((always_inline)) {
     const unsigned char* st = lds + ring * G::STAGE;
+    const float* ss = reinterpret_cast<const float*>(st + (AROWS + BN) * 128) + xrow;
+    const float bs = sb[ring];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) sp[mt] = ss[16 * mt] * bs;
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) wa[nt] = read_op(st, (wpos0 + 512 * nt) ^ (64 * (nt & 1)));
   };
@@ -190,24 +201,42 @@ fp8_blockwise_gemm_kernel(const GemmParams p) {
   auto compute = [&](int ring, auto mlo, auto mhi) __attribute__((always_inline)) {
     constexpr int MLO = decltype(mlo)::value, MHI = decltype(mhi)::value;
     const unsigned char* st = lds + ring * G::STAGE;
-    const float bs = sb[ring];
-    const float* ss = reinterpret_cast<const float*>(st + (AROWS + BN) * 128) + xrow;
-    // the activation operand of row block mt + 1 is read from LDS while row block mt is multiplied
+    // software pipeline: the activation operand of row block mt + 1 is read from LDS, and the
+    // partial sums of row block mt - 1 are folded into the accumulators, while row block mt is
+    // in the matrix unit
     i32x8 xa = read_op(st, (xrow + 16 * MLO) * 128 + xpos);
+    f32x4 pprev[NT];
 #pragma unroll
     for (int mt = MLO; mt < MHI; ++mt) {
       i32x8 xn = xa;
       if (mt + 1 < MHI) xn = read_op(st, (xrow + 16 * (mt + 1)) * 128 + xpos);
-      const float sp = ss[16 * mt] * bs;
       f32x4 part[NT];
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt)
         part[nt] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(
             wa[nt], xa, f32x4{0.f, 0.f, 0.f, 0.f}, 0, 0, 0, 0, 0, 0);   // e4m3 x e4m3, no block exponents
+      if (mt > MLO) {
 #pragma unroll
-      for (int nt = 0; nt < NT; ++nt) acc[mt][nt] += part[nt] * sp;
+        for (int nt = 0; nt < NT; ++nt) acc[mt - 1][nt] += pprev[nt] * sp[mt - 1];
+      }
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) pprev[nt] = part[nt];
       xa = xn;
+      // Instruction order.  Left to itself the scheduler gathers every FMA of the block at its
+      // end, which keeps all partial sums alive.  An empty asm that takes the accumulators just
+      // updated and the next activation operand ties them together: the matrix instructions of
+      // row block mt + 1 cannot start before the FMAs of row block mt - 1 are done.
+      if (mt > MLO) {
+        if constexpr (NT == 4)
+          asm volatile("" : "+v"(acc[mt - 1][0]), "+v"(acc[mt - 1][1]), "+v"(acc[mt - 1][2]), "+v"(acc[mt - 1][3]), "+v"(xa));
+        else if constexpr (NT == 2)
+          asm volatile("" : "+v"(acc[mt - 1][0]), "+v"(acc[mt - 1][1]), "+v"(xa));
+        else
+          asm volatile("" : "+v"(acc[mt - 1][0]), "+v"(xa));
+      }
     }
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) acc[MHI - 1][nt] += pprev[nt] * sp[MHI - 1];
   };
   using std::integral_constant;
   auto stage = [&](int cur, int kb_next) __attribute__((always_inline)) {
@@ -216,6 +245,7 @@ fp8_blockwise_gemm_kernel(const GemmParams p) {
       load_b(kb_next);
       __builtin_amdgcn_sched_barrier(0);     // the loads stay ahead of the arithmetic they overlap
       read_w(cur);
+      __builtin_amdgcn_sched_barrier(0);     // scales and weight operands are read before the arithmetic
       compute(cur, integral_constant<int, 0>{}, integral_constant<int, MT / 2>{});
       store_b(nxt);
       load_a(nxt, kb_next);
@@ -227,6 +257,7 @@ fp8_blockwise_gemm_kernel(const GemmParams p) {
       load_a(nxt, kb_next);
       __builtin_amdgcn_sched_barrier(0);
       read_w(cur);
+      __builtin_amdgcn_sched_barrier(0);
       compute(cur, integral_constant<int, 0>{}, integral_constant<int, MT>{});
       store_b(nxt);
       store_a(nxt);
