@@ -44,6 +44,7 @@ FP8_CONFIGS: Dict[str, Fp8GemmConfig] = {c.name: c for c in [
     Fp8GemmConfig("fp8_tiny", M=37, N=192, K=384),
     Fp8GemmConfig("fp8_qkv_decode", M=64, N=10240, K=5120),
     Fp8GemmConfig("fp8_down_decode", M=16, N=5120, K=25600),
+    Fp8GemmConfig("fp8_gateup_decode", M=32, N=51200, K=5120),
     Fp8GemmConfig("fp8_gateup_prefill", M=4096, N=51200, K=5120),
     Fp8GemmConfig("fp8_qkv_prefill", M=4096, N=10240, K=5120),
     Fp8GemmConfig("fp8_down_prefill", M=4096, N=5120, K=25600),

@@ -302,13 +302,13 @@ static bool fp8_plan(int M, int N, int K, Fp8Plan& pl) {
   int bn = 128;
   while (bn > 64 && N % bn != 0) bn >>= 1;
   // small problems: narrower feature tiles first (more workgroups streaming weights) ...
-  while (bn > 64 && m_blocks * (N / bn) < 512) bn >>= 1;
+  while (bn > 64 && m_blocks * (N / bn) < 256) bn >>= 1;
   if (g_fp8_nt) bn = 64 * g_fp8_nt;
   if ((bn != 64 && bn != 128 && bn != 256) || N % bn != 0 || (bm == 256 && bn != 256)) return false;
   const long long wgs = m_blocks * (N / bn);
   // ... then a split of the reduction, each split at least four blocks long
   int splits = 1;
-  if (wgs < 512) {
+  if (wgs < 256) {
     splits = (int)((768 + wgs - 1) / wgs);
     if (splits > KB / 4) splits = KB / 4;
     if (splits > 16) splits = 16;

@@ -117,7 +117,7 @@ def test_uniform_random_codes_and_wide_scales():
     assert worst <= 1.0
 
 
-@pytest.mark.parametrize("name", ["fp8_qkv_decode", "fp8_down_decode", "fp8_qkv_prefill"])
+@pytest.mark.parametrize("name", ["fp8_qkv_decode", "fp8_down_decode", "fp8_gateup_decode", "fp8_qkv_prefill"])
 def test_benchmark_shapes_sampled(name):
     """Full-size launches in the benchmark's configuration; the oracle recomputes sampled
     128-row blocks of B (whole scale blocks) against sampled rows of A."""
