@@ -660,9 +660,7 @@ int fp8_blockwise_gemm(const uint8_t* A, const float* a_scale, const uint8_t* B,
   } else {
     p.C = C;
   }
-  // every weight byte is used once per launch when one row block covers M: stream past the caches
-  const int ntl = m_blocks == 1 ? 1 : 0;
-  int err = fp8::launch_fp8_gemm(p, pl.bm, pl.bn, ntl, (hipStream_t)stream);
+  int err = fp8::launch_fp8_gemm(p, pl.bm, pl.bn, (hipStream_t)stream);
   if (err == -1) return fail(MOE_UNSUPPORTED_SHAPE, "no FP8 GEMM variant for tile %d x %d", pl.bm, pl.bn);
   if (err != 0) return hip_fail(err, "FP8 GEMM launch");
   if (pl.splits > 1) {

@@ -8,14 +8,17 @@
 // The features are the matrix instruction's row operand and the tokens its column operand, so a
 // lane ends up with one token and 4 NT consecutive features: 16-byte stores, one activation scale
 // per lane and row block.
-//   * Both operands go global -> registers -> LDS -> operand registers.  The global loads are
-//     fully coalesced (eight lanes per 128-byte row block); operand-order loads straight from
-//     global memory (one row per lane) cost the texture path four times the cycles and were the
-//     bottleneck of a first version.  LDS rows are 128 bytes with their 16-byte chunks XOR-swizzled
-//     by the row index, two buffers, one barrier per reduction block.
+//   * Both operands go global -> LDS with direct-to-LDS loads (global_load_lds_dwordx4: no staging
+//     registers, no ds_write) -> operand registers.  The global side is fully coalesced (eight lanes
+//     per 128-byte row block); operand-order loads straight from global memory (one row per lane)
+//     cost the texture path four times the cycles and were the bottleneck of a first version.  LDS
+//     rows are 128 bytes with their 16-byte chunks XOR-swizzled by the row index (the swizzle is
+//     applied on the global side: which chunk a lane fetches), two buffers, one barrier per
+//     reduction block; every wave waits for its own loads (vmcnt(0)) before that barrier.
 //   * The order of the 128 reduction indices inside an instruction is free as long as both
 //     operands use the same one: lane group j takes bytes [16 j, +16) and [64 + 16 j, +16) of a row.
-//   * The activation scales of a block travel through LDS with the tile (one load per token).
+//   * The activation scales of a block travel through LDS with the tile (one 4-byte direct-to-LDS
+//     load per token).
 //   * Split reduction: blockIdx also selects a range of reduction blocks; split i writes plane i
 //     of a float32 buffer and a second kernel adds the planes in order and rounds once.
 #include <hip/hip_runtime.h>
@@ -50,7 +53,6 @@ __device__ __forceinline__ uint32_t pack2(float lo, float hi) {
 
 // Workgroup = WM x WN waves; wave (wm, wn) owns tokens [16 MT wm, 16 MT (wm + 1)) and features
 // [16 NT wn, 16 NT (wn + 1)) of the BM x BN tile (BM = 16 MT WM, BN = 16 NT WN).
-// NTL: weights are read once per launch (one row block): non-temporal loads.
 template <int WM, int WN, int MT, int NT>
 struct Geom {
   static constexpr int T = 64 * WM * WN;                 // threads
@@ -58,12 +60,13 @@ struct Geom {
   static constexpr int RPP = T / 8;                      // tile rows one pass of the workgroup loads
   static constexpr int AROWS = (BM + RPP - 1) / RPP * RPP;   // activation rows held in LDS (padded to whole passes)
   static constexpr int CHA = AROWS / RPP, CHB = BN / RPP;    // 16-byte chunks per thread and block
-  static constexpr int STAGE = (AROWS + BN) * 128 + BM * 4;  // bytes: A rows, B rows, BM activation scales
+  static constexpr int SCALES = BM < 64 ? 64 : BM;          // activation-scale slots (a whole wave's worth at least)
+  static constexpr int STAGE = (AROWS + BN) * 128 + SCALES * 4;  // bytes: A rows, B rows, activation scales
   static constexpr int LDS = 2 * STAGE;
   static_assert(BN % RPP == 0, "feature tile must be whole passes");
 };
 
-template <int WM, int WN, int MT, int NT, int NTL>
+template <int WM, int WN, int MT, int NT>
 __global__ void __launch_bounds__(64 * WM * WN, (WM * WN == 4 && MT * NT <= 16 ? 2 : 1))
 fp8_blockwise_gemm_kernel(const GemmParams p) {
   using G = Geom<WM, WN, MT, NT>;
@@ -102,21 +105,23 @@ fp8_blockwise_gemm_kernel(const GemmParams p) {
   if (kb1 > KB) kb1 = KB;
   const int nkb = kb1 - kb0;                      // >= 1 by construction of the grid
 
-  // ---- global -> LDS staging: thread t moves chunk (t & 7) of tile row (t >> 3) + RPP * pass ----
+  // ---- global -> LDS: direct-to-LDS loads (no staging registers, no ds_write) ----
   // LDS row r keeps its chunk c at position c ^ (r & 7): the operand reads below (16 rows, one
-  // chunk position per lane group) then touch every bank group once
+  // chunk position per lane group) then touch every bank group once.  One load instruction of a
+  // wave fills 1 KiB of LDS in lane order = 8 rows x 8 positions; the lane at position s of row r
+  // therefore fetches chunk s ^ (r & 7) of that row.  Pass i of the workgroup covers tile rows
+  // [RPP i, RPP (i + 1)), wave w rows 8 w .. 8 w + 7 of the pass.
   const int srow = tid >> 3, sc = tid & 7;
   uint32_t aoff[CHA], boff[CHB];                  // byte offsets from A / B (host checks they fit 32 bits)
 #pragma unroll
   for (int i = 0; i < CHA; ++i) {
     int g = row0 + srow + RPP * i;
     if (g >= p.M) g = p.M - 1;                    // rows past the matrix repeat its last row (never stored to C)
-    aoff[i] = (uint32_t)g * (uint32_t)p.K + 16u * sc;
+    aoff[i] = (uint32_t)g * (uint32_t)p.K + 16u * (sc ^ (srow & 7));
   }
 #pragma unroll
-  for (int i = 0; i < CHB; ++i) boff[i] = (uint32_t)(n0 + srow + RPP * i) * (uint32_t)p.K + 16u * sc;
-  const int sdst = srow * 128 + 16 * (sc ^ (srow & 7));      // RPP is a multiple of 8: same swizzle every pass
-  int sg = row0 + (tid < BM ? tid : BM - 1);      // activation scale of tile row tid (stored by threads < BM)
+  for (int i = 0; i < CHB; ++i) boff[i] = (uint32_t)(n0 + srow + RPP * i) * (uint32_t)p.K + 16u * (sc ^ (srow & 7));
+  int sg = row0 + (tid < BM ? tid : BM - 1);      // activation scale of tile row tid (threads past BM repeat the last row)
   if (sg >= p.M) sg = p.M - 1;
   const float* assrc = p.a_scale + (size_t)sg * KB;
   const float* bssrc = p.b_scale + (size_t)((n0 + wn * 16 * NT) >> 7) * KB;      // wave-uniform
@@ -137,48 +142,24 @@ fp8_blockwise_gemm_kernel(const GemmParams p) {
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  // Chunks on their way to LDS.  SPLIT (large tiles): the weight chunks travel during the first
-  // half of a block's arithmetic and the activation chunks during the second, through the same
-  // registers.
-  constexpr bool SPLIT = (CHA + CHB >= 8) && (MT % 2 == 0);
-  constexpr int NSTG = SPLIT ? (CHA > CHB ? CHA : CHB) : CHA + CHB;
-  i32x4 rg[NSTG];
-  float rs = 0.f;              // activation scale on its way to LDS
-  float sb[2];
+  float sb[2];                // weight-block scale of the block in each LDS buffer
 
-  auto load_b = [&](int kb) __attribute__((always_inline)) {
-#ifdef FP8_EXP_SAMEBLOCK
-    kb = kb0;
-#endif
-    const uint8_t* bb = p.B + (size_t)kb * 128;
-#pragma unroll
-    for (int i = 0; i < CHB; ++i) {
-      const i32x4* s = reinterpret_cast<const i32x4*>(bb + boff[i]);
-      rg[i] = NTL ? __builtin_nontemporal_load(s) : *s;
-    }
-  };
-  auto load_a = [&](int ring, int kb) __attribute__((always_inline)) {
-#ifdef FP8_EXP_SAMEBLOCK
-    kb = kb0;
-#endif
+  typedef const __attribute__((address_space(1))) void* gptr_t;
+  typedef __attribute__((address_space(3))) void* lptr_t;
+  auto dma_block = [&](int buf, int kb) __attribute__((always_inline)) {
     const uint8_t* ab = p.A + (size_t)kb * 128;
-    constexpr int o = SPLIT ? 0 : CHB;
+    const uint8_t* bb = p.B + (size_t)kb * 128;
+    unsigned char* st = lds + buf * G::STAGE + 1024 * wave;            // this wave's 8 rows of every pass
 #pragma unroll
-    for (int i = 0; i < CHA; ++i) rg[o + i] = *reinterpret_cast<const i32x4*>(ab + aoff[i]);
-    rs = assrc[kb];
-    sb[ring] = bssrc[kb];
-  };
-  auto store_b = [&](int buf) __attribute__((always_inline)) {
-    unsigned char* st = lds + buf * G::STAGE + AROWS * 128;
+    for (int i = 0; i < CHB; ++i)
+      __builtin_amdgcn_global_load_lds((gptr_t)(bb + boff[i]), (lptr_t)(st + (AROWS + RPP * i) * 128), 16, 0, 0);
 #pragma unroll
-    for (int i = 0; i < CHB; ++i) *reinterpret_cast<i32x4*>(st + sdst + RPP * 128 * i) = rg[i];
-  };
-  auto store_a = [&](int buf) __attribute__((always_inline)) {
-    unsigned char* st = lds + buf * G::STAGE;
-    constexpr int o = SPLIT ? 0 : CHB;
-#pragma unroll
-    for (int i = 0; i < CHA; ++i) *reinterpret_cast<i32x4*>(st + sdst + RPP * 128 * i) = rg[o + i];
-    if (BM >= T || tid < BM) *reinterpret_cast<float*>(st + (AROWS + BN) * 128 + 4 * tid) = rs;
+    for (int i = 0; i < CHA; ++i)
+      __builtin_amdgcn_global_load_lds((gptr_t)(ab + aoff[i]), (lptr_t)(st + RPP * i * 128), 16, 0, 0);
+    if (64 * wave < G::SCALES)                                         // wave-uniform
+      __builtin_amdgcn_global_load_lds((gptr_t)(assrc + kb),
+                                       (lptr_t)(lds + buf * G::STAGE + (AROWS + BN) * 128 + 256 * wave), 4, 0, 0);
+    sb[buf] = bssrc[kb];
   };
   auto read_op = [&](const unsigned char* st, int off) __attribute__((always_inline)) -> i32x8 {
     // chunk positions c and c ^ 4 of the row: reduction indices [16 lj, +16) and [64 + 16 lj, +16)
@@ -241,36 +222,18 @@ fp8_blockwise_gemm_kernel(const GemmParams p) {
   using std::integral_constant;
   auto stage = [&](int cur, int kb_next) __attribute__((always_inline)) {
     const int nxt = cur ^ 1;
-    if constexpr (SPLIT) {
-      load_b(kb_next);
-      __builtin_amdgcn_sched_barrier(0);     // the loads stay ahead of the arithmetic they overlap
-      read_w(cur);
-      __builtin_amdgcn_sched_barrier(0);     // scales and weight operands are read before the arithmetic
-      compute(cur, integral_constant<int, 0>{}, integral_constant<int, MT / 2>{});
-      store_b(nxt);
-      load_a(nxt, kb_next);
-      __builtin_amdgcn_sched_barrier(0);
-      compute(cur, integral_constant<int, MT / 2>{}, integral_constant<int, MT>{});
-      store_a(nxt);
-    } else {
-      load_b(kb_next);
-      load_a(nxt, kb_next);
-      __builtin_amdgcn_sched_barrier(0);
-      read_w(cur);
-      __builtin_amdgcn_sched_barrier(0);
-      compute(cur, integral_constant<int, 0>{}, integral_constant<int, MT>{});
-      store_b(nxt);
-      store_a(nxt);
-    }
+    read_w(cur);
+    __builtin_amdgcn_sched_barrier(0);       // the LDS reads above are issued before the next block's loads
+    dma_block(nxt, kb_next);
+    __builtin_amdgcn_sched_barrier(0);
+    compute(cur, integral_constant<int, 0>{}, integral_constant<int, MT>{});
+    __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0): this wave's part of the next block has landed in LDS
     __syncthreads();
   };
 
   // ---- pipeline: block i + 1 is in flight while block i is multiplied ----
-  load_b(kb0);
-  if constexpr (SPLIT) { store_b(0); }
-  load_a(0, kb0);
-  if constexpr (!SPLIT) { store_b(0); }
-  store_a(0);
+  dma_block(0, kb0);
+  __builtin_amdgcn_s_waitcnt(0x0F70);
   __syncthreads();
   for (int it = 0; it < nkb; it += 2) {
     stage(0, kb0 + (it + 1 < nkb ? it + 1 : nkb - 1));      // past the end: a valid block, never consumed
@@ -323,10 +286,10 @@ fp8_split_reduce_kernel(const f32x4* __restrict__ planes, int k_splits, long lon
   }
 }
 
-template <int WM, int WN, int MT, int NT, int NTL>
+template <int WM, int WN, int MT, int NT>
 static int launch_one(const GemmParams& p, hipStream_t stream) {
   using G = Geom<WM, WN, MT, NT>;
-  auto kern = fp8_blockwise_gemm_kernel<WM, WN, MT, NT, NTL>;
+  auto kern = fp8_blockwise_gemm_kernel<WM, WN, MT, NT>;
   if (G::LDS > 64 * 1024) {
     // raise the dynamic LDS limit of this kernel once per device
     constexpr int kMaxDev = 64;
@@ -348,11 +311,12 @@ static int launch_one(const GemmParams& p, hipStream_t stream) {
 
 // Tiles.  bm = tokens per workgroup in {16, 32, 64, 128, 256}, bn = features per workgroup in
 // {64, 128, 256}; 256 x 256 runs eight waves (2 x 4), everything else four (1 x 4).
-// ntl: non-temporal weight loads.  Returns a hipError_t, or -1 for an unknown tile.
-int launch_fp8_gemm(const GemmParams& p, int bm, int bn, int ntl, hipStream_t stream) {
+// Returns a hipError_t, or -1 for an unknown tile.  (The non-temporal cache policy on the
+// direct-to-LDS weight loads measured 18 % slower on streaming shapes and is not used.)
+int launch_fp8_gemm(const GemmParams& p, int bm, int bn, hipStream_t stream) {
 #define FP8_TILE(BMv, BNv, WMv, WNv, MTv, NTv)                                        \
   if (bm == BMv && bn == BNv)                                                         \
-    return ntl ? launch_one<WMv, WNv, MTv, NTv, 1>(p, stream) : launch_one<WMv, WNv, MTv, NTv, 0>(p, stream);
+    return launch_one<WMv, WNv, MTv, NTv>(p, stream);
   FP8_TILE(16, 64, 1, 4, 1, 1)   FP8_TILE(16, 128, 1, 4, 1, 2)   FP8_TILE(16, 256, 1, 4, 1, 4)
   FP8_TILE(32, 64, 1, 4, 2, 1)   FP8_TILE(32, 128, 1, 4, 2, 2)   FP8_TILE(32, 256, 1, 4, 2, 4)
   FP8_TILE(64, 64, 1, 4, 4, 1)   FP8_TILE(64, 128, 1, 4, 4, 2)   FP8_TILE(64, 256, 1, 4, 4, 4)

@@ -19,10 +19,10 @@ struct GemmParams {
 };
 
 // bm = tokens per workgroup in {16, 32, 64, 128, 256}, bn = features per workgroup in {64, 128, 256}
-// (256 x 256 and bm <= 128 with any bn), ntl: non-temporal weight loads.  A and B are addressed with
+// (256 x 256 and bm <= 128 with any bn).  A and B are addressed with
 // 32-bit byte offsets: M * K and N * K must be below 2^32.  Returns a hipError_t, or -1 for an
 // unknown tile.
-int launch_fp8_gemm(const GemmParams& p, int bm, int bn, int ntl, hipStream_t stream);
+int launch_fp8_gemm(const GemmParams& p, int bm, int bn, hipStream_t stream);
 int launch_fp8_split_reduce(const float* planes, int k_splits, long long mn, void* C, int out_bf16,
                             hipStream_t stream);
 
