@@ -48,7 +48,7 @@ int fp8_blockwise_gemm(const uint8_t* A, const float* a_scale, const uint8_t* B,
 
 /*
  * Tuning hook (thread-local, not part of the operator): force the tile (mt in {1,2,4,8,16} = rows
- * of A per workgroup / 16, nt in {1,2,4} = rows of B per workgroup / 64; mt = 16 only with nt = 4)
+ * of A per workgroup / 16, nt in {1,2,4} = rows of B per workgroup / 64; mt = 16 not with nt = 1)
  * and the number of
  * reduction splits, and group_m = how many row blocks form a group in the order tiles are handed
  * to the XCDs (L2 reuse); zeros restore the automatic choice.  A forced plan that does not fit the

@@ -294,17 +294,20 @@ struct Fp8Plan { int bm, bn, splits, kb_per_split; };
 static bool fp8_plan(int M, int N, int K, Fp8Plan& pl) {
   const int KB = K / 128;
   int bm = M <= 16 ? 16 : M <= 32 ? 32 : M <= 64 ? 64 : 128;
-  if (g_fp8_mt) bm = 16 * g_fp8_mt;
+  // 128 features per workgroup measured fastest at every token-tile height up to 128 (two or
+  // more workgroups per CU; 256 wide costs occupancy, 64 wide LDS traffic per matrix
+  // instruction).  Large problems take the 256 x 256 eight-wave tile (fewest LDS bytes per
+  // matrix instruction: 1.65-1.8 against 1.4-1.5 PFLOP/s) when it still yields two workgroups per CU.
+  int bn = 128;
+  if (M > 128 && N % 256 == 0 && (long long)((M + 255) / 256) * (N / 256) >= 512) { bm = 256; bn = 256; }
+  if (g_fp8_mt) { bm = 16 * g_fp8_mt; bn = 128; }
   if (bm != 16 && bm != 32 && bm != 64 && bm != 128 && bm != 256) return false;
   const long long m_blocks = (M + bm - 1) / bm;
-  // 128 features per workgroup measured fastest at every token-tile height (two or more
-  // workgroups per CU; 256 wide costs occupancy, 64 wide LDS traffic per matrix instruction)
-  int bn = 128;
   while (bn > 64 && N % bn != 0) bn >>= 1;
   // small problems: narrower feature tiles first (more workgroups streaming weights) ...
   while (bn > 64 && m_blocks * (N / bn) < 256) bn >>= 1;
   if (g_fp8_nt) bn = 64 * g_fp8_nt;
-  if ((bn != 64 && bn != 128 && bn != 256) || N % bn != 0 || (bm == 256 && bn != 256)) return false;
+  if ((bn != 64 && bn != 128 && bn != 256) || N % bn != 0 || (bm == 256 && bn == 64)) return false;
   const long long wgs = m_blocks * (N / bn);
   // ... then a split of the reduction, each split at least four blocks long
   int splits = 1;
@@ -650,7 +653,7 @@ int fp8_blockwise_gemm(const uint8_t* A, const float* a_scale, const uint8_t* B,
   p.A = A; p.a_scale = a_scale; p.B = B; p.b_scale = b_scale;
   p.M = M; p.N = N; p.K = K;
   p.k_splits = pl.splits; p.kb_per_split = pl.kb_per_split; p.out_bf16 = out_dtype;
-  p.group_m = g_fp8_group_m ? g_fp8_group_m : 8;
+  p.group_m = g_fp8_group_m ? g_fp8_group_m : 8;     // row blocks per tile group (4 ... 16 measured alike)
   if (pl.splits > 1) {
     const size_t need = round_up((size_t)pl.splits * (size_t)M * (size_t)N * sizeof(float), 256);
     if (!workspace || workspace_bytes < need)

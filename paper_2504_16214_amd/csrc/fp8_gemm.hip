@@ -53,23 +53,26 @@ __device__ __forceinline__ uint32_t pack2(float lo, float hi) {
 
 // Workgroup = WM x WN waves; wave (wm, wn) owns tokens [16 MT wm, 16 MT (wm + 1)) and features
 // [16 NT wn, 16 NT (wn + 1)) of the BM x BN tile (BM = 16 MT WM, BN = 16 NT WN).
-template <int WM, int WN, int MT, int NT>
+template <int WM, int WN, int MT, int NT, int NS>
 struct Geom {
   static constexpr int T = 64 * WM * WN;                 // threads
   static constexpr int BM = 16 * MT * WM, BN = 16 * NT * WN;
   static constexpr int RPP = T / 8;                      // tile rows one pass of the workgroup loads
   static constexpr int AROWS = (BM + RPP - 1) / RPP * RPP;   // activation rows held in LDS (padded to whole passes)
   static constexpr int CHA = AROWS / RPP, CHB = BN / RPP;    // 16-byte chunks per thread and block
-  static constexpr int SCALES = BM < 64 ? 64 : BM;          // activation-scale slots (a whole wave's worth at least)
+  static constexpr int SCALES = T;                          // activation-scale slots: one per thread (slots past BM repeat the last row)
   static constexpr int STAGE = (AROWS + BN) * 128 + SCALES * 4;  // bytes: A rows, B rows, activation scales
-  static constexpr int LDS = 2 * STAGE;
+  static constexpr int LDS = NS * STAGE;                    // NS buffers: NS - 1 blocks in flight
+  static constexpr int LPB = CHA + CHB + 1;                 // vector-memory loads per wave and block
+  static_assert(BM <= T, "one activation scale per thread");
+  static_assert(LPB * (NS - 2) <= 63, "vmcnt is six bits");
   static_assert(BN % RPP == 0, "feature tile must be whole passes");
 };
 
-template <int WM, int WN, int MT, int NT>
+template <int WM, int WN, int MT, int NT, int NS>
 __global__ void __launch_bounds__(64 * WM * WN, (WM * WN == 4 && MT * NT <= 16 ? 2 : 1))
 fp8_blockwise_gemm_kernel(const GemmParams p) {
-  using G = Geom<WM, WN, MT, NT>;
+  using G = Geom<WM, WN, MT, NT, NS>;
   constexpr int T = G::T, BM = G::BM, BN = G::BN, RPP = G::RPP, AROWS = G::AROWS, CHA = G::CHA, CHB = G::CHB;
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
 
@@ -142,7 +145,7 @@ fp8_blockwise_gemm_kernel(const GemmParams p) {
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  float sb[2];                // weight-block scale of the block in each LDS buffer
+  float sb[NS];               // weight-block scale of the block in each LDS buffer
 
   typedef const __attribute__((address_space(1))) void* gptr_t;
   typedef __attribute__((address_space(3))) void* lptr_t;
@@ -156,9 +159,8 @@ fp8_blockwise_gemm_kernel(const GemmParams p) {
 #pragma unroll
     for (int i = 0; i < CHA; ++i)
       __builtin_amdgcn_global_load_lds((gptr_t)(ab + aoff[i]), (lptr_t)(st + RPP * i * 128), 16, 0, 0);
-    if (64 * wave < G::SCALES)                                         // wave-uniform
-      __builtin_amdgcn_global_load_lds((gptr_t)(assrc + kb),
-                                       (lptr_t)(lds + buf * G::STAGE + (AROWS + BN) * 128 + 256 * wave), 4, 0, 0);
+    __builtin_amdgcn_global_load_lds((gptr_t)(assrc + kb),
+                                     (lptr_t)(lds + buf * G::STAGE + (AROWS + BN) * 128 + 256 * wave), 4, 0, 0);
     sb[buf] = bssrc[kb];
   };
   auto read_op = [&](const unsigned char* st, int off) __attribute__((always_inline)) -> i32x8 {
@@ -220,24 +222,35 @@ fp8_blockwise_gemm_kernel(const GemmParams p) {
     for (int nt = 0; nt < NT; ++nt) acc[MHI - 1][nt] += pprev[nt] * sp[MHI - 1];
   };
   using std::integral_constant;
-  auto stage = [&](int cur, int kb_next) __attribute__((always_inline)) {
-    const int nxt = cur ^ 1;
+  // vmcnt(n): at most n of this wave's vector-memory loads still in flight (six bits, split 4 + 2)
+  constexpr int kLanded = ((G::LPB * (NS - 2)) & 15) | (((G::LPB * (NS - 2)) >> 4) << 14) | 0x0F70;
+  // One block.  Buffer cur is multiplied; the block NS - 1 ahead is sent to the buffer that was
+  // multiplied last (every wave is past the barrier that followed it); before the closing barrier
+  // each wave waits until its own part of the NEXT block has landed.
+  auto stage = [&](auto cur_c, int kb_far) __attribute__((always_inline)) {
+    constexpr int cur = decltype(cur_c)::value;
     read_w(cur);
-    __builtin_amdgcn_sched_barrier(0);       // the LDS reads above are issued before the next block's loads
-    dma_block(nxt, kb_next);
+    __builtin_amdgcn_sched_barrier(0);       // the LDS reads above are issued before the far block's loads
+    dma_block((cur + NS - 1) % NS, kb_far);
     __builtin_amdgcn_sched_barrier(0);
     compute(cur, integral_constant<int, 0>{}, integral_constant<int, MT>{});
-    __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0): this wave's part of the next block has landed in LDS
+    __builtin_amdgcn_s_waitcnt(kLanded);
     __syncthreads();
   };
 
-  // ---- pipeline: block i + 1 is in flight while block i is multiplied ----
-  dma_block(0, kb0);
-  __builtin_amdgcn_s_waitcnt(0x0F70);
+  // ---- pipeline: NS - 1 blocks in flight while one is multiplied ----
+  // (block indices past the end are clamped: a valid block is loaded and never consumed, so every
+  // wave issues the same number of loads per stage and the vmcnt arithmetic holds)
+  auto clampk = [&](int i) __attribute__((always_inline)) { return kb0 + (i < nkb ? i : nkb - 1); };
+#pragma unroll
+  for (int s = 0; s < NS - 1; ++s) dma_block(s, clampk(s));
+  __builtin_amdgcn_s_waitcnt(kLanded);
   __syncthreads();
-  for (int it = 0; it < nkb; it += 2) {
-    stage(0, kb0 + (it + 1 < nkb ? it + 1 : nkb - 1));      // past the end: a valid block, never consumed
-    if (it + 1 < nkb) stage(1, kb0 + (it + 2 < nkb ? it + 2 : nkb - 1));
+  for (int it = 0; it < nkb; it += NS) {
+    stage(integral_constant<int, 0>{}, clampk(it + NS - 1));
+    if constexpr (NS >= 2) { if (it + 1 < nkb) stage(integral_constant<int, 1>{}, clampk(it + NS)); }
+    if constexpr (NS >= 3) { if (it + 2 < nkb) stage(integral_constant<int, 2>{}, clampk(it + NS + 1)); }
+    if constexpr (NS >= 4) { if (it + 3 < nkb) stage(integral_constant<int, 3>{}, clampk(it + NS + 2)); }
   }
 
   // ---- epilogue: the lane's token, 4 NT consecutive features ----
@@ -286,10 +299,10 @@ fp8_split_reduce_kernel(const f32x4* __restrict__ planes, int k_splits, long lon
   }
 }
 
-template <int WM, int WN, int MT, int NT>
+template <int WM, int WN, int MT, int NT, int NS>
 static int launch_one(const GemmParams& p, hipStream_t stream) {
-  using G = Geom<WM, WN, MT, NT>;
-  auto kern = fp8_blockwise_gemm_kernel<WM, WN, MT, NT>;
+  using G = Geom<WM, WN, MT, NT, NS>;
+  auto kern = fp8_blockwise_gemm_kernel<WM, WN, MT, NT, NS>;
   if (G::LDS > 64 * 1024) {
     // raise the dynamic LDS limit of this kernel once per device
     constexpr int kMaxDev = 64;
@@ -310,18 +323,19 @@ static int launch_one(const GemmParams& p, hipStream_t stream) {
 }
 
 // Tiles.  bm = tokens per workgroup in {16, 32, 64, 128, 256}, bn = features per workgroup in
-// {64, 128, 256}; 256 x 256 runs eight waves (2 x 4), everything else four (1 x 4).
-// Returns a hipError_t, or -1 for an unknown tile.  (The non-temporal cache policy on the
-// direct-to-LDS weight loads measured 18 % slower on streaming shapes and is not used.)
+// {64, 128, 256}; bm = 256 runs eight waves (2 x 4), everything else four (1 x 4).  Returns a
+// hipError_t, or -1 for an unknown tile.  Measured and not compiled in: three LDS buffers (two
+// blocks in flight: no gain on the small tiles, -30 % on 128 x 128 where it costs the second
+// workgroup per CU) and the non-temporal cache policy on the weight loads (-18 % on streaming
+// shapes).
 int launch_fp8_gemm(const GemmParams& p, int bm, int bn, hipStream_t stream) {
-#define FP8_TILE(BMv, BNv, WMv, WNv, MTv, NTv)                                        \
-  if (bm == BMv && bn == BNv)                                                         \
-    return launch_one<WMv, WNv, MTv, NTv>(p, stream);
-  FP8_TILE(16, 64, 1, 4, 1, 1)   FP8_TILE(16, 128, 1, 4, 1, 2)   FP8_TILE(16, 256, 1, 4, 1, 4)
-  FP8_TILE(32, 64, 1, 4, 2, 1)   FP8_TILE(32, 128, 1, 4, 2, 2)   FP8_TILE(32, 256, 1, 4, 2, 4)
-  FP8_TILE(64, 64, 1, 4, 4, 1)   FP8_TILE(64, 128, 1, 4, 4, 2)   FP8_TILE(64, 256, 1, 4, 4, 4)
-  FP8_TILE(128, 64, 1, 4, 8, 1)  FP8_TILE(128, 128, 1, 4, 8, 2)  FP8_TILE(128, 256, 1, 4, 8, 4)
-  FP8_TILE(256, 256, 2, 4, 8, 4)
+#define FP8_TILE(BMv, BNv, WMv, WNv, MTv, NTv, NSv)                                   \
+  if (bm == BMv && bn == BNv) return launch_one<WMv, WNv, MTv, NTv, NSv>(p, stream);
+  FP8_TILE(16, 64, 1, 4, 1, 1, 2)   FP8_TILE(16, 128, 1, 4, 1, 2, 2)   FP8_TILE(16, 256, 1, 4, 1, 4, 2)
+  FP8_TILE(32, 64, 1, 4, 2, 1, 2)   FP8_TILE(32, 128, 1, 4, 2, 2, 2)   FP8_TILE(32, 256, 1, 4, 2, 4, 2)
+  FP8_TILE(64, 64, 1, 4, 4, 1, 2)   FP8_TILE(64, 128, 1, 4, 4, 2, 2)   FP8_TILE(64, 256, 1, 4, 4, 4, 2)
+  FP8_TILE(128, 64, 1, 4, 8, 1, 2)  FP8_TILE(128, 128, 1, 4, 8, 2, 2)  FP8_TILE(128, 256, 1, 4, 8, 4, 2)
+  FP8_TILE(256, 256, 2, 4, 8, 4, 2) FP8_TILE(256, 128, 2, 4, 8, 2, 2)
 #undef FP8_TILE
   return -1;
 }

@@ -19,7 +19,8 @@ struct GemmParams {
 };
 
 // bm = tokens per workgroup in {16, 32, 64, 128, 256}, bn = features per workgroup in {64, 128, 256}
-// (256 x 256 and bm <= 128 with any bn).  A and B are addressed with
+// (bm = 256 with bn in {128, 256}, bm <= 128 with any bn).
+// A and B are addressed with
 // 32-bit byte offsets: M * K and N * K must be below 2^32.  Returns a hipError_t, or -1 for an
 // unknown tile.
 int launch_fp8_gemm(const GemmParams& p, int bm, int bn, hipStream_t stream);

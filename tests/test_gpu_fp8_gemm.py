@@ -72,7 +72,7 @@ def check(inp, dtype=torch.bfloat16, what=""):
 
 
 @pytest.mark.parametrize("mt,nt,splits", [(mt, nt, sp) for mt in (1, 2, 4, 8) for nt in (1, 2, 4) for sp in (1, 3)]
-                         + [(16, 4, 1), (16, 4, 3)])
+                         + [(16, 4, 1), (16, 4, 3), (16, 2, 1), (16, 2, 2)])
 def test_every_tile_variant_matches_oracle(mt, nt, splits):
     """Each compiled tile, with and without a split reduction, on a shape with two row blocks (the
     second one ragged), two feature blocks and an odd number of reduction blocks."""
