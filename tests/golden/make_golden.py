@@ -1,4 +1,5 @@
-"""Writes tests/golden/small_layer_<dtype>.json from the CPU oracle alone.
+"""Writes tests/golden/small_layer_<dtype>.json and tests/golden/small_fp8_gemm.json from the CPU
+oracles alone.
 
 The paper (Section VII-B, "Mixed-type MoE") prints no worked numeric example
 for this operator, so these fixtures are not paper values: they freeze what the
@@ -16,6 +17,8 @@ ROOT = os.path.dirname(os.path.dirname(os.path.dirname(os.path.abspath(__file__)
 sys.path.insert(0, ROOT)
 from moe_workloads import MoEConfig, make_inputs  # noqa: E402
 from oracle import moe_oracle as O  # noqa: E402
+from oracle import fp8_oracle as F  # noqa: E402
+from moe_workloads.fp8 import Fp8GemmConfig, make_fp8_inputs  # noqa: E402
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 
@@ -40,6 +43,21 @@ def main():
         with open(os.path.join(HERE, f"small_layer_{dt}.json"), "w") as f:
             json.dump(doc, f, separators=(",", ":"))
             f.write("\n")
+    # blockwise-scaled FP8 GEMM (the paper names the operator, Table II, and prints no example)
+    cfg = Fp8GemmConfig("golden_fp8", M=5, N=128, K=256, seed=4321)
+    inp = make_fp8_inputs(cfg)
+    out = F.blockwise_gemm(inp.a_codes, inp.a_scale, inp.b_codes, inp.b_scale, "bf16")
+    doc = {
+        "source": "oracle/fp8_oracle.py via tests/golden/make_golden.py (not a paper value)",
+        "config": dict(M=cfg.M, N=cfg.N, K=cfg.K, seed=cfg.seed, out="bf16"),
+        "a_codes_row0": inp.a_codes[0].tolist(),
+        "a_scale": [[float(v).hex() for v in r] for r in inp.a_scale],
+        "b_scale": [[float(v).hex() for v in r] for r in inp.b_scale],
+        "out_bits": O.encode_bits(out, "bf16").tolist(),
+    }
+    with open(os.path.join(HERE, "small_fp8_gemm.json"), "w") as f:
+        json.dump(doc, f, separators=(",", ":"))
+        f.write("\n")
 
 
 if __name__ == "__main__":

@@ -97,6 +97,39 @@ def test_validation_before_launch_returns_status(binding):
     assert lib.moe_set_tile_override(0, 0) == 0
 
 
+def test_fp8_gemm_host_logic(binding):
+    """Workspace sizing and every check that happens before a launch (no kernel runs: the dummy
+    pointers are never dereferenced)."""
+    lib = binding.load_library()
+    wsb = binding.fp8_blockwise_gemm_workspace_bytes
+    assert wsb(4096, 51200, 5120) == 0                        # enough workgroups: no split reduction
+    assert wsb(32, 51200, 5120) == 0
+    need = wsb(16, 5120, 25600)                               # few workgroups, long reduction: float32 planes
+    plane = 16 * 5120 * 4
+    assert need % plane == 0 and 2 <= need // plane <= 16
+    assert wsb(16, 5120, 200) == 0 and wsb(16, 100, 256) == 0 and wsb(0, 128, 256) == 0
+    p = 0x10000                                               # aligned, never touched
+    call = lib.fp8_blockwise_gemm
+    assert call(p, p, p, p, 2 * p, 4, 128, 200, 1, None, 0, None) == 2          # K % 128
+    assert call(p, p, p, p, 2 * p, 4, 100, 256, 1, None, 0, None) == 2          # N % 64
+    assert call(p, p, p, p, 2 * p, 4, 128, 256, 3, None, 0, None) == 1          # output type
+    assert call(None, p, p, p, 2 * p, 4, 128, 256, 1, None, 0, None) == 1       # null pointer
+    assert call(p + 4, p, p, p, 2 * p, 4, 128, 256, 1, None, 0, None) == 1      # alignment
+    assert call(p, p, p, p, p, 4, 128, 256, 1, None, 0, None) == 1              # C aliases A
+    assert call(None, None, None, None, None, 0, 128, 256, 1, None, 0, None) == 0   # M == 0: no-op
+    assert call(p, p, p, p, 2 * p, 70000, 64, 65536, 1, None, 0, None) == 2     # M * K >= 2^32
+    assert b"2^32" in lib.moe_last_error()
+    assert call(p, p, p, p, 2 * p, 16, 5120, 25600, 1, None, 0, None) == 3      # split reduction without workspace
+    assert lib.fp8_set_plan_override(3, 0, 0, 0) == 0
+    try:
+        assert call(p, p, p, p, 2 * p, 4, 128, 256, 1, None, 0, None) == 2      # no 48-row tile
+        assert wsb(4, 128, 256) == 0
+    finally:
+        assert lib.fp8_set_plan_override(0, 0, 0, 0) == 0
+    assert lib.fp8_set_plan_override(-1, 0, 0, 0) == 1
+    assert lib.fp8_probe_mfma(None, 4, None) == 1
+
+
 def test_product_path_does_not_import_the_oracle():
     pkg = os.path.join(ROOT, "paper_2504_16214_amd")
     for dirpath, _, files in os.walk(pkg):
@@ -106,3 +139,5 @@ def test_product_path_does_not_import_the_oracle():
                 assert "oracle" not in text.lower().replace("no cpu fallback", ""), f
     assert "oracle" not in open(os.path.join(ROOT, "moe_workloads", "__init__.py")).read().replace(
         "CPU oracle and the HIP path alike", "")
+    assert "oracle" not in open(os.path.join(ROOT, "moe_workloads", "fp8.py")).read().replace(
+        "The oracle and the HIP path read", "")

@@ -6,6 +6,8 @@ linearity; mutation checks show the brute force catches a transposed scale index
 and a wrong exponent bias."""
 from __future__ import annotations
 
+import json
+import os
 from fractions import Fraction
 
 import numpy as np
@@ -168,3 +170,17 @@ def test_generator_shapes_and_range():
     assert np.all(np.abs(A).reshape(7, 2, 128).max(axis=2) == 448.0)
     again = make_fp8_inputs(Fp8GemmConfig("g", M=7, N=130, K=256, seed=3))
     assert np.array_equal(again.b_codes, inp.b_codes) and np.array_equal(again.a_scale, inp.a_scale)
+
+
+def test_oracle_reproduces_golden_fixture():
+    """Regression guard: the frozen output of the pinned oracle on a small seeded case (also the
+    generator's codes and scales, so a change of the input recipe shows up here)."""
+    with open(os.path.join(os.path.dirname(__file__), "golden", "small_fp8_gemm.json")) as f:
+        doc = json.load(f)
+    c = doc["config"]
+    inp = make_fp8_inputs(Fp8GemmConfig("golden_fp8", M=c["M"], N=c["N"], K=c["K"], seed=c["seed"]))
+    assert inp.a_codes[0].tolist() == doc["a_codes_row0"]
+    assert [[float(v).hex() for v in r] for r in inp.a_scale] == doc["a_scale"]
+    assert [[float(v).hex() for v in r] for r in inp.b_scale] == doc["b_scale"]
+    out = F.blockwise_gemm(inp.a_codes, inp.a_scale, inp.b_codes, inp.b_scale, "bf16")
+    assert O.encode_bits(out, "bf16").tolist() == doc["out_bits"]

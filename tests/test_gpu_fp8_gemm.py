@@ -12,6 +12,8 @@ Bound, per output element (derived from the arithmetic, not tuned to pass):
 For the benchmark's inputs the second term is about half a bf16 ulp of a typical output."""
 from __future__ import annotations
 
+import json
+import os
 import sys
 
 import numpy as np
@@ -20,6 +22,7 @@ import torch
 
 from moe_workloads.fp8 import FP8_CONFIGS, Fp8GemmConfig, make_fp8_inputs
 from oracle import fp8_oracle as F
+from oracle import moe_oracle as O
 
 pytestmark = pytest.mark.gpu
 
@@ -138,6 +141,18 @@ def test_benchmark_shapes_sampled(name):
     worst = float((np.abs(sub - want) / bound).max())
     say(f"{name}: max err / bound = {worst:.3f} on {sub.size} sampled outputs")
     assert worst <= 1.0
+
+
+def test_matches_golden_fixture():
+    with open(os.path.join(os.path.dirname(__file__), "golden", "small_fp8_gemm.json")) as f:
+        doc = json.load(f)
+    c = doc["config"]
+    say(f"fp8 gemm golden M={c['M']} N={c['N']} K={c['K']}")
+    inp = make_fp8_inputs(Fp8GemmConfig("golden_fp8", M=c["M"], N=c["N"], K=c["K"], seed=c["seed"]))
+    got = run_gemm(inp.a_codes, inp.a_scale, inp.b_codes, inp.b_scale)
+    want = O.decode_bits(np.array(doc["out_bits"], np.uint16), "bf16")
+    bound = error_bound(want, inp.a_codes, inp.a_scale, inp.b_codes, inp.b_scale)
+    assert float((np.abs(got - want) / bound).max()) <= 1.0
 
 
 def test_empty_and_error_paths():
