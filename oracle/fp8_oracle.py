@@ -27,7 +27,8 @@ walk tiny cases.
 Parity pins (tests/test_fp8_oracle_pins.py): the 256-entry decode table against a library's e4m3
 cast and hand values; an exact-rational brute force on tiny shapes; unit scales => the plain
 product of the decoded matrices; a closed form; linearity in one block scale (only the outputs
-of that block move, by exactly that block's partial product).
+of that block move, by exactly that block's partial product); the grouped form against the
+brute force per slot, its one-expert case (= the dense product) and the row_div gather.
 """
 from __future__ import annotations
 
@@ -71,3 +72,31 @@ def blockwise_gemm(a_codes, a_scale, b_codes, b_scale, out_dt="bf16", block: int
         col_scale = np.repeat(sb[:, kb], block)[:N]                   # b_scale[n // block, kb]
         C += sa[:, kb][:, None] * col_scale[None, :] * part
     return C if out_dt is None else rnd(C, out_dt)
+
+
+def grouped_blockwise_gemm(a_codes, a_scale, row_div: int, b_codes, b_scale, slot_expert,
+                           out_dt="bf16", block: int = BLOCK):
+    """The same product with one weight matrix per expert (the FP8 form of the paper's grouped
+    mixture-of-experts GEMM, Section VII-B: one launch over all experts): slot s multiplies row
+    s // row_div of A with the matrix of expert slot_expert[s],
+
+        C[s, :] = blockwise_gemm(A[s // row_div], a_scale[s // row_div], B[e], b_scale[e]),  e = slot_expert[s].
+
+    a_codes [R, K], a_scale [R, K/block], b_codes [E, N, K], b_scale [E, ceil(N/block), K/block],
+    slot_expert [S] (ids outside [0, E) are ignored).  Returns (C [S, N] float64 values rounded to
+    out_dt, rows of ignored slots zero; valid [S] bool)."""
+    a_codes = np.asarray(a_codes)
+    b_codes = np.asarray(b_codes)
+    slot_expert = np.asarray(slot_expert)
+    E, N, K = b_codes.shape
+    S = slot_expert.shape[0]
+    C = np.zeros((S, N), dtype=np.float64)
+    valid = (slot_expert >= 0) & (slot_expert < E)
+    for e in range(E):
+        slots = np.nonzero(slot_expert == e)[0]
+        if slots.size == 0:
+            continue
+        rows = slots // row_div
+        C[slots] = blockwise_gemm(a_codes[rows], np.asarray(a_scale)[rows], b_codes[e], np.asarray(b_scale)[e],
+                                  out_dt, block)
+    return C, valid

@@ -160,6 +160,48 @@ def test_block_scale_linearity():
     assert np.all(np.delete(moved, m, axis=0) == 0) and np.any(moved[m] != 0)
 
 
+# ------------------------------------------------------------------ grouped (one matrix per expert)
+def test_grouped_against_brute_force_per_slot():
+    rng = np.random.default_rng(31)
+    E, N, K, block, R, row_div = 3, 6, 8, 4, 4, 2
+    a = valid_codes(rng, (R, K))
+    b = valid_codes(rng, (E, N, K))
+    sa = rng.uniform(0.5, 2.0, size=(R, K // block)).astype(np.float32)
+    sb = rng.uniform(0.5, 2.0, size=(E, -(-N // block), K // block)).astype(np.float32)
+    slot_expert = np.array([2, 0, 1, 7, 0, -1, 2, 2])                 # two ignored ids
+    C, valid = F.grouped_blockwise_gemm(a, sa, row_div, b, sb, slot_expert, out_dt=None, block=block)
+    assert valid.tolist() == [True, True, True, False, True, False, True, True]
+    for s_, e in enumerate(slot_expert):
+        if not valid[s_]:
+            assert np.all(C[s_] == 0)
+            continue
+        r = s_ // row_div
+        want = brute(a[r:r + 1], sa[r:r + 1], b[e], sb[e], block)
+        np.testing.assert_allclose(C[s_:s_ + 1], want, rtol=1e-13, atol=1e-9)
+
+
+def test_grouped_special_cases():
+    """One expert and row_div = 1 is the dense product; row_div = k equals the same call on A with
+    every row repeated k times; permuting the experts (and the ids alike) changes nothing."""
+    inp = make_fp8_inputs(Fp8GemmConfig("g1", M=6, N=128, K=256, seed=5))
+    dense = F.blockwise_gemm(inp.a_codes, inp.a_scale, inp.b_codes, inp.b_scale)
+    C, valid = F.grouped_blockwise_gemm(inp.a_codes, inp.a_scale, 1, inp.b_codes[None], inp.b_scale[None],
+                                        np.zeros(6, np.int32))
+    assert valid.all() and np.array_equal(C, dense)
+    rng = np.random.default_rng(6)
+    E = 3
+    b = np.stack([make_fp8_inputs(Fp8GemmConfig("g", M=1, N=128, K=256, seed=10 + e)).b_codes for e in range(E)])
+    sb = np.stack([make_fp8_inputs(Fp8GemmConfig("g", M=1, N=128, K=256, seed=10 + e)).b_scale for e in range(E)])
+    ids = rng.integers(0, E, size=12)
+    C2, _ = F.grouped_blockwise_gemm(inp.a_codes, inp.a_scale, 2, b, sb, ids)
+    C1, _ = F.grouped_blockwise_gemm(np.repeat(inp.a_codes, 2, axis=0), np.repeat(inp.a_scale, 2, axis=0), 1, b, sb, ids)
+    assert np.array_equal(C1, C2)
+    perm = np.array([2, 0, 1])                                         # new expert j is old expert perm[j]
+    inv = np.argsort(perm)
+    C3, _ = F.grouped_blockwise_gemm(inp.a_codes, inp.a_scale, 2, b[perm], sb[perm], inv[ids])
+    assert np.array_equal(C3, C2)
+
+
 def test_generator_shapes_and_range():
     inp = make_fp8_inputs(Fp8GemmConfig("g", M=7, N=130, K=256, seed=3))
     assert inp.a_codes.shape == (7, 256) and inp.a_scale.shape == (7, 2) and inp.a_scale.dtype == np.float32
