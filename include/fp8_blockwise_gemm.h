@@ -47,6 +47,27 @@ int fp8_blockwise_gemm(const uint8_t* A, const float* a_scale, const uint8_t* B,
                        void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Grouped form: one weight matrix per expert, one launch over all experts (the structure of the
+ * paper's mixture-of-experts kernel, Section VII-B, with the FP8 operands above):
+ *   C[s, :] = the blockwise-scaled product of row s / row_div of A with B[e_s]  for every
+ *   bucketed slot s, e_s being the expert whose segment of sorted_slot_ids contains s.
+ *   A [rows_A, K] e4m3, a_scale [rows_A, K/128] float32, rows_A >= ceil(num_slots / row_div);
+ *   B [E, N, K] e4m3, b_scale [E, ceil(N/128), K/128] float32;
+ *   sorted_slot_ids / block_expert_ids / num_padded: as produced by moe_align_by_expert
+ *   (include/moe_w4a16.h) with the same block_m, E and num_slots = T * topk;
+ *   C [num_slots, N] 16-bit, written at row = slot id; rows of slots that were not bucketed are
+ *   left untouched.
+ * Same arithmetic, alignment and size rules as fp8_blockwise_gemm; block_m in
+ * {16, 32, 64, 128, 256} is the token tile of the kernel (N % 128 == 0 at 256); the reduction is
+ * never split, so no workspace.  num_slots == 0 is a no-op.
+ */
+int fp8_moe_grouped_gemm(const uint8_t* A, const float* a_scale, int row_div,
+                         const uint8_t* B, const float* b_scale,
+                         const int32_t* sorted_slot_ids, const int32_t* block_expert_ids,
+                         const int32_t* num_padded, int num_slots, int E, int N, int K, int block_m,
+                         int out_dtype, void* C, void* stream);
+
+/*
  * Tuning hook (thread-local, not part of the operator): force the tile (mt in {1,2,4,8,16} = rows
  * of A per workgroup / 16, nt in {1,2,4} = rows of B per workgroup / 64; mt = 16 not with nt = 1)
  * and the number of

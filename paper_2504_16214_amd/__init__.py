@@ -11,6 +11,7 @@ from .binding import (  # noqa: F401
     moe_w4a16_dense_gemm, moe_route_topk, moe_probe_stream_read, moe_probe_mfma,
     moe_w4a16_routed_layer_workspace_bytes, moe_w4a16_routed_layer,
     moe_repack_qweight, moe_w4a16_layer_prepacked, moe_import_awq,
-    fp8_blockwise_gemm_workspace_bytes, fp8_blockwise_gemm, fp8_set_plan_override, fp8_probe_mfma,
+    fp8_blockwise_gemm_workspace_bytes, fp8_blockwise_gemm, fp8_moe_grouped_gemm, fp8_set_plan_override,
+    fp8_probe_mfma,
     moe_set_tile_override, moe_set_scale_path, moe_set_tiles_per_workgroup, moe_set_reduction_splits, moe_set_stage_events, moe_last_error,
 )

@@ -20,7 +20,8 @@ EXPORTS = [
     "moe_w4a16_dense_gemm", "moe_route_topk", "moe_probe_stream_read", "moe_probe_mfma",
     "moe_w4a16_routed_layer_workspace_bytes", "moe_w4a16_routed_layer",
     "moe_repack_qweight", "moe_w4a16_layer_prepacked", "moe_import_awq",
-    "fp8_blockwise_gemm_workspace_bytes", "fp8_blockwise_gemm", "fp8_set_plan_override", "fp8_probe_mfma",
+    "fp8_blockwise_gemm_workspace_bytes", "fp8_blockwise_gemm", "fp8_moe_grouped_gemm", "fp8_set_plan_override",
+    "fp8_probe_mfma",
 ]
 
 
@@ -71,6 +72,8 @@ def load_library() -> ctypes.CDLL:
     lib.fp8_blockwise_gemm_workspace_bytes.argtypes = [i32, i32, i32]
     lib.fp8_blockwise_gemm.restype = i32
     lib.fp8_blockwise_gemm.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, vp, sz, vp]
+    lib.fp8_moe_grouped_gemm.restype = i32
+    lib.fp8_moe_grouped_gemm.argtypes = [vp, vp, i32, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, vp, vp]
     lib.fp8_set_plan_override.restype = i32
     lib.fp8_set_plan_override.argtypes = [i32, i32, i32, i32]
     lib.fp8_probe_mfma.restype = i32
@@ -268,6 +271,18 @@ def fp8_blockwise_gemm(A, a_scale, B, b_scale, C, workspace=None, stream=None) -
     _check(load_library().fp8_blockwise_gemm(_ptr(A), _ptr(a_scale), _ptr(B), _ptr(b_scale), _ptr(C), M, N, K,
                                              out_dtype, None if workspace is None else _ptr(workspace), wb,
                                              _stream(stream)))
+
+
+def fp8_moe_grouped_gemm(A, a_scale, row_div: int, B, b_scale, sorted_slot_ids, block_expert_ids, num_padded,
+                         num_slots: int, block_m: int, C, stream=None) -> None:
+    """A [rows_A, K] uint8, a_scale [rows_A, K/128] float32, B [E, N, K] uint8, b_scale [E, ceil(N/128), K/128],
+    slot tables from moe_align_by_expert, C [num_slots, N] float16 / bfloat16 (preallocated)."""
+    import torch
+    E, N, K = B.shape
+    out_dtype = 1 if C.dtype == torch.bfloat16 else 0
+    _check(load_library().fp8_moe_grouped_gemm(_ptr(A), _ptr(a_scale), row_div, _ptr(B), _ptr(b_scale),
+                                               _ptr(sorted_slot_ids), _ptr(block_expert_ids), _ptr(num_padded),
+                                               num_slots, E, N, K, block_m, out_dtype, _ptr(C), _stream(stream)))
 
 
 def fp8_set_plan_override(mt: int, nt: int, k_splits: int, group_m: int = 0) -> None:

@@ -649,7 +649,7 @@ int fp8_blockwise_gemm(const uint8_t* A, const float* a_scale, const uint8_t* B,
   const long long m_blocks = (M + pl.bm - 1) / pl.bm;
   const long long grid = m_blocks * (N / pl.bn) * pl.splits;
   if (grid > 0x7fffffffLL) return fail(MOE_UNSUPPORTED_SHAPE, "too many workgroups");
-  fp8::GemmParams p;
+  fp8::GemmParams p = {};
   p.A = A; p.a_scale = a_scale; p.B = B; p.b_scale = b_scale;
   p.M = M; p.N = N; p.K = K;
   p.k_splits = pl.splits; p.kb_per_split = pl.kb_per_split; p.out_bf16 = out_dtype;
@@ -671,6 +671,46 @@ int fp8_blockwise_gemm(const uint8_t* A, const float* a_scale, const uint8_t* B,
                                        (hipStream_t)stream);
     if (err != 0) return hip_fail(err, "FP8 split reduction launch");
   }
+  return MOE_OK;
+}
+
+int fp8_moe_grouped_gemm(const uint8_t* A, const float* a_scale, int row_div, const uint8_t* B,
+                         const float* b_scale, const int32_t* sorted_slot_ids, const int32_t* block_expert_ids,
+                         const int32_t* num_padded, int num_slots, int E, int N, int K, int block_m, int out_dtype,
+                         void* C, void* stream) {
+  if (num_slots < 0 || E < 1 || E > 1024 || N < 1 || K < 1 || row_div < 1)
+    return fail(MOE_INVALID_ARGUMENT, "need num_slots >= 0, 1 <= E <= 1024, N >= 1, K >= 1, row_div >= 1");
+  if (out_dtype != 0 && out_dtype != 1) return fail(MOE_INVALID_ARGUMENT, "out_dtype must be 0 (fp16) or 1 (bf16)");
+  if (!valid_block_m(block_m)) return fail(MOE_INVALID_ARGUMENT, "block_m must be 16, 32, 64, 128 or 256");
+  if (K % 128 != 0 || N % 64 != 0 || (block_m == 256 && N % 128 != 0))
+    return fail(MOE_UNSUPPORTED_SHAPE,
+                "the grouped FP8 GEMM needs K %% 128 == 0 and N %% 64 == 0 (N %% 128 == 0 at block_m 256); got N=%d K=%d",
+                N, K);
+  if (num_slots == 0) return MOE_OK;
+  if (!A || !a_scale || !B || !b_scale || !sorted_slot_ids || !block_expert_ids || !num_padded || !C)
+    return fail(MOE_INVALID_ARGUMENT, "null pointer argument");
+  if (((uintptr_t)A | (uintptr_t)B | (uintptr_t)C) % 16 != 0 || ((uintptr_t)a_scale | (uintptr_t)b_scale) % 4 != 0)
+    return fail(MOE_INVALID_ARGUMENT, "A, B, C must be 16-byte aligned, the scales 4-byte aligned");
+  if (C == (const void*)A || C == (const void*)B) return fail(MOE_INVALID_ARGUMENT, "C must not alias an input");
+  const unsigned long long rows_a = ((unsigned long long)num_slots + row_div - 1) / row_div;
+  if (rows_a * (unsigned long long)K >= (1ull << 32) || (unsigned long long)N * (unsigned long long)K >= (1ull << 32))
+    return fail(MOE_UNSUPPORTED_SHAPE, "32-bit operand offsets: rows(A) * K and N * K must be below 2^32");
+  const size_t cap = align_capacity(num_slots, E, block_m);
+  const int bn = N % 128 == 0 ? 128 : 64;
+  const long long grid = (long long)(cap / block_m) * (N / bn);
+  if (cap > 0x7fffffffULL || grid > 0x7fffffffLL) return fail(MOE_UNSUPPORTED_SHAPE, "too many workgroups");
+  fp8::GemmParams p = {};
+  p.A = A; p.a_scale = a_scale; p.B = B; p.b_scale = b_scale; p.C = C;
+  p.M = (int)cap; p.N = N; p.K = K;
+  p.k_splits = 1; p.kb_per_split = K / 128; p.out_bf16 = out_dtype;
+  p.group_m = g_fp8_group_m ? g_fp8_group_m : 8;
+  p.sorted_slot_ids = sorted_slot_ids; p.block_expert_ids = block_expert_ids; p.num_padded = num_padded;
+  p.num_slots = num_slots; p.row_div = row_div;
+  p.b_expert_stride = (size_t)N * (size_t)K;
+  p.bs_expert_stride = (size_t)((N + 127) / 128) * (size_t)(K / 128);
+  const int err = fp8::launch_fp8_gemm(p, block_m, bn, (hipStream_t)stream);
+  if (err == -1) return fail(MOE_UNSUPPORTED_SHAPE, "no FP8 GEMM variant for tile %d x %d", block_m, bn);
+  if (err != 0) return hip_fail(err, "grouped FP8 GEMM launch");
   return MOE_OK;
 }
 

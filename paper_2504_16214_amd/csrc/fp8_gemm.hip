@@ -115,19 +115,40 @@ fp8_blockwise_gemm_kernel(const GemmParams p) {
   // therefore fetches chunk s ^ (r & 7) of that row.  Pass i of the workgroup covers tile rows
   // [RPP i, RPP (i + 1)), wave w rows 8 w .. 8 w + 7 of the pass.
   const int srow = tid >> 3, sc = tid & 7;
+  const bool grouped = p.sorted_slot_ids != nullptr;
+  const uint8_t* Bmat = p.B;
+  const float* bsmat = p.b_scale;
+  if (grouped) {
+    // row blocks past the bucketed slots, and blocks without an expert, have nothing to do
+    // (uniform over the workgroup: nobody reaches a barrier)
+    if (row0 >= *p.num_padded) return;
+    const int e = p.block_expert_ids[mb];
+    if (e < 0) return;
+    Bmat += (size_t)e * p.b_expert_stride;
+    bsmat += (size_t)e * p.bs_expert_stride;
+  }
+  // A row behind a tile row: dense = the row itself (rows past the matrix repeat its last row and
+  // are never stored); grouped = slot / row_div (padding rows read row 0)
+  auto a_row_of = [&](int r) __attribute__((always_inline)) -> int {
+    if (grouped) {
+      const int slot = p.sorted_slot_ids[row0 + r];
+      return (slot >= 0 && slot < p.num_slots) ? slot / p.row_div : 0;
+    }
+    const int g = row0 + r;
+    return g >= p.M ? p.M - 1 : g;
+  };
   uint32_t aoff[CHA], boff[CHB];                  // byte offsets from A / B (host checks they fit 32 bits)
 #pragma unroll
   for (int i = 0; i < CHA; ++i) {
-    int g = row0 + srow + RPP * i;
-    if (g >= p.M) g = p.M - 1;                    // rows past the matrix repeat its last row (never stored to C)
-    aoff[i] = (uint32_t)g * (uint32_t)p.K + 16u * (sc ^ (srow & 7));
+    int r = srow + RPP * i;
+    if (r >= BM) r = BM - 1;                      // LDS rows past the token tile (padding of the pass) repeat its last row
+    aoff[i] = (uint32_t)a_row_of(r) * (uint32_t)p.K + 16u * (sc ^ (srow & 7));
   }
 #pragma unroll
   for (int i = 0; i < CHB; ++i) boff[i] = (uint32_t)(n0 + srow + RPP * i) * (uint32_t)p.K + 16u * (sc ^ (srow & 7));
-  int sg = row0 + (tid < BM ? tid : BM - 1);      // activation scale of tile row tid (threads past BM repeat the last row)
-  if (sg >= p.M) sg = p.M - 1;
-  const float* assrc = p.a_scale + (size_t)sg * KB;
-  const float* bssrc = p.b_scale + (size_t)((n0 + wn * 16 * NT) >> 7) * KB;      // wave-uniform
+  // activation scale of tile row tid (threads past BM repeat the last row)
+  const float* assrc = p.a_scale + (size_t)a_row_of(tid < BM ? tid : BM - 1) * KB;
+  const float* bssrc = bsmat + (size_t)((n0 + wn * 16 * NT) >> 7) * KB;      // wave-uniform
 
   // ---- operand read positions ----
   // features: operand row ln of sub-tile nt is feature 4 NT (ln >> 2) + 4 nt + (ln & 3) of the wave's
@@ -151,7 +172,7 @@ fp8_blockwise_gemm_kernel(const GemmParams p) {
   typedef __attribute__((address_space(3))) void* lptr_t;
   auto dma_block = [&](int buf, int kb) __attribute__((always_inline)) {
     const uint8_t* ab = p.A + (size_t)kb * 128;
-    const uint8_t* bb = p.B + (size_t)kb * 128;
+    const uint8_t* bb = Bmat + (size_t)kb * 128;
     unsigned char* st = lds + buf * G::STAGE + 1024 * wave;            // this wave's 8 rows of every pass
 #pragma unroll
     for (int i = 0; i < CHB; ++i)
@@ -257,8 +278,13 @@ fp8_blockwise_gemm_kernel(const GemmParams p) {
   const int f0 = n0 + wn * 16 * NT + 4 * NT * lj;
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {
-    const int t = row0 + xrow + 16 * mt;
-    if (t >= p.M) continue;
+    int t = row0 + xrow + 16 * mt;               // dense: the token; grouped: the slot behind the tile row
+    if (grouped) {
+      t = p.sorted_slot_ids[t];
+      if (t < 0 || t >= p.num_slots) continue;   // padding row
+    } else if (t >= p.M) {
+      continue;
+    }
     if (p.k_splits > 1) {
       float* dst = reinterpret_cast<float*>(p.C) + ((size_t)split * p.M + t) * p.N + f0;
 #pragma unroll

@@ -16,6 +16,16 @@ struct GemmParams {
   int kb_per_split;    // reduction blocks per split (the last split may be shorter)
   int out_bf16;        // 16-bit output type when k_splits == 1: 1 bf16, 0 fp16
   int group_m;         // row blocks per tile group (>= 1): the order in which tiles are handed out
+  // Grouped (one weight matrix per expert) mode, sorted_slot_ids != nullptr: M is the capacity of
+  // the slot table (a multiple of the token tile), tile row r of row block mb is slot
+  // sorted_slot_ids[mb * BM + r] (>= num_slots: padding), its A row is slot / row_div, its C row is
+  // slot; row block mb belongs to expert block_expert_ids[mb] (blocks at or past *num_padded do
+  // nothing); B and b_scale advance by b_expert_stride / bs_expert_stride elements per expert.
+  const int32_t* sorted_slot_ids;
+  const int32_t* block_expert_ids;
+  const int32_t* num_padded;
+  int num_slots, row_div;
+  size_t b_expert_stride, bs_expert_stride;
 };
 
 // bm = tokens per workgroup in {16, 32, 64, 128, 256}, bn = features per workgroup in {64, 128, 256}

@@ -182,3 +182,88 @@ def test_mfma_probe_runs():
     M_.fp8_probe_mfma(sink, 64)
     torch.cuda.synchronize()
     assert torch.isfinite(sink).all()
+
+
+# ------------------------------------------------------------------ grouped (one matrix per expert)
+def _grouped_case(T, topk, E, N, K, row_div_is_topk, seed, bad_ids=False):
+    """Seeded routed workload: random expert ids (optionally with ignored ids), activations and E
+    weight matrices quantised by the generator's recipe."""
+    rng = np.random.default_rng(seed)
+    ids = rng.integers(0, E, size=(T, topk)).astype(np.int32)
+    if bad_ids:
+        ids[0, 0] = -1
+        ids[T - 1, topk - 1] = E + 3
+    rows = T if row_div_is_topk else T * topk
+    a = make_fp8_inputs(Fp8GemmConfig("ga", M=rows, N=128, K=K, seed=seed))
+    ws = [make_fp8_inputs(Fp8GemmConfig("gb", M=1, N=N, K=K, seed=seed + 1 + e)) for e in range(E)]
+    b = np.stack([w.b_codes for w in ws])
+    sb = np.stack([w.b_scale for w in ws])
+    return ids, a.a_codes, a.a_scale, b, sb
+
+
+@pytest.mark.parametrize("T,topk,E,N,K,block_m,row_div_is_topk,bad_ids", [
+    (5, 2, 3, 128, 256, 16, True, False),          # tiny
+    (40, 2, 4, 192, 384, 16, True, True),          # N % 128 != 0 (64-feature tiles), ignored ids
+    (64, 4, 8, 256, 512, 32, False, False),        # A already per slot (row_div 1)
+    (300, 2, 5, 256, 384, 64, True, True),         # several row blocks per expert, ragged last ones
+    (700, 1, 3, 384, 256, 128, True, False),       # 128-slot tiles
+    (900, 2, 2, 256, 256, 256, False, False),      # 256-slot eight-wave tile
+])
+def test_grouped_gemm_matches_oracle(T, topk, E, N, K, block_m, row_div_is_topk, bad_ids):
+    import gpu_util as U
+    say(f"fp8 grouped gemm T={T} topk={topk} E={E} N={N} K={K} block_m={block_m} row_div={'topk' if row_div_is_topk else 1}")
+    ids, a, sa, b, sb = _grouped_case(T, topk, E, N, K, row_div_is_topk, seed=500 + T + block_m, bad_ids=bad_ids)
+    row_div = topk if row_div_is_topk else 1
+    S = T * topk
+    al = U.run_align(torch.from_numpy(ids).cuda(), E, block_m)
+    C = torch.full((S, N), float("nan"), dtype=torch.bfloat16, device="cuda")
+    M_.fp8_moe_grouped_gemm(torch.from_numpy(a).cuda(), torch.from_numpy(sa).cuda(), row_div,
+                            torch.from_numpy(b).cuda(), torch.from_numpy(sb).cuda(),
+                            al["sorted_slot_ids"], al["block_expert_ids"], al["num_padded"], S, block_m, C)
+    torch.cuda.synchronize()
+    got = C.to(torch.float64).cpu().numpy()
+    want, valid = F.grouped_blockwise_gemm(a, sa, row_div, b, sb, ids.reshape(-1))
+    assert np.isnan(got[~valid]).all(), "rows of ignored slots must stay untouched"
+    assert not np.isnan(got[valid]).any()
+    worst = 0.0
+    flat = ids.reshape(-1)
+    for e in range(E):
+        slots = np.nonzero(flat == e)[0]
+        if slots.size == 0:
+            continue
+        rows = slots // row_div
+        bound = error_bound(want[slots], a[rows], sa[rows], b[e], sb[e])
+        worst = max(worst, float((np.abs(got[slots] - want[slots]) / bound).max()))
+    say(f"grouped: max err / bound = {worst:.3f}")
+    assert worst <= 1.0
+
+
+def test_grouped_gemm_one_expert_equals_dense_bitwise():
+    import gpu_util as U
+    say("fp8 grouped gemm, one expert == dense")
+    inp = make_fp8_inputs(Fp8GemmConfig("g1", M=70, N=256, K=512, seed=77))
+    A, B = torch.from_numpy(inp.a_codes).cuda(), torch.from_numpy(inp.b_codes).cuda()
+    sa, sb = torch.from_numpy(inp.a_scale).cuda(), torch.from_numpy(inp.b_scale).cuda()
+    C1 = torch.zeros((70, 256), dtype=torch.bfloat16, device="cuda")
+    C2 = torch.zeros_like(C1)
+    M_.fp8_set_plan_override(4, 2, 1, 0)                       # the tile the grouped call uses at block_m 64
+    try:
+        M_.fp8_blockwise_gemm(A, sa, B, sb, C1, None)
+    finally:
+        M_.fp8_set_plan_override(0, 0, 0, 0)
+    al = U.run_align(torch.zeros((70, 1), dtype=torch.int32, device="cuda"), 1, 64)
+    M_.fp8_moe_grouped_gemm(A, sa, 1, B[None].contiguous(), sb[None].contiguous(), al["sorted_slot_ids"],
+                            al["block_expert_ids"], al["num_padded"], 70, 64, C2)
+    torch.cuda.synchronize()
+    assert torch.equal(C1, C2)
+
+
+def test_grouped_gemm_empty_and_errors():
+    say("fp8 grouped gemm: no slots / errors")
+    lib = M_.load_library()
+    p = 0x10000
+    assert lib.fp8_moe_grouped_gemm(None, None, 1, None, None, None, None, None, 0, 4, 128, 256, 16, 1, None, None) == 0
+    assert lib.fp8_moe_grouped_gemm(p, p, 1, p, p, p, p, p, 8, 4, 128, 200, 16, 1, 2 * p, None) == 2      # K % 128
+    assert lib.fp8_moe_grouped_gemm(p, p, 1, p, p, p, p, p, 8, 4, 128, 256, 24, 1, 2 * p, None) == 1      # block_m
+    assert lib.fp8_moe_grouped_gemm(p, p, 0, p, p, p, p, p, 8, 4, 128, 256, 16, 1, 2 * p, None) == 1      # row_div
+    assert lib.fp8_moe_grouped_gemm(p, p, 1, p, p, None, p, p, 8, 4, 128, 256, 16, 1, 2 * p, None) == 1   # null table
