@@ -13,8 +13,9 @@
 //     per 128-byte row block); operand-order loads straight from global memory (one row per lane)
 //     cost the texture path four times the cycles and were the bottleneck of a first version.  LDS
 //     rows are 128 bytes with their 16-byte chunks XOR-swizzled by the row index (the swizzle is
-//     applied on the global side: which chunk a lane fetches), two buffers, one barrier per
-//     reduction block; every wave waits for its own loads (vmcnt(0)) before that barrier.
+//     applied on the global side: which chunk a lane fetches), a ring of NS buffers (two in every
+//     compiled variant), one barrier per reduction block; every wave waits for its own loads of the
+//     next block (vmcnt) before that barrier.
 //   * The order of the 128 reduction indices inside an instruction is free as long as both
 //     operands use the same one: lane group j takes bytes [16 j, +16) and [64 + 16 j, +16) of a row.
 //   * The activation scales of a block travel through LDS with the tile (one 4-byte direct-to-LDS
