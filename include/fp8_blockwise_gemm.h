@@ -14,7 +14,8 @@
  *   a_scale [M, K/128] float32
  *   B       [N, K] e4m3 (the weight: one row per output feature)
  *   b_scale [ceil(N/128), K/128] float32
- *   C       [M, N] 16-bit floats (out_dtype: 0 = fp16, 1 = bf16), rounded once from float32.
+ *   C       [M, N] out_dtype: 0 = fp16, 1 = bf16 (rounded once from float32), 2 = float32 (the
+ *           accumulator as it is).
  *
  * Arithmetic: the 128 products of a block are summed by one matrix instruction (exact products,
  * the instruction's own internal alignment of the sum), every block's sum is scaled by

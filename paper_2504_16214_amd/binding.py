@@ -261,12 +261,12 @@ def fp8_blockwise_gemm_workspace_bytes(M: int, N: int, K: int) -> int:
 
 def fp8_blockwise_gemm(A, a_scale, B, b_scale, C, workspace=None, stream=None) -> None:
     """A [M, K] uint8 e4m3 codes, a_scale [M, K/128] float32, B [N, K] uint8, b_scale [ceil(N/128), K/128]
-    float32, C [M, N] float16 / bfloat16 (preallocated); workspace: uint8 tensor of at least
+    float32, C [M, N] float16 / bfloat16 / float32 (preallocated); workspace: uint8 tensor of at least
     fp8_blockwise_gemm_workspace_bytes(M, N, K) bytes (None when that is 0)."""
     import torch
     M, K = A.shape
     N = B.shape[0]
-    out_dtype = 1 if C.dtype == torch.bfloat16 else 0
+    out_dtype = {torch.float16: 0, torch.bfloat16: 1, torch.float32: 2}[C.dtype]
     wb = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(load_library().fp8_blockwise_gemm(_ptr(A), _ptr(a_scale), _ptr(B), _ptr(b_scale), _ptr(C), M, N, K,
                                              out_dtype, None if workspace is None else _ptr(workspace), wb,
@@ -279,7 +279,7 @@ def fp8_moe_grouped_gemm(A, a_scale, row_div: int, B, b_scale, sorted_slot_ids, 
     slot tables from moe_align_by_expert, C [num_slots, N] float16 / bfloat16 (preallocated)."""
     import torch
     E, N, K = B.shape
-    out_dtype = 1 if C.dtype == torch.bfloat16 else 0
+    out_dtype = {torch.float16: 0, torch.bfloat16: 1, torch.float32: 2}[C.dtype]
     _check(load_library().fp8_moe_grouped_gemm(_ptr(A), _ptr(a_scale), row_div, _ptr(B), _ptr(b_scale),
                                                _ptr(sorted_slot_ids), _ptr(block_expert_ids), _ptr(num_padded),
                                                num_slots, E, N, K, block_m, out_dtype, _ptr(C), _stream(stream)))

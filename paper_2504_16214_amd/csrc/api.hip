@@ -633,7 +633,8 @@ size_t fp8_blockwise_gemm_workspace_bytes(int M, int N, int K) {
 int fp8_blockwise_gemm(const uint8_t* A, const float* a_scale, const uint8_t* B, const float* b_scale, void* C,
                        int M, int N, int K, int out_dtype, void* workspace, size_t workspace_bytes, void* stream) {
   if (M < 0 || N < 1 || K < 1) return fail(MOE_INVALID_ARGUMENT, "need M >= 0, N >= 1, K >= 1");
-  if (out_dtype != 0 && out_dtype != 1) return fail(MOE_INVALID_ARGUMENT, "out_dtype must be 0 (fp16) or 1 (bf16)");
+  if (out_dtype < 0 || out_dtype > 2)
+    return fail(MOE_INVALID_ARGUMENT, "out_dtype must be 0 (fp16), 1 (bf16) or 2 (float32)");
   if (K % 128 != 0 || N % 64 != 0)
     return fail(MOE_UNSUPPORTED_SHAPE, "the FP8 GEMM needs K %% 128 == 0 and N %% 64 == 0 (got N=%d K=%d)", N, K);
   if (M == 0) return MOE_OK;
@@ -680,7 +681,8 @@ int fp8_moe_grouped_gemm(const uint8_t* A, const float* a_scale, int row_div, co
                          void* C, void* stream) {
   if (num_slots < 0 || E < 1 || E > 1024 || N < 1 || K < 1 || row_div < 1)
     return fail(MOE_INVALID_ARGUMENT, "need num_slots >= 0, 1 <= E <= 1024, N >= 1, K >= 1, row_div >= 1");
-  if (out_dtype != 0 && out_dtype != 1) return fail(MOE_INVALID_ARGUMENT, "out_dtype must be 0 (fp16) or 1 (bf16)");
+  if (out_dtype < 0 || out_dtype > 2)
+    return fail(MOE_INVALID_ARGUMENT, "out_dtype must be 0 (fp16), 1 (bf16) or 2 (float32)");
   if (!valid_block_m(block_m)) return fail(MOE_INVALID_ARGUMENT, "block_m must be 16, 32, 64, 128 or 256");
   if (K % 128 != 0 || N % 64 != 0 || (block_m == 256 && N % 128 != 0))
     return fail(MOE_UNSUPPORTED_SHAPE,

@@ -286,7 +286,7 @@ fp8_blockwise_gemm_kernel(const GemmParams p) {
     } else if (t >= p.M) {
       continue;
     }
-    if (p.k_splits > 1) {
+    if (p.k_splits > 1 || p.out_bf16 == 2) {     // float32: a partial plane, or the result itself
       float* dst = reinterpret_cast<float*>(p.C) + ((size_t)split * p.M + t) * p.N + f0;
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt) *reinterpret_cast<f32x4*>(dst + 4 * nt) = acc[mt][nt];
@@ -295,7 +295,7 @@ fp8_blockwise_gemm_kernel(const GemmParams p) {
       uint32_t w[2 * NT];
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt) {
-        if (p.out_bf16) {
+        if (p.out_bf16 == 1) {
           w[2 * nt] = pack2<1>(acc[mt][nt][0], acc[mt][nt][1]);
           w[2 * nt + 1] = pack2<1>(acc[mt][nt][2], acc[mt][nt][3]);
         } else {
@@ -316,13 +316,15 @@ fp8_blockwise_gemm_kernel(const GemmParams p) {
 
 // Sum of the float32 planes in plane order, one rounding.  n4 = M * N / 4.
 __global__ void __launch_bounds__(256)
-fp8_split_reduce_kernel(const f32x4* __restrict__ planes, int k_splits, long long n4, u32x2* __restrict__ C,
-                        int out_bf16) {
+fp8_split_reduce_kernel(const f32x4* __restrict__ planes, int k_splits, long long n4, void* __restrict__ C,
+                        int out_type) {
   for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < n4; i += (long long)gridDim.x * 256) {
     f32x4 s = planes[i];
     for (int k = 1; k < k_splits; ++k) s += planes[(long long)k * n4 + i];
-    C[i] = out_bf16 ? u32x2{pack2<1>(s[0], s[1]), pack2<1>(s[2], s[3])}
-                    : u32x2{pack2<0>(s[0], s[1]), pack2<0>(s[2], s[3])};
+    if (out_type == 2) reinterpret_cast<f32x4*>(C)[i] = s;
+    else
+      reinterpret_cast<u32x2*>(C)[i] = out_type == 1 ? u32x2{pack2<1>(s[0], s[1]), pack2<1>(s[2], s[3])}
+                                                     : u32x2{pack2<0>(s[0], s[1]), pack2<0>(s[2], s[3])};
   }
 }
 
@@ -398,7 +400,7 @@ int launch_fp8_split_reduce(const float* planes, int k_splits, long long mn, voi
   if (blocks > 8192) blocks = 8192;
   if (blocks < 1) blocks = 1;
   hipLaunchKernelGGL(fp8_split_reduce_kernel, dim3((int)blocks), dim3(256), 0, stream, (const f32x4*)planes,
-                     k_splits, n4, (u32x2*)C, out_bf16);
+                     k_splits, n4, C, out_bf16);
   return (int)hipGetLastError();
 }
 

@@ -10,11 +10,11 @@ struct GemmParams {
   const float* a_scale;
   const uint8_t* B;
   const float* b_scale;
-  void* C;             // k_splits == 1: 16-bit [M, N]; otherwise float32 planes [k_splits, M, N]
+  void* C;             // k_splits == 1: the result [M, N]; otherwise float32 planes [k_splits, M, N]
   int M, N, K;
   int k_splits;        // >= 1
   int kb_per_split;    // reduction blocks per split (the last split may be shorter)
-  int out_bf16;        // 16-bit output type when k_splits == 1: 1 bf16, 0 fp16
+  int out_bf16;        // output type of the result: 0 fp16, 1 bf16, 2 float32
   int group_m;         // row blocks per tile group (>= 1): the order in which tiles are handed out
   // Grouped (one weight matrix per expert) mode, sorted_slot_ids != nullptr: M is the capacity of
   // the slot table (a multiple of the token tile), tile row r of row block mb is slot

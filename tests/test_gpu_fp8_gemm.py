@@ -5,10 +5,13 @@ Bound, per output element (derived from the arithmetic, not tuned to pass):
 * first term: one unit in the last place of the 16-bit result (8 significant bits for bf16; fp16
   is finer) -- a near-tie that the float32 and the float64 sums round to different neighbours;
 * second term: the matrix instruction sums the 128 exact products of a block with its own
-  internal alignment, not in full float32: measured on uniformly random codes, the error of one
-  block sum reaches 2^-13.2 of the block's largest product; 2^-10 of the largest possible product
-  of the block (amaxA * amaxB) bounds it with room, and the float32 scale product and the
-  K/128-term float32 accumulation (2^-24 each) vanish next to it.
+  internal alignment, not in full float32: measured on uniformly random codes (the test with
+  float32 output below), the error of one block sum reaches 2^-11.1 of the block's largest product
+  over 16384 outputs (median 2^-14.4) -- what truncating each of the 128 products some 18 bits
+  below the largest one would give, whose worst case is 2^-10 of the largest product.  The bound
+  takes 2^-10 of the largest POSSIBLE product of the block (amaxA * amaxB >= the largest actual
+  one); the float32 scale product and the K/128-term float32 accumulation (2^-24 each) vanish
+  next to it.
 For the benchmark's inputs the second term is about half a bf16 ulp of a typical output."""
 from __future__ import annotations
 
@@ -267,3 +270,45 @@ def test_grouped_gemm_empty_and_errors():
     assert lib.fp8_moe_grouped_gemm(p, p, 1, p, p, p, p, p, 8, 4, 128, 256, 24, 1, 2 * p, None) == 1      # block_m
     assert lib.fp8_moe_grouped_gemm(p, p, 0, p, p, p, p, p, 8, 4, 128, 256, 16, 1, 2 * p, None) == 1      # row_div
     assert lib.fp8_moe_grouped_gemm(p, p, 1, p, p, None, p, p, 8, 4, 128, 256, 16, 1, 2 * p, None) == 1   # null table
+
+
+# ------------------------------------------------------------------ float32 output: the accumulator itself
+def test_float32_output_and_the_block_sum_error_of_the_matrix_instruction():
+    """With float32 output and unit scales a single reduction block shows the matrix instruction's
+    own summation error: uniformly random codes (the widest dynamic range a block can have), exact
+    float64 block sums from the oracle.  Observed: up to 2^-11.1 of the block's largest product
+    (median 2^-14.4); the parity bound of this file allows 2^-10 of the largest possible product.
+    A float32-exact summation would sit near 2^-24 * 128 = 2^-17."""
+    rng = np.random.default_rng(99)
+    Mr, N, K = 64, 256, 128
+    a = rng.integers(0, 256, size=(Mr, K), dtype=np.uint8); a[(a & 0x7F) == 0x7F] = 0x38
+    b = rng.integers(0, 256, size=(N, K), dtype=np.uint8); b[(b & 0x7F) == 0x7F] = 0xB8
+    ones_a, ones_b = np.ones((Mr, 1), np.float32), np.ones((N // 128, 1), np.float32)
+    say(f"fp8 gemm float32 output, one block, M={Mr} N={N}")
+    got = run_gemm(a, ones_a, b, ones_b, dtype=torch.float32)
+    want = F.blockwise_gemm(a, ones_a, b, ones_b, out_dt=None)
+    A, B = np.abs(F.decode_e4m3(a)), np.abs(F.decode_e4m3(b))
+    maxprod = (A[:, None, :] * B[None, :, :]).max(axis=2)                 # largest |a_k b_k| per output
+    rel = np.abs(got - want) / maxprod
+    say(f"block-sum error of the matrix instruction: max = 2^{np.log2(rel.max()):.1f} of the largest product, "
+        f"median = 2^{np.log2(np.median(rel[rel > 0])):.1f}")
+    assert rel.max() <= 2.0 ** -10
+    assert rel.max() >= 2.0 ** -20        # it is NOT a full float32 summation: the tolerance term is needed
+
+
+@pytest.mark.parametrize("splits", [1, 3])
+def test_float32_output_matches_unrounded_oracle(splits):
+    cfg = Fp8GemmConfig("f32", M=45, N=256, K=896, seed=61)
+    say(f"fp8 gemm float32 output, splits {splits}")
+    inp = make_fp8_inputs(cfg)
+    M_.fp8_set_plan_override(2, 2, splits, 0)
+    try:
+        got = run_gemm(inp.a_codes, inp.a_scale, inp.b_codes, inp.b_scale, dtype=torch.float32)
+    finally:
+        M_.fp8_set_plan_override(0, 0, 0, 0)
+    want = F.blockwise_gemm(inp.a_codes, inp.a_scale, inp.b_codes, inp.b_scale, out_dt=None)
+    # no 16-bit rounding: only the block-sum term of the bound (and float32 accumulation, 2^-22 with room)
+    bound = error_bound(np.zeros_like(want), inp.a_codes, inp.a_scale, inp.b_codes, inp.b_scale) + 2.0 ** -22 * np.abs(want)
+    worst = float((np.abs(got - want) / bound).max())
+    say(f"float32 out: max err / bound = {worst:.3f}")
+    assert worst <= 1.0
