@@ -312,3 +312,39 @@ def test_float32_output_matches_unrounded_oracle(splits):
     worst = float((np.abs(got - want) / bound).max())
     say(f"float32 out: max err / bound = {worst:.3f}")
     assert worst <= 1.0
+
+
+def test_gemm_with_split_reduction_is_graph_capturable():
+    """Nothing is allocated, nothing synchronises and both kernels go to the given stream, so the
+    call (GEMM into float32 planes + plane reduction) can be recorded into a HIP graph; every replay,
+    with eager work and synchronisations in between and with the workspace overwritten, equals the
+    eager result bit for bit."""
+    cfg = Fp8GemmConfig("graph", M=24, N=1024, K=2048, seed=71)
+    say(f"fp8 gemm graph capture {cfg}")
+    inp = make_fp8_inputs(cfg)
+    A, B = torch.from_numpy(inp.a_codes).cuda(), torch.from_numpy(inp.b_codes).cuda()
+    sa, sb = torch.from_numpy(inp.a_scale).cuda(), torch.from_numpy(inp.b_scale).cuda()
+    nbytes = M_.fp8_blockwise_gemm_workspace_bytes(cfg.M, cfg.N, cfg.K)
+    assert nbytes > 0, "the shape is meant to take the split-reduction path"
+    ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    eager = torch.full((cfg.M, cfg.N), float("nan"), dtype=torch.bfloat16, device="cuda")
+    M_.fp8_blockwise_gemm(A, sa, B, sb, eager, ws)
+    torch.cuda.synchronize()
+    out = torch.zeros_like(eager)
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        M_.fp8_blockwise_gemm(A, sa, B, sb, out, ws)                       # warm-up on the side stream
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            M_.fp8_blockwise_gemm(A, sa, B, sb, out, ws, stream=side)
+    for rep in range(3):
+        out.fill_(float("nan"))
+        ws.random_(0, 255)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out.view(torch.int16), eager.view(torch.int16)), f"replay {rep}"
+        junk = torch.randn(1 << 16, device="cuda").sum().item()
+        assert junk == junk
