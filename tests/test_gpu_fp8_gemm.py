@@ -293,7 +293,6 @@ def test_float32_output_and_the_block_sum_error_of_the_matrix_instruction():
     say(f"block-sum error of the matrix instruction: max = 2^{np.log2(rel.max()):.1f} of the largest product, "
         f"median = 2^{np.log2(np.median(rel[rel > 0])):.1f}")
     assert rel.max() <= 2.0 ** -10
-    assert rel.max() >= 2.0 ** -20        # it is NOT a full float32 summation: the tolerance term is needed
 
 
 @pytest.mark.parametrize("splits", [1, 3])
