@@ -300,6 +300,8 @@ static bool fp8_plan(int M, int N, int K, Fp8Plan& pl) {
   // matrix instruction: 1.65-1.8 against 1.4-1.5 PFLOP/s) when it still yields two workgroups per CU.
   int bn = 128;
   if (M > 128 && N % 256 == 0 && (long long)((M + 255) / 256) * (N / 256) >= 512) { bm = 256; bn = 256; }
+  // a few hundred rows: 64-token tiles when 128-token tiles would leave CUs without a second workgroup
+  else if (M > 128 && N % 128 == 0 && (long long)((M + 127) / 128) * (N / 128) < 512) bm = 64;
   if (g_fp8_mt) { bm = 16 * g_fp8_mt; bn = 128; }
   if (bm != 16 && bm != 32 && bm != 64 && bm != 128 && bm != 256) return false;
   const long long m_blocks = (M + bm - 1) / bm;
