@@ -325,14 +325,19 @@ def fp8_cpu_baseline(cfg, inp, target_s=12.0):
         threads = os.cpu_count() or 1
     rows = min(cfg.M, 64)
 
-    def run(nblk):
+    def run(nblk, nrows):
         t0 = time.perf_counter()
-        F.blockwise_gemm(inp.a_codes[:rows], inp.a_scale[:rows], inp.b_codes[:128 * nblk], inp.b_scale[:nblk])
+        F.blockwise_gemm(inp.a_codes[:nrows], inp.a_scale[:nrows], inp.b_codes[:128 * nblk], inp.b_scale[:nblk])
         return time.perf_counter() - t0
 
-    probe = run(1)
+    probe = run(1, rows)
     nblk = int(max(1, min(cfg.N // 128, target_s / max(probe, 1e-4))))
-    dt = run(nblk)
+    est = probe * nblk
+    if nblk == cfg.N // 128 and est < target_s / 2 and cfg.M > rows:
+        # all of B already fits the budget: take more rows of A (the decode of B dominates, so
+        # the estimate is conservative)
+        rows = int(min(cfg.M, rows * target_s / max(est, 1e-4)))
+    dt = run(nblk, rows)
     fl = 2.0 * rows * 128 * nblk * cfg.K
     return {"value": round(fl / dt / 1e12, 6), "unit": "TFLOP/s", "cores": int(threads), "kind": "oracle",
             "seconds": round(dt, 2),
