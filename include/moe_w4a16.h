@@ -241,6 +241,15 @@ int moe_w4a16_routed_layer(const void* X, const float* logits, const float* bias
  * Thread-local.
  *
  * moe_layer_block_m: the bucketing block size the layer picks for these sizes.
+ *
+ * moe_set_block_m_override: force the bucketing block of moe_w4a16_layer (16 ... 256) instead of
+ * the built-in choice; 0 restores it.  Thread-local.
+ *
+ * moe_last_gemm_plan: what the last grouped / dense GEMM launch issued from this thread used:
+ * plan8 (HOST pointer to 8 ints) = {mt, nt, ks, register_scales, tiles_per_workgroup,
+ * reduction_splits, reduction_indices_per_split, fused_silu}.  A workgroup covers 16*mt rows and
+ * tiles_per_workgroup consecutive tiles of 64*nt features (32*nt act columns when fused).  Tests
+ * use it to aim samples at tile and tile-group borders.
  */
 int moe_set_stage_events(void* const* events, int n);
 
@@ -262,6 +271,8 @@ int moe_set_scale_path(int mode);
 int moe_set_tiles_per_workgroup(int n);
 int moe_set_reduction_splits(int n);
 int moe_layer_block_m(int T, int E, int topk);
+int moe_set_block_m_override(int block_m);
+int moe_last_gemm_plan(int* plan8);
 
 #ifdef __cplusplus
 }

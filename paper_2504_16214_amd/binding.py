@@ -21,7 +21,7 @@ EXPORTS = [
     "moe_w4a16_routed_layer_workspace_bytes", "moe_w4a16_routed_layer",
     "moe_repack_qweight", "moe_w4a16_layer_prepacked", "moe_import_awq",
     "fp8_blockwise_gemm_workspace_bytes", "fp8_blockwise_gemm", "fp8_moe_grouped_gemm", "fp8_set_plan_override",
-    "fp8_probe_mfma",
+    "fp8_probe_mfma", "moe_set_block_m_override", "moe_last_gemm_plan",
 ]
 
 
@@ -102,6 +102,10 @@ def load_library() -> ctypes.CDLL:
     lib.moe_set_reduction_splits.argtypes = [i32]
     lib.moe_layer_block_m.restype = i32
     lib.moe_layer_block_m.argtypes = [i32, i32, i32]
+    lib.moe_set_block_m_override.restype = i32
+    lib.moe_set_block_m_override.argtypes = [i32]
+    lib.moe_last_gemm_plan.restype = i32
+    lib.moe_last_gemm_plan.argtypes = [ctypes.POINTER(ctypes.c_int)]
     _LIB = lib
     return lib
 
@@ -295,6 +299,18 @@ def fp8_probe_mfma(sink, iters: int, stream=None) -> None:
 
 def moe_set_tile_override(mt: int, nt: int) -> None:
     _check(load_library().moe_set_tile_override(mt, nt))
+
+
+def moe_set_block_m_override(block_m: int) -> None:
+    _check(load_library().moe_set_block_m_override(block_m))
+
+
+def moe_last_gemm_plan() -> dict:
+    """The tile plan of the last grouped / dense GEMM launched from this thread."""
+    arr = (ctypes.c_int * 8)()
+    _check(load_library().moe_last_gemm_plan(arr))
+    keys = ("mt", "nt", "ks", "register_scales", "tiles_per_workgroup", "reduction_splits", "k_span", "fused")
+    return dict(zip(keys, (int(v) for v in arr)))
 
 
 def moe_set_scale_path(mode: int) -> None:

@@ -73,6 +73,8 @@ static thread_local int g_force_mt = 0, g_force_nt = 0;
 static thread_local int g_scale_path = 0;   // 0 auto, 1 LDS table, 2 registers
 static thread_local int g_force_tpw = 0;    // feature tiles per workgroup (register-scale kernels), 0 = auto
 static thread_local int g_force_ksplit = 0; // reduction splits of the layer's down projection, 0 = auto
+static thread_local int g_force_block_m = 0; // bucketing block of the layer, 0 = auto
+static thread_local int g_last_plan[8] = {0, 0, 0, 0, 0, 0, 0, 0};   // what the last grouped GEMM launch used
 
 static int fail(int status, const char* fmt, ...) {
   va_list ap;
@@ -235,6 +237,8 @@ static int run_gemm(const GemmArgs& a, hipStream_t stream) {
   p.tiles_per_wg = tpw;
   const long long grid = (long long)(cap / (16 * mt)) * ((p.n_tiles + tpw - 1) / tpw) * ksp;
   if (grid > 0x7fffffffLL) return fail(MOE_UNSUPPORTED_SHAPE, "grid too large");
+  g_last_plan[0] = mt; g_last_plan[1] = nt; g_last_plan[2] = ks; g_last_plan[3] = szr;
+  g_last_plan[4] = tpw; g_last_plan[5] = ksp; g_last_plan[6] = kspan; g_last_plan[7] = fuse;
   const int err = v->fn(p, (int)grid, stream);
   if (err != 0) return hip_fail(err, "grouped GEMM launch");
   return MOE_OK;
@@ -272,7 +276,7 @@ static Workspace carve(long long T, int K, int N, int E, int topk) {
   w.counts = o;      o += round_up((size_t)E * 4, 256);
   w.offsets = o;     o += round_up((size_t)(E + 1) * 4, 256);
   w.num_padded = o;  o += 256;
-  w.sorted = o;      o += round_up(align_capacity(S, E, 128) * 4, 256);
+  w.sorted = o;      o += round_up(align_capacity(S, E, 256) * 4, 256);   // the largest block any caller can force
   w.blocks = o;      o += round_up((align_capacity(S, E, 16) / 16 + 1) * 4, 256);
   w.act = o;         o += round_up((size_t)S * N * 2, 256);
   // float32 (combined unrounded); one plane per reduction split (at most 8, small batches only)
@@ -472,8 +476,9 @@ static int layer_impl(const void* X, const int32_t* topk_ids, const float* topk_
   int32_t* blocks = (int32_t*)(base + w.blocks);
   void* act = base + w.act;
   void* Y = base + w.Y;
-  // a forced token tile (tuning hook) also fixes the bucketing block
-  const int block_m = (g_force_mt == 1 || g_force_mt == 2 || g_force_mt == 4 || g_force_mt == 8)
+  // a forced bucketing block wins; a forced token tile (tuning hook) also fixes the block
+  const int block_m = g_force_block_m > 0 ? g_force_block_m
+                      : (g_force_mt == 1 || g_force_mt == 2 || g_force_mt == 4 || g_force_mt == 8)
                           ? 16 * g_force_mt : pick_block_m(S, E);
   const bool ev = g_nevents == 5;
 
@@ -615,6 +620,19 @@ int moe_set_tiles_per_workgroup(int n) {
 int moe_set_reduction_splits(int n) {
   if (n < 0 || n > 64) return fail(MOE_INVALID_ARGUMENT, "reduction splits must be in 0..64");
   g_force_ksplit = n;
+  return MOE_OK;
+}
+
+int moe_set_block_m_override(int block_m) {
+  if (block_m != 0 && !valid_block_m(block_m))
+    return fail(MOE_INVALID_ARGUMENT, "block_m override must be 0, 16, 32, 64, 128 or 256");
+  g_force_block_m = block_m;
+  return MOE_OK;
+}
+
+int moe_last_gemm_plan(int* plan8) {
+  if (!plan8) return fail(MOE_INVALID_ARGUMENT, "null pointer argument");
+  for (int i = 0; i < 8; ++i) plan8[i] = g_last_plan[i];
   return MOE_OK;
 }
 

@@ -117,7 +117,7 @@ GEMM_SHAPES = [
 
 
 @pytest.mark.parametrize("shape", GEMM_SHAPES)
-@pytest.mark.parametrize("block_m", [16, 64])
+@pytest.mark.parametrize("block_m", [16, 64, 256])
 @pytest.mark.parametrize("which", ["w1", "w2"])
 def test_grouped_gemm_matches_oracle(shape, block_m, which):
     cfg = MoEConfig(name="g", seed=5, **shape)
@@ -208,6 +208,30 @@ def test_grouped_gemm_ignores_invalid_slots_and_leaves_rows_untouched():
     cfg = MoEConfig(name="inv", T=30, K=256, N=128, E=4, topk=2, group=128, dtype="f16", seed=6)
     say("gemm with out-of-range expert ids")
     staged_gemm_case(cfg, 16, "w1", corrupt_ids=True)
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("which", ["w1", "w2"])
+def test_grouped_gemm_block_256_register_scales(dtype, which):
+    """256-row bucketing blocks (walked as two 128-row tiles) on the register-scale kernels; each
+    expert owns two blocks, the second one ragged."""
+    cfg = MoEConfig(name="bm256", T=700, K=1024, N=1024, E=3, topk=2, group=128, dtype=dtype, seed=31)
+    say(f"gemm block_m=256 register scales dtype={dtype} {which}")
+    staged_gemm_case(cfg, 256, which)
+    assert M.moe_last_gemm_plan()["mt"] == 8
+
+
+@pytest.mark.parametrize("dtype,group", [("f16", 128), ("bf16", 64)])
+def test_layer_forced_to_block_256(dtype, group):
+    cfg = MoEConfig("bm256_layer", T=400, K=1024, N=1024, E=3, topk=2, group=group, dtype=dtype, seed=32)
+    say(f"layer forced to block_m=256 {cfg}")
+    inp = make_inputs(cfg)
+    M.moe_set_block_m_override(256)
+    try:
+        out = U.run_layer(U.DevInputs(inp))
+    finally:
+        M.moe_set_block_m_override(0)
+    U.assert_close(U.dev_to_f64(out), oracle_layer(inp), "layer block_m 256")
 
 
 # ------------------------------------------------------------------ elementwise steps
@@ -370,9 +394,45 @@ def test_error_paths_report_status():
 
 
 # ------------------------------------------------------------------ full-size seeded configurations
-def sampled_gemm_check(inp, d, which, block_m, nsamples, rng):
-    """Staged GEMM at full size: nsamples (slot, feature) outputs against the oracle's
-    single-entry evaluation of the definition."""
+def stratified_samples(slot_expert, E, block_m, N_out, plan, rng, per_expert=8):
+    """(slot, feature) samples aimed at the borders of the launch's decomposition: for every active
+    expert the first and last row of each of its row blocks (and of each 16*mt-row tile inside a
+    block), paired with features taken in rotation from: column 0, column N_out - 1, and the first
+    and last column of the first and last feature tile of every workgroup's tile group; plus two
+    uniformly random entries per expert."""
+    tile_w = 64 * plan["nt"]
+    group_w = tile_w * plan["tiles_per_workgroup"]
+    cols = {0, N_out - 1}
+    for g0 in range(0, N_out, group_w):
+        g1 = min(g0 + group_w, N_out)
+        last_tile0 = g0 + ((g1 - g0 - 1) // tile_w) * tile_w
+        cols.update({g0, min(g0 + tile_w, g1) - 1, last_tile0, g1 - 1})
+    cols = sorted(cols)
+    rows_per_tile = 16 * plan["mt"]
+    ss, nn = [], []
+    cursor = 0
+    for e in range(E):
+        slots = np.nonzero(slot_expert == e)[0]          # ascending = the order inside the expert's segment
+        if slots.size == 0:
+            continue
+        picks = set()
+        for r0 in range(0, slots.size, min(block_m, rows_per_tile)):
+            picks.update({r0, min(r0 + min(block_m, rows_per_tile), slots.size) - 1})
+        picks = sorted(picks)
+        n_here = max(per_expert - 2, len(picks))
+        for i in range(n_here):
+            ss.append(int(slots[picks[i % len(picks)]]))
+            nn.append(cols[cursor % len(cols)])
+            cursor += 1
+        for _ in range(2):
+            ss.append(int(slots[rng.integers(0, slots.size)]))
+            nn.append(int(rng.integers(0, N_out)))
+    return np.array(ss), np.array(nn), len(cols)
+
+
+def sampled_gemm_check(inp, d, which, block_m, rng):
+    """Staged GEMM at full size, in the tile plan the library picks for it: stratified (slot, feature)
+    outputs against the oracle's single-entry evaluation of the definition."""
     c = inp.cfg
     S = c.S
     al = U.run_align(d.ids, c.E, block_m)
@@ -388,14 +448,13 @@ def sampled_gemm_check(inp, d, which, block_m, nsamples, rng):
     M.moe_w4a16_grouped_gemm(A_dev, row_div, qw, s, z, al["sorted_slot_ids"], al["block_expert_ids"],
                              al["num_padded"], S, c.group, block_m, C)
     torch.cuda.synchronize()
-    ss = rng.integers(0, S, nsamples)
-    nn = rng.integers(0, N_out, nsamples)
-    # always include the corners of the output
-    ss[:4] = [0, 0, S - 1, S - 1]
-    nn[:4] = [0, N_out - 1, 0, N_out - 1]
-    got = U.dev_to_f64(C[torch.from_numpy(ss).cuda(), torch.from_numpy(nn).cuda()])
+    plan = M.moe_last_gemm_plan()
     se = inp.topk_ids.reshape(-1)
-    want = np.empty(nsamples)
+    ss, nn, ncols = stratified_samples(se, c.E, block_m, N_out, plan, rng)
+    say(f"  staged {which}: plan {plan}, {ss.size} samples over {np.unique(se[ss]).size} experts, "
+        f"{ncols} border columns")
+    got = U.dev_to_f64(C[torch.from_numpy(ss).cuda(), torch.from_numpy(nn).cuda()])
+    want = np.empty(ss.size)
     for i, (si, ni) in enumerate(zip(ss, nn)):
         e = int(se[si])
         want[i] = O.gemm_entry(A64, row_div, qw_h[e, ni][None, None], O.decode_bits(s_h[e, ni], c.dtype)[None, None],
@@ -404,31 +463,100 @@ def sampled_gemm_check(inp, d, which, block_m, nsamples, rng):
     del C
 
 
-@pytest.mark.parametrize("name", ["mixtral_decode", "deepseek_decode", "deepseek_prefill", "skewed_bf16"])
-def test_full_size_config(name):
+def tokens_covering_experts(topk_ids, n_tokens, always=()):
+    """Greedy choice of n_tokens tokens whose routed experts are as many distinct ones as possible."""
+    chosen = list(dict.fromkeys(int(t) for t in always))
+    seen = set(int(e) for t in chosen for e in topk_ids[t])
+    while len(chosen) < n_tokens:
+        gain = np.array([len(set(row.tolist()) - seen) for row in topk_ids])
+        gain[chosen] = -1
+        t = int(np.argmax(gain))
+        chosen.append(t)
+        seen.update(int(e) for e in topk_ids[t])
+    return sorted(chosen), len(seen)
+
+
+def prepacked_layer(d):
+    c = d.cfg
+    dtc = M.MOE_F16 if c.dtype == "f16" else M.MOE_BF16
+    p1, p2 = torch.empty_like(d.qw1), torch.empty_like(d.qw2)
+    M.moe_repack_qweight(d.qw1, False, p1)
+    M.moe_repack_qweight(d.qw2, True, p2)
+    ws = torch.empty(M.moe_w4a16_layer_workspace_bytes(c.T, c.K, c.N, c.E, c.topk, dtc), dtype=torch.uint8, device="cuda")
+    out = torch.full((c.T, c.K), float("nan"), dtype=U.TORCH_DT[c.dtype], device="cuda")
+    M.moe_w4a16_layer_prepacked(d.X, d.ids, d.w, p1, d.s1, d.z1, p2, d.s2, d.z2, out, c.group, ws)
+    torch.cuda.synchronize()
+    return out
+
+
+@pytest.mark.parametrize("name", ["mixtral_decode", "skewed_bf16"])
+def test_full_size_config_elementwise(name):
+    """Configurations whose oracle finishes in about a minute: the whole layer output and both staged
+    GEMMs, every element, in the launch configuration the benchmark times."""
     cfg = CONFIGS[name]
-    say(f"full-size {cfg}: generating")
+    say(f"full-size elementwise {cfg}: generating")
+    inp = make_inputs(cfg)
+    d = U.DevInputs(inp)
+    say(f"full-size elementwise {name}: oracle (whole layer with intermediates)")
+    want, mid = oracle_layer(inp, return_intermediates=True)
+    block_m = M.moe_layer_block_m(cfg.T, cfg.E, cfg.topk)
+    al = U.run_align(d.ids, cfg.E, block_m)
+    U.assert_align_equal(al, O.align_by_expert(inp.topk_ids, cfg.E, block_m), block_m)
+    tables = (al["sorted_slot_ids"], al["block_expert_ids"], al["num_padded"])
+    say(f"full-size elementwise {name}: staged gate/up GEMM (block_m={block_m})")
+    H = torch.empty((cfg.S, 2 * cfg.N), dtype=U.TORCH_DT[cfg.dtype], device="cuda")
+    M.moe_w4a16_grouped_gemm(d.X, cfg.topk, d.qw1, d.s1, d.z1, *tables, cfg.S, cfg.group, block_m, H)
+    torch.cuda.synchronize()
+    say(f"  plan {M.moe_last_gemm_plan()}")
+    U.assert_close(U.dev_to_f64(H), mid["H"], f"{name} staged gate/up GEMM, all {H.numel()} outputs")
+    say(f"full-size elementwise {name}: staged SiLU-and-multiply and down GEMM on the oracle's act")
+    act = torch.empty((cfg.S, cfg.N), dtype=U.TORCH_DT[cfg.dtype], device="cuda")
+    M.moe_silu_mul(U.vals_to_dev(mid["H"], cfg.dtype), act)
+    torch.cuda.synchronize()
+    U.assert_close(U.dev_to_f64(act), mid["act"], f"{name} staged silu_mul")
+    Y = torch.empty((cfg.S, cfg.K), dtype=U.TORCH_DT[cfg.dtype], device="cuda")
+    M.moe_w4a16_grouped_gemm(U.vals_to_dev(mid["act"], cfg.dtype), 1, d.qw2, d.s2, d.z2, *tables, cfg.S, cfg.group,
+                             block_m, Y)
+    torch.cuda.synchronize()
+    say(f"  plan {M.moe_last_gemm_plan()}")
+    U.assert_close(U.dev_to_f64(Y), O.rnd(mid["Y"], cfg.dtype), f"{name} staged down GEMM, all {Y.numel()} outputs")
+    say(f"full-size elementwise {name}: layer")
+    got = U.dev_to_f64(U.run_layer(d))
+    say(f"  down-projection plan {M.moe_last_gemm_plan()}")
+    worst = U.assert_close(got, want, f"{name} layer, all {got.size} outputs")
+    say(f"  layer worst error / bound = {worst:.4f}")
+    assert np.array_equal(got, U.dev_to_f64(U.run_layer(d))), "layer is not run-to-run deterministic"
+    if cfg.group == 128 and cfg.K % 1024 == 0 and cfg.N % 1024 == 0:
+        say(f"full-size elementwise {name}: layer on operand-order weights")
+        U.assert_close(U.dev_to_f64(prepacked_layer(d)), want, f"{name} prepacked layer, all outputs")
+
+
+@pytest.mark.parametrize("name,n_tokens", [("deepseek_decode", 16), ("deepseek_prefill", 8)])
+def test_full_size_config_stratified(name, n_tokens):
+    """The two 256-expert configurations (5.9 GB of weights: a full oracle pass is out of reach):
+    staged GEMMs on stratified samples -- every active expert, every row block, the border tiles
+    of every tile group -- and the layer on tokens chosen to cover as many experts as possible."""
+    cfg = CONFIGS[name]
+    say(f"full-size stratified {cfg}: generating")
     inp = make_inputs(cfg)
     d = U.DevInputs(inp)
     rng = np.random.default_rng(123)
     block_m = M.moe_layer_block_m(cfg.T, cfg.E, cfg.topk)
-    say(f"full-size {name}: staged GEMM samples (block_m={block_m})")
-    sampled_gemm_check(inp, d, "w1", block_m, 96, rng)
-    sampled_gemm_check(inp, d, "w2", block_m, 96, rng)
-    say(f"full-size {name}: layer")
-    out = U.run_layer(d)
-    got = U.dev_to_f64(out)
+    say(f"full-size stratified {name}: staged GEMM samples (block_m={block_m})")
+    sampled_gemm_check(inp, d, "w1", block_m, rng)
+    sampled_gemm_check(inp, d, "w2", block_m, rng)
+    say(f"full-size stratified {name}: layer")
+    got = U.dev_to_f64(U.run_layer(d))
     assert np.all(np.isfinite(got))
-    # whole-layer outputs of a few tokens through the oracle's token-subset form
     loads = np.bincount(inp.topk_ids.reshape(-1), minlength=cfg.E)
     hot_expert = int(np.argmax(loads))
     tok_hot = int(np.nonzero((inp.topk_ids == hot_expert).any(axis=1))[0][0])
-    tokens = sorted({0, cfg.T - 1, tok_hot})
-    if cfg.E * cfg.K * cfg.N > 2e9:          # big experts: fewer tokens so the oracle stays in budget
-        tokens = tokens[:2]
-    say(f"full-size {name}: oracle for tokens {tokens}")
+    tokens, n_experts = tokens_covering_experts(inp.topk_ids, n_tokens, always=(0, cfg.T - 1, tok_hot))
+    say(f"full-size stratified {name}: oracle for tokens {tokens} ({n_experts} distinct experts)")
+    assert n_experts >= (100 if n_tokens >= 16 else 48)
     want = oracle_layer(inp, tokens=tokens)
-    U.assert_close(got[tokens], want, f"{name} layer tokens {tokens}")
-    # property that holds at any size: a token routed nowhere new gets the same result twice
-    out2 = U.dev_to_f64(U.run_layer(d))
-    assert np.array_equal(got, out2), "layer is not run-to-run deterministic"
+    worst = U.assert_close(got[tokens], want, f"{name} layer tokens {tokens}")
+    say(f"  layer worst error / bound = {worst:.4f}")
+    assert np.array_equal(got, U.dev_to_f64(U.run_layer(d))), "layer is not run-to-run deterministic"
+    say(f"full-size stratified {name}: layer on operand-order weights, same tokens")
+    U.assert_close(U.dev_to_f64(prepacked_layer(d))[tokens], want, f"{name} prepacked layer tokens {tokens}")
