@@ -158,6 +158,25 @@ int moe_w4a16_layer(const void* X, const int32_t* topk_ids, const float* topk_we
                     moe_dtype dt, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * moe_w4a16_layer for callers that cannot allocate device memory or carry a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments
+ * (minus the workspace), same kernels and same results bit for bit.  The bucketing tables, the
+ * activation between the two GEMMs and the float32 down-projection planes live in a fixed
+ * 64 MiB device array inside the library (one copy per GPU, held until the process ends); the
+ * call performs no allocation of any kind.  Sizes for which
+ * moe_w4a16_layer_workspace_bytes(...) exceeds 64 MiB return MOE_WORKSPACE_TOO_SMALL (the
+ * DeepSeek-shaped decode batch of 128 tokens needs 33 MiB).  The array's address is resolved on
+ * the first call on each device (make that call outside a graph capture).  All calls on one GPU
+ * share the array: calls that overlap on one GPU (different streams or threads) race; calls
+ * ordered on one stream, or serialised by the caller, are safe.
+ */
+int moe_w4a16_layer_noalloc(const void* X, const int32_t* topk_ids, const float* topk_weights,
+                            const int32_t* qw1, const void* s1, const uint8_t* z1,
+                            const int32_t* qw2, const void* s2, const uint8_t* z2,
+                            void* out, int T, int K, int N, int E, int topk, int group_size,
+                            moe_dtype dt, void* stream);
+
+/*
  * Offline weight repack and the layer on repacked weights (the "offline repack into the matrix
  * unit's operand order" that weight-only kernels of this kind use; the paper's kernels move packed
  * weights in their consumption order as well, Fig. 5 / Table III).

@@ -22,6 +22,7 @@ EXPORTS = [
     "moe_repack_qweight", "moe_w4a16_layer_prepacked", "moe_import_awq",
     "fp8_blockwise_gemm_workspace_bytes", "fp8_blockwise_gemm", "fp8_moe_grouped_gemm", "fp8_set_plan_override",
     "fp8_probe_mfma", "moe_set_block_m_override", "moe_last_gemm_plan",
+    "moe_w4a16_layer_noalloc",
 ]
 
 
@@ -102,6 +103,8 @@ def load_library() -> ctypes.CDLL:
     lib.moe_set_reduction_splits.argtypes = [i32]
     lib.moe_layer_block_m.restype = i32
     lib.moe_layer_block_m.argtypes = [i32, i32, i32]
+    lib.moe_w4a16_layer_noalloc.restype = i32
+    lib.moe_w4a16_layer_noalloc.argtypes = [vp] * 10 + [i32] * 7 + [vp]
     lib.moe_set_block_m_override.restype = i32
     lib.moe_set_block_m_override.argtypes = [i32]
     lib.moe_last_gemm_plan.restype = i32
@@ -216,6 +219,16 @@ def moe_w4a16_layer(X, topk_ids, topk_weights, qw1, s1, z1, qw2, s2, z2, out, gr
         _ptr(X), _ptr(topk_ids), _ptr(topk_weights), _ptr(qw1), _ptr(s1), _ptr(z1), _ptr(qw2), _ptr(s2),
         _ptr(z2), _ptr(out), T, K, N2 // 2, E, topk, group_size, _dt(X), _ptr(workspace),
         workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+def moe_w4a16_layer_noalloc(X, topk_ids, topk_weights, qw1, s1, z1, qw2, s2, z2, out, group_size, stream=None) -> None:
+    """moe_w4a16_layer on the library's built-in scratch array: no workspace, no allocation."""
+    T, K = X.shape
+    E, N2, _ = qw1.shape
+    topk = topk_ids.shape[1]
+    _check(load_library().moe_w4a16_layer_noalloc(
+        _ptr(X), _ptr(topk_ids), _ptr(topk_weights), _ptr(qw1), _ptr(s1), _ptr(z1), _ptr(qw2), _ptr(s2),
+        _ptr(z2), _ptr(out), T, K, N2 // 2, E, topk, group_size, _dt(X), _stream(stream)))
 
 
 def moe_w4a16_routed_layer_workspace_bytes(T, K, N, E, topk, dt) -> int:

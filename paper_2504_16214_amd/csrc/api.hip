@@ -535,6 +535,53 @@ int moe_w4a16_layer_prepacked(const void* X, const int32_t* topk_ids, const floa
                     workspace, workspace_bytes, stream, 1);
 }
 
+// ---- the layer for callers that cannot allocate ---------------------------------------------
+// Same kernels as moe_w4a16_layer; the bucketing tables, `act` and the float32 down-projection
+// planes live in a fixed device array of this module instead of a caller workspace.  Every GPU
+// the library runs on holds its own copy of the array (at its own address) until the process ends.
+constexpr size_t kStaticScratchBytes = (size_t)64 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+// Device address of `scratch` on the current device, resolved once per device.  (In host code the
+// array's name is only a handle for hipGetSymbolAddress, never an address to hand to a kernel.)
+static int static_scratch(void** ptr) {
+  constexpr int kMaxDev = 64;
+  static void* ptrs[kMaxDev] = {};
+  int dev = 0;
+  hipError_t err = hipGetDevice(&dev);
+  if (err != hipSuccess) return hip_fail((int)err, "hipGetDevice");
+  if (dev < 0 || dev >= kMaxDev) return fail(MOE_UNSUPPORTED_SHAPE, "device index %d outside [0, %d)", dev, kMaxDev);
+  void* p = __atomic_load_n(&ptrs[dev], __ATOMIC_ACQUIRE);
+  if (!p) {
+    err = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (err != hipSuccess || !p) return hip_fail((int)err, "hipGetSymbolAddress(scratch)");
+    __atomic_store_n(&ptrs[dev], p, __ATOMIC_RELEASE);      // racing first calls resolve the same address
+  }
+  *ptr = p;
+  return MOE_OK;
+}
+
+int moe_w4a16_layer_noalloc(const void* X, const int32_t* topk_ids, const float* topk_weights,
+                            const int32_t* qw1, const void* s1, const uint8_t* z1,
+                            const int32_t* qw2, const void* s2, const uint8_t* z2,
+                            void* out, int T, int K, int N, int E, int topk, int group_size, moe_dtype dt,
+                            void* stream) {
+  if (T < 0 || K < 1 || N < 1 || E < 1 || topk < 1)
+    return fail(MOE_INVALID_ARGUMENT, "need T >= 0 and positive K, N, E, topk, group_size");
+  const size_t need = carve(T, K, N, E, topk).total;
+  if (need > kStaticScratchBytes)
+    return fail(MOE_WORKSPACE_TOO_SMALL,
+                "moe_w4a16_layer_noalloc: these sizes need %zu bytes of scratch, the built-in array holds %zu; "
+                "use moe_w4a16_layer with a caller workspace", need, kStaticScratchBytes);
+  void* ptr = nullptr;
+  const int st = static_scratch(&ptr);
+  if (st != MOE_OK) return st;
+  // nothing in the array has to start at zero: the bucketing kernel writes every table entry it or
+  // the GEMMs read, and act / Y rows are read only for slots whose rows this call wrote
+  return layer_impl(X, topk_ids, topk_weights, qw1, s1, z1, qw2, s2, z2, out, T, K, N, E, topk, group_size, dt,
+                    ptr, kStaticScratchBytes, stream, 0);
+}
+
 int moe_repack_qweight(const int32_t* qweight, int E, int N_out, int K_in, int paired, int32_t* out, void* stream) {
   if (E < 1 || N_out < 1 || K_in < 1) return fail(MOE_INVALID_ARGUMENT, "need positive E, N_out, K_in");
   if (K_in % 128 != 0 || N_out % (paired ? 32 : 16) != 0)
