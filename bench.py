@@ -174,7 +174,7 @@ def main():
         "config": {"workload": f"{cfg.name}: T={cfg.T} K={cfg.K} N={cfg.N} E={cfg.E} top{cfg.topk} "
                                f"g={cfg.group} {cfg.dtype}, seed {cfg.seed}",
                    "active_experts": E_act, "algorithmic_bytes": layer_bytes, "flop": flops,
-                   "block_m": M.moe_layer_block_m(cfg.T, cfg.E, cfg.topk), "tile_override": args.tile or None,
+                   "block_m": M.moe_layer_block_m_for(cfg.T, cfg.K, cfg.N, cfg.E, cfg.topk, cfg.group), "tile_override": args.tile or None,
                    "weights": "operand-order repack (offline)" if args.prepacked else "as stated: [E, rows, K/8] int32"},
         "tflops": round(tflops, 2), "hbm_frac": round(gbs / HBM_PEAK_GBS, 4),
         "mfma_frac": round(tflops / MFMA_PEAK_TFLOPS, 4),

@@ -264,11 +264,18 @@ int moe_w4a16_routed_layer(const void* X, const float* logits, const float* bias
  * moe_set_block_m_override: force the bucketing block of moe_w4a16_layer (16 ... 256) instead of
  * the built-in choice; 0 restores it.  Thread-local.
  *
+ * moe_layer_block_m_for: the same with the layer's shapes known (group-128 layers with
+ * K % 1024 == 0 and N % 1024 == 0 and about 100 or more rows per expert take 128-slot blocks for
+ * the eight-wave tile); honours moe_set_block_m_override.
+ *
+ * moe_set_wide_tiles: 0 = use the eight-wave 128-token tile whenever block_m >= 128 and the shape
+ * allows it (default), 1 = never (the four-wave tiles serve every block size).  Thread-local.
+ *
  * moe_last_gemm_plan: what the last grouped / dense GEMM launch issued from this thread used:
- * plan8 (HOST pointer to 8 ints) = {mt, nt, ks, register_scales, tiles_per_workgroup,
- * reduction_splits, reduction_indices_per_split, fused_silu}.  A workgroup covers 16*mt rows and
- * tiles_per_workgroup consecutive tiles of 64*nt features (32*nt act columns when fused).  Tests
- * use it to aim samples at tile and tile-group borders.
+ * plan9 (HOST pointer to 9 ints) = {mt, nt, ks, register_scales, tiles_per_workgroup,
+ * reduction_splits, reduction_indices_per_split, fused_silu, waves}.  A workgroup covers 16*mt
+ * rows and tiles_per_workgroup consecutive tiles of 16*nt*waves features (half as many act
+ * columns when fused).  Tests use it to aim samples at tile and tile-group borders.
  */
 int moe_set_stage_events(void* const* events, int n);
 
@@ -291,7 +298,9 @@ int moe_set_tiles_per_workgroup(int n);
 int moe_set_reduction_splits(int n);
 int moe_layer_block_m(int T, int E, int topk);
 int moe_set_block_m_override(int block_m);
-int moe_last_gemm_plan(int* plan8);
+int moe_last_gemm_plan(int* plan9);
+int moe_layer_block_m_for(int T, int K, int N, int E, int topk, int group_size);
+int moe_set_wide_tiles(int mode);
 
 #ifdef __cplusplus
 }

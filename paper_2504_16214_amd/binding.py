@@ -22,7 +22,7 @@ EXPORTS = [
     "moe_repack_qweight", "moe_w4a16_layer_prepacked", "moe_import_awq",
     "fp8_blockwise_gemm_workspace_bytes", "fp8_blockwise_gemm", "fp8_moe_grouped_gemm", "fp8_set_plan_override",
     "fp8_probe_mfma", "moe_set_block_m_override", "moe_last_gemm_plan",
-    "moe_w4a16_layer_noalloc",
+    "moe_w4a16_layer_noalloc", "moe_layer_block_m_for", "moe_set_wide_tiles",
 ]
 
 
@@ -105,6 +105,10 @@ def load_library() -> ctypes.CDLL:
     lib.moe_layer_block_m.argtypes = [i32, i32, i32]
     lib.moe_w4a16_layer_noalloc.restype = i32
     lib.moe_w4a16_layer_noalloc.argtypes = [vp] * 10 + [i32] * 7 + [vp]
+    lib.moe_layer_block_m_for.restype = i32
+    lib.moe_layer_block_m_for.argtypes = [i32] * 6
+    lib.moe_set_wide_tiles.restype = i32
+    lib.moe_set_wide_tiles.argtypes = [i32]
     lib.moe_set_block_m_override.restype = i32
     lib.moe_set_block_m_override.argtypes = [i32]
     lib.moe_last_gemm_plan.restype = i32
@@ -314,15 +318,23 @@ def moe_set_tile_override(mt: int, nt: int) -> None:
     _check(load_library().moe_set_tile_override(mt, nt))
 
 
+def moe_layer_block_m_for(T: int, K: int, N: int, E: int, topk: int, group_size: int) -> int:
+    return int(load_library().moe_layer_block_m_for(T, K, N, E, topk, group_size))
+
+
+def moe_set_wide_tiles(mode: int) -> None:
+    _check(load_library().moe_set_wide_tiles(mode))
+
+
 def moe_set_block_m_override(block_m: int) -> None:
     _check(load_library().moe_set_block_m_override(block_m))
 
 
 def moe_last_gemm_plan() -> dict:
     """The tile plan of the last grouped / dense GEMM launched from this thread."""
-    arr = (ctypes.c_int * 8)()
+    arr = (ctypes.c_int * 9)()
     _check(load_library().moe_last_gemm_plan(arr))
-    keys = ("mt", "nt", "ks", "register_scales", "tiles_per_workgroup", "reduction_splits", "k_span", "fused")
+    keys = ("mt", "nt", "ks", "register_scales", "tiles_per_workgroup", "reduction_splits", "k_span", "fused", "waves")
     return dict(zip(keys, (int(v) for v in arr)))
 
 

@@ -10,6 +10,7 @@
 #include "fp8_gemm.hpp"
 #include "gemm_kernel.hpp"
 
+
 namespace moe {
 
 int launch_align(const int32_t*, int, int, int, int, int32_t*, int32_t*, int32_t*, int32_t*, int32_t*,
@@ -26,9 +27,11 @@ int launch_combine(const void*, int, int, const float*, const int32_t*, int, voi
 
 // ---- table of compiled GEMM variants ------------------------------------------------------
 #define MOE_DECL(DT, MT, NT, KS, KW, F, Z) \
-  extern template int launch_w4a16_gemm<DT, MT, NT, KS, KW, F, Z, 0>(const GemmParams&, int, hipStream_t);
+  extern template int launch_w4a16_gemm<DT, MT, NT, KS, KW, F, Z, 0, 4>(const GemmParams&, int, hipStream_t);
 #define MOE_DECL_PRE(DT, MT, NT, KS, F) \
-  extern template int launch_w4a16_gemm<DT, MT, NT, KS, 4, F, 1, 1>(const GemmParams&, int, hipStream_t);
+  extern template int launch_w4a16_gemm<DT, MT, NT, KS, 4, F, 1, 1, 4>(const GemmParams&, int, hipStream_t);
+#define MOE_DECL_WIDE(DT, MT, NT, KS, F) \
+  extern template int launch_w4a16_gemm<DT, MT, NT, KS, 4, F, 1, 2, 8>(const GemmParams&, int, hipStream_t);
 #define MOE_ALL_DT_KW(M, MT, NT, KS, F) \
   M(0, MT, NT, KS, 1, F, 0) M(0, MT, NT, KS, 2, F, 0) M(0, MT, NT, KS, 4, F, 0) \
   M(1, MT, NT, KS, 1, F, 0) M(1, MT, NT, KS, 2, F, 0) M(1, MT, NT, KS, 4, F, 0)
@@ -41,11 +44,17 @@ int launch_combine(const void*, int, int, const float*, const int32_t*, int, voi
 #define MOE_TILE_PRE(MT, NT, KS) MOE_DECL_PRE(0, MT, NT, KS, 0) MOE_DECL_PRE(1, MT, NT, KS, 0)
 #define MOE_TILE_PRE_FUSE(MT, NT, KS) MOE_DECL_PRE(0, MT, NT, KS, 1) MOE_DECL_PRE(1, MT, NT, KS, 1)
 #include "gemm_variants_pre.def"
+#define MOE_TILE_WIDE(MT, NT, KS) MOE_DECL_WIDE(0, MT, NT, KS, 0) MOE_DECL_WIDE(1, MT, NT, KS, 0)
+#define MOE_TILE_WIDE_FUSE(MT, NT, KS) MOE_DECL_WIDE(0, MT, NT, KS, 1) MOE_DECL_WIDE(1, MT, NT, KS, 1)
+#include "gemm_variants_wide.def"
 
 typedef int (*GemmLaunchFn)(const GemmParams&, int, hipStream_t);
-struct GemmVariant { int dt, mt, nt, ks, kw, fuse, szr, pre; GemmLaunchFn fn; };
-#define MOE_ENTRY(DT, MT, NT, KS, KW, F, Z) {DT, MT, NT, KS, KW, F, Z, 0, &launch_w4a16_gemm<DT, MT, NT, KS, KW, F, Z, 0>},
-#define MOE_ENTRY_PRE(DT, MT, NT, KS, F) {DT, MT, NT, KS, 4, F, 1, 1, &launch_w4a16_gemm<DT, MT, NT, KS, 4, F, 1, 1>},
+// pre: 0 = weight tile staged in LDS, 1 = operand-order (repacked) weights, 2 = row-major weights
+// loaded in operand order; wv = wavefronts per workgroup
+struct GemmVariant { int dt, mt, nt, ks, kw, fuse, szr, pre, wv; GemmLaunchFn fn; };
+#define MOE_ENTRY(DT, MT, NT, KS, KW, F, Z) {DT, MT, NT, KS, KW, F, Z, 0, 4, &launch_w4a16_gemm<DT, MT, NT, KS, KW, F, Z, 0, 4>},
+#define MOE_ENTRY_PRE(DT, MT, NT, KS, F) {DT, MT, NT, KS, 4, F, 1, 1, 4, &launch_w4a16_gemm<DT, MT, NT, KS, 4, F, 1, 1, 4>},
+#define MOE_ENTRY_WIDE(DT, MT, NT, KS, F) {DT, MT, NT, KS, 4, F, 1, 2, 8, &launch_w4a16_gemm<DT, MT, NT, KS, 4, F, 1, 2, 8>},
 static const GemmVariant kVariants[] = {
 #define MOE_TILE(MT, NT, KS) MOE_ALL_DT_KW(MOE_ENTRY, MT, NT, KS, 0)
 #define MOE_TILE_FUSE(MT, NT, KS) MOE_ALL_DT_KW(MOE_ENTRY, MT, NT, KS, 1)
@@ -56,11 +65,15 @@ static const GemmVariant kVariants[] = {
 #define MOE_TILE_PRE(MT, NT, KS) MOE_ENTRY_PRE(0, MT, NT, KS, 0) MOE_ENTRY_PRE(1, MT, NT, KS, 0)
 #define MOE_TILE_PRE_FUSE(MT, NT, KS) MOE_ENTRY_PRE(0, MT, NT, KS, 1) MOE_ENTRY_PRE(1, MT, NT, KS, 1)
 #include "gemm_variants_pre.def"
+#define MOE_TILE_WIDE(MT, NT, KS) MOE_ENTRY_WIDE(0, MT, NT, KS, 0) MOE_ENTRY_WIDE(1, MT, NT, KS, 0)
+#define MOE_TILE_WIDE_FUSE(MT, NT, KS) MOE_ENTRY_WIDE(0, MT, NT, KS, 1) MOE_ENTRY_WIDE(1, MT, NT, KS, 1)
+#include "gemm_variants_wide.def"
 };
 
-static const GemmVariant* find_variant(int dt, int mt, int nt, int kw, int fuse, int szr, int pre = 0) {
+static const GemmVariant* find_variant(int dt, int mt, int nt, int kw, int fuse, int szr, int pre = 0, int wv = 4) {
   for (const GemmVariant& v : kVariants)
-    if (v.dt == dt && v.mt == mt && v.nt == nt && v.kw == kw && v.fuse == fuse && v.szr == szr && v.pre == pre)
+    if (v.dt == dt && v.mt == mt && v.nt == nt && v.kw == kw && v.fuse == fuse && v.szr == szr && v.pre == pre &&
+        v.wv == wv)
       return &v;
   return nullptr;
 }
@@ -74,7 +87,8 @@ static thread_local int g_scale_path = 0;   // 0 auto, 1 LDS table, 2 registers
 static thread_local int g_force_tpw = 0;    // feature tiles per workgroup (register-scale kernels), 0 = auto
 static thread_local int g_force_ksplit = 0; // reduction splits of the layer's down projection, 0 = auto
 static thread_local int g_force_block_m = 0; // bucketing block of the layer, 0 = auto
-static thread_local int g_last_plan[8] = {0, 0, 0, 0, 0, 0, 0, 0};   // what the last grouped GEMM launch used
+static thread_local int g_wide_mode = 0;     // eight-wave 128-token tiles: 0 = when the shape allows, 1 = never
+static thread_local int g_last_plan[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};   // what the last grouped GEMM launch used
 
 static int fail(int status, const char* fmt, ...) {
   va_list ap;
@@ -99,6 +113,12 @@ constexpr int kMaxGroups = 512;
 static size_t gemm_lds_bytes(int mt, int nt, int ks, int G, int szr) {
   const size_t M_T = 16 * mt, NW = 16 * nt;
   return kXBufs(mt, ks) * M_T * (ks * 2 + kXRowPad) + 4 * NW * (ks / 2 + kWRowPad(ks)) + (szr ? 0 : (size_t)G * 64 * nt * 4) + M_T * 4;
+}
+
+// The eight-wave 128-token tile serves 128-slot blocks of register-scale shapes in the stated
+// weight layout (group 128, 16-byte aligned scale rows).
+static bool wide_tile_usable(int block_m, int szr_ok, int pre) {
+  return block_m >= 128 && szr_ok && !pre && g_wide_mode != 1 && g_force_mt == 0 && g_force_nt == 0;
 }
 
 // Tile choice.  Tokens per tile follow the bucketing block; the feature width per workgroup is
@@ -186,10 +206,14 @@ static int run_gemm(const GemmArgs& a, hipStream_t stream) {
   if (a.pre && (!szr_ok || (!fuse && a.N_out % 32 != 0)))
     return fail(MOE_UNSUPPORTED_SHAPE, "operand-order weights need group_size 128, K_in %% 1024 == 0, 16-byte aligned "
                 "scale rows and (down projection) N_out %% 32 == 0");
-  if (choose_tile(a.num_slots, a.E, feat, G, a.block_m, fuse, szr_ok, a.dt, a.pre, mt, nt, ks, szr) != 0)
+  int wv = 4, pre = a.pre;
+  if (wide_tile_usable(a.block_m, szr_ok, a.pre) && find_variant(a.dt, 8, 2, 4, fuse, 1, 2, 8)) {
+    mt = 8; nt = 2; ks = 128; szr = 1; wv = 8; pre = 2;
+  } else if (choose_tile(a.num_slots, a.E, feat, G, a.block_m, fuse, szr_ok, a.dt, a.pre, mt, nt, ks, szr) != 0) {
     return fail(MOE_UNSUPPORTED_SHAPE, "no GEMM tile fits (K_in/group_size = %d, block_m = %d, override %d/%d)",
                 G, a.block_m, g_force_mt, g_force_nt);
-  const GemmVariant* v = find_variant(a.dt, mt, nt, kw, fuse, szr, a.pre);
+  }
+  const GemmVariant* v = find_variant(a.dt, mt, nt, kw, fuse, szr, pre, wv);
   if (!v) return fail(MOE_UNSUPPORTED_SHAPE, "GEMM variant mt=%d nt=%d kw=%d fuse=%d szr=%d is not compiled", mt, nt, kw, fuse, szr);
 
   GemmParams p;
@@ -198,7 +222,7 @@ static int run_gemm(const GemmArgs& a, hipStream_t stream) {
   p.sorted_slot_ids = a.sorted_slot_ids; p.block_expert_ids = a.block_expert_ids; p.num_padded = a.num_padded;
   p.num_slots = a.num_slots; p.E = a.E; p.N_out = a.N_out; p.K_in = a.K_in; p.group = a.group;
   p.block_m = a.block_m; p.C = a.C; p.ldc = a.ldc;
-  const int fpw = fuse ? 32 * nt : 64 * nt;
+  const int fpw = (fuse ? 8 : 16) * nt * wv;     // features (act columns when fused) per workgroup tile
   p.n_tiles = (feat + fpw - 1) / fpw;
   p.G = G;
   p.cpg = a.group / (32 * kw);
@@ -239,16 +263,26 @@ static int run_gemm(const GemmArgs& a, hipStream_t stream) {
   if (grid > 0x7fffffffLL) return fail(MOE_UNSUPPORTED_SHAPE, "grid too large");
   g_last_plan[0] = mt; g_last_plan[1] = nt; g_last_plan[2] = ks; g_last_plan[3] = szr;
   g_last_plan[4] = tpw; g_last_plan[5] = ksp; g_last_plan[6] = kspan; g_last_plan[7] = fuse;
+  g_last_plan[8] = wv;
   const int err = v->fn(p, (int)grid, stream);
   if (err != 0) return hip_fail(err, "grouped GEMM launch");
   return MOE_OK;
 }
 
-static int pick_block_m(long long S, int E) {
+static int pick_block_m(long long S, int E, bool wide_ok = false) {
   const long long avg = S / (E > 0 ? E : 1);
   if (avg <= 8) return 16;
   if (avg <= 24) return 32;
-  return 64;     // 64-slot tiles at two workgroups per CU beat 128-slot tiles (measured)
+  // 128-slot blocks only for the eight-wave tile (every unpacked weight feeds eight matrix
+  // instructions); the four-wave 128-slot tiles run one workgroup per CU and lose to 64-slot ones
+  if (wide_ok && avg >= 96) return 128;
+  return 64;
+}
+
+// Can both projections of a layer run on the eight-wave tile?  (group 128, whole 8-group scale
+// panels in K and N; pointer alignment is checked again at launch)
+static bool layer_wide_ok(int K, int N, int group_size) {
+  return group_size == 128 && K % 1024 == 0 && N % 1024 == 0 && g_wide_mode != 1 && g_force_mt == 0 && g_force_nt == 0;
 }
 
 // Reduction splits of the layer's down projection.  With few experts and few rows the launch has
@@ -440,6 +474,12 @@ int moe_layer_block_m(int T, int E, int topk) {
   return pick_block_m((long long)T * topk, E);
 }
 
+int moe_layer_block_m_for(int T, int K, int N, int E, int topk, int group_size) {
+  if (T < 0 || K < 1 || N < 1 || E < 1 || topk < 1 || group_size < 1) return 0;
+  if (g_force_block_m > 0) return g_force_block_m;
+  return pick_block_m((long long)T * topk, E, layer_wide_ok(K, N, group_size));
+}
+
 }  // extern "C"
 
 static int layer_impl(const void* X, const int32_t* topk_ids, const float* topk_weights,
@@ -479,7 +519,7 @@ static int layer_impl(const void* X, const int32_t* topk_ids, const float* topk_
   // a forced bucketing block wins; a forced token tile (tuning hook) also fixes the block
   const int block_m = g_force_block_m > 0 ? g_force_block_m
                       : (g_force_mt == 1 || g_force_mt == 2 || g_force_mt == 4 || g_force_mt == 8)
-                          ? 16 * g_force_mt : pick_block_m(S, E);
+                          ? 16 * g_force_mt : pick_block_m(S, E, !pre && layer_wide_ok(K, N, group_size));
   const bool ev = g_nevents == 5;
 
   if (ev) (void)hipEventRecord((hipEvent_t)g_events[0], stream);
@@ -677,9 +717,15 @@ int moe_set_block_m_override(int block_m) {
   return MOE_OK;
 }
 
-int moe_last_gemm_plan(int* plan8) {
-  if (!plan8) return fail(MOE_INVALID_ARGUMENT, "null pointer argument");
-  for (int i = 0; i < 8; ++i) plan8[i] = g_last_plan[i];
+int moe_last_gemm_plan(int* plan9) {
+  if (!plan9) return fail(MOE_INVALID_ARGUMENT, "null pointer argument");
+  for (int i = 0; i < 9; ++i) plan9[i] = g_last_plan[i];
+  return MOE_OK;
+}
+
+int moe_set_wide_tiles(int mode) {
+  if (mode < 0 || mode > 1) return fail(MOE_INVALID_ARGUMENT, "wide tile mode must be 0 (when usable) or 1 (never)");
+  g_wide_mode = mode;
   return MOE_OK;
 }
 

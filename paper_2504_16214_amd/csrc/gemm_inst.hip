@@ -11,10 +11,10 @@
 
 namespace moe {
 
-template <int DT, int MT, int NT, int KS, int KW, int FUSE, int SZR, int PRE>
+template <int DT, int MT, int NT, int KS, int KW, int FUSE, int SZR, int PRE, int WV>
 int launch_w4a16_gemm(const GemmParams& p, int grid, hipStream_t stream) {
-  auto kern = w4a16_gemm_kernel<DT, MT, NT, KS, KW, FUSE, SZR, PRE>;
-  const size_t lds = TileGeom<MT, NT, KS>::lds_bytes(p.G, SZR, PRE);
+  auto kern = w4a16_gemm_kernel<DT, MT, NT, KS, KW, FUSE, SZR, PRE, WV>;
+  const size_t lds = TileGeom<MT, NT, KS, WV>::lds_bytes(p.G, SZR, PRE);
   if (lds > 64 * 1024) {
     // Raise the dynamic LDS limit of this kernel, once per device and size (the attribute is
     // per device; remembering it per device keeps a second GPU of the process correct).
@@ -30,34 +30,44 @@ int launch_w4a16_gemm(const GemmParams& p, int grid, hipStream_t stream) {
       if (dev >= 0 && dev < kMaxDev) lds_allowed[dev] = lds;
     }
   }
-  hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, stream, p);
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * WV), lds, stream, p);
   return (int)hipGetLastError();
 }
 
-#ifndef MOE_PRE
+#if !defined(MOE_PRE) && !defined(MOE_WIDE)
 #define MOE_TILE(MT, NT, KS) \
-  template int launch_w4a16_gemm<MOE_DT, MT, NT, KS, MOE_KW, 0, 0, 0>(const GemmParams&, int, hipStream_t);
+  template int launch_w4a16_gemm<MOE_DT, MT, NT, KS, MOE_KW, 0, 0, 0, 4>(const GemmParams&, int, hipStream_t);
 #define MOE_TILE_FUSE(MT, NT, KS) \
-  template int launch_w4a16_gemm<MOE_DT, MT, NT, KS, MOE_KW, 1, 0, 0>(const GemmParams&, int, hipStream_t);
+  template int launch_w4a16_gemm<MOE_DT, MT, NT, KS, MOE_KW, 1, 0, 0, 4>(const GemmParams&, int, hipStream_t);
 #include "gemm_variants.def"
 
 // register-resident scale variants: group 128 only (KW == 4), small token tiles
 #if MOE_KW == 4
 #define MOE_TILE_SZR(MT, NT, KS) \
-  template int launch_w4a16_gemm<MOE_DT, MT, NT, KS, 4, 0, 1, 0>(const GemmParams&, int, hipStream_t);
+  template int launch_w4a16_gemm<MOE_DT, MT, NT, KS, 4, 0, 1, 0, 4>(const GemmParams&, int, hipStream_t);
 #define MOE_TILE_SZR_FUSE(MT, NT, KS) \
-  template int launch_w4a16_gemm<MOE_DT, MT, NT, KS, 4, 1, 1, 0>(const GemmParams&, int, hipStream_t);
+  template int launch_w4a16_gemm<MOE_DT, MT, NT, KS, 4, 1, 1, 0, 4>(const GemmParams&, int, hipStream_t);
 #include "gemm_variants_szr.def"
 #endif
-#endif  // !MOE_PRE
+#endif  // !MOE_PRE && !MOE_WIDE
 
 // operand-order (prepacked) weights: own translation unit (-DMOE_PRE) so it builds in parallel
 #if defined(MOE_PRE) && MOE_KW == 4
 #define MOE_TILE_PRE(MT, NT, KS) \
-  template int launch_w4a16_gemm<MOE_DT, MT, NT, KS, 4, 0, 1, 1>(const GemmParams&, int, hipStream_t);
+  template int launch_w4a16_gemm<MOE_DT, MT, NT, KS, 4, 0, 1, 1, 4>(const GemmParams&, int, hipStream_t);
 #define MOE_TILE_PRE_FUSE(MT, NT, KS) \
-  template int launch_w4a16_gemm<MOE_DT, MT, NT, KS, 4, 1, 1, 1>(const GemmParams&, int, hipStream_t);
+  template int launch_w4a16_gemm<MOE_DT, MT, NT, KS, 4, 1, 1, 1, 4>(const GemmParams&, int, hipStream_t);
 #include "gemm_variants_pre.def"
+#endif
+
+// eight-wave workgroups on row-major weights loaded in operand order (large token tiles, group 128):
+// own translation unit (-DMOE_WIDE)
+#if defined(MOE_WIDE) && MOE_KW == 4
+#define MOE_TILE_WIDE(MT, NT, KS) \
+  template int launch_w4a16_gemm<MOE_DT, MT, NT, KS, 4, 0, 1, 2, 8>(const GemmParams&, int, hipStream_t);
+#define MOE_TILE_WIDE_FUSE(MT, NT, KS) \
+  template int launch_w4a16_gemm<MOE_DT, MT, NT, KS, 4, 1, 1, 2, 8>(const GemmParams&, int, hipStream_t);
+#include "gemm_variants_wide.def"
 #endif
 
 }  // namespace moe

@@ -295,15 +295,16 @@ constexpr int kWRowPad(int ks) { return ks >= 512 ? 16 : 32; }   // 512-k stages
 // activation tile buffers in LDS per token-tile size (see TileGeom::XBUFS)
 constexpr int kXBufs(int mt, int ks) { return (mt == 2 || ks >= 512) ? 1 : 2; }
 
-template <int MT, int NT, int KS>
+template <int MT, int NT, int KS, int WV = 4>
 struct TileGeom {
+  static constexpr int THREADS = 64 * WV;    // WV wavefronts per workgroup (4, or 8 for the widest tiles)
   static constexpr int M_T = 16 * MT;        // slots per workgroup tile
   static constexpr int NW = 16 * NT;         // features per wave
-  static constexpr int N_T = 4 * NW;         // features per workgroup
+  static constexpr int N_T = WV * NW;        // features per workgroup
   static constexpr int XP = KS * 2 + kXRowPad;   // LDS bytes per activation row (padded)
   static constexpr int WP = KS / 2 + kWRowPad(KS);   // LDS bytes per packed weight row (padded)
   static constexpr int CPR = KS / 8;         // 16-byte chunks per activation row
-  static constexpr int RPP = 256 / CPR;      // activation rows per cooperative pass
+  static constexpr int RPP = THREADS / CPR;  // activation rows per cooperative pass
   static constexpr int XPASS = M_T / RPP;    // passes per stage
   static constexpr int LPR = KS / 32;        // lanes covering one weight row (16 B each)
   static constexpr int RPI = 64 / LPR;       // weight rows per wave load instruction
@@ -313,7 +314,7 @@ struct TileGeom {
   // buffer (two barriers per stage) is what lets a third workgroup fit on a CU.
   static constexpr int XBUFS = kXBufs(MT, KS);
   static size_t lds_bytes(int G, int szr, int pre = 0) {
-    return (size_t)XBUFS * M_T * XP + (pre ? 0 : (size_t)4 * NW * WP) + (szr ? 0 : (size_t)G * N_T * 4) +
+    return (size_t)XBUFS * M_T * XP + (pre ? 0 : (size_t)WV * NW * WP) + (szr ? 0 : (size_t)G * N_T * 4) +
            (size_t)M_T * 4;
   }
 };
@@ -325,10 +326,10 @@ struct TileGeom {
 //           instruction: full 128-byte lines per row for float32 output.
 //   fused SiLU-and-multiply: wave-local sub-tiles alternate gate, up; the pair (2p, 2p+1)
 //   covers act columns c..c+15 with weight rows c (gate) and N + c (up).
-template <int NT, int FUSE>
+template <int NT, int FUSE, int WV = 4>
 __device__ __forceinline__ void feature_of(int n_tile, int wave, int sub, int n, const GemmParams& p,
                                            int& wrow, int& ocol, bool& valid) {
-  constexpr int NW = 16 * NT, N_T = 4 * NW;
+  constexpr int NW = 16 * NT, N_T = WV * NW;
   if constexpr (FUSE == 0) {
     const int f = NT == 1 ? n_tile * N_T + wave * NW + n
                           : n_tile * N_T + wave * NW + (sub >> 1) * 32 + 2 * n + (sub & 1);
@@ -351,12 +352,22 @@ __device__ __forceinline__ void feature_of(int n_tile, int wave, int sub, int n,
 // contiguous for the fused gate/up GEMM, even/odd pairs of 32 rows otherwise).  A wave then loads
 // its operand words fully coalesced straight into registers: no weight tile in LDS, one per-lane
 // offset (lane * 16) for every weight load.  Register-scale kernels only.
-template <int DT, int MT, int NT, int KS, int KW, int FUSE, int SZR, int PRE = 0>
-__global__ void __launch_bounds__(256, ((MT * NT <= 4 || (SZR && MT <= 4)) ? 2 : 1))
+//
+// PRE = 2: `qweight` is in the stated row-major layout, but a wave still loads its operand words
+// straight into registers (a load instruction covers 16 rows x 64 bytes): no weight tile in LDS.
+// Only for large token tiles, whose weights mostly come from L2 (the row blocks of an expert
+// re-read them); from HBM this access shape is slower than 128-byte row segments.
+//
+// WV = 8: eight wavefronts per workgroup (two per SIMD) share one activation tile; wave w owns
+// features [w*16*NT, (w+1)*16*NT) of a tile of 128*NT features.
+template <int DT, int MT, int NT, int KS, int KW, int FUSE, int SZR, int PRE = 0, int WV = 4>
+__global__ void __launch_bounds__(64 * WV, (WV == 8 ? 1 : ((MT * NT <= 4 || (SZR && MT <= 4) || (PRE == 2 && NT <= 2)) ? 2 : 1)))
 w4a16_gemm_kernel(const GemmParams p) {
   static_assert(SZR == 0 || KW == 4, "register-resident scales need 128-k chunk-steps (group 128)");
   static_assert(PRE == 0 || (SZR == 1 && (FUSE == 1 || NT >= 2)), "operand-order weights: register-scale, paired tiles");
-  using G_ = TileGeom<MT, NT, KS>;
+  static_assert(WV == 4 || (WV == 8 && SZR == 1), "eight-wave workgroups: register-scale kernels only");
+  using G_ = TileGeom<MT, NT, KS, WV>;
+  constexpr int THREADS = G_::THREADS;
   constexpr int M_T = G_::M_T, NW = G_::NW, N_T = G_::N_T, XP = G_::XP, WP = G_::WP;
   constexpr int CPR = G_::CPR, RPP = G_::RPP, XPASS = G_::XPASS;
   constexpr int LPR = G_::LPR, RPI = G_::RPI, WPASS = G_::WPASS;
@@ -381,8 +392,8 @@ w4a16_gemm_kernel(const GemmParams p) {
   extern __shared__ __align__(16) unsigned char smem[];
   unsigned char* xs = smem;                                        // [2][M_T][XP]
   constexpr int XBUFS = G_::XBUFS;
-  unsigned char* ws_all = xs + XBUFS * M_T * XP;                   // [4][NW][WP] (absent when PRE)
-  uint32_t* sz = reinterpret_cast<uint32_t*>(ws_all + (PRE ? 0 : 4 * NW * WP));  // [G][N_T] (absent when SZR)
+  unsigned char* ws_all = xs + XBUFS * M_T * XP;                   // [WV][NW][WP] (absent when PRE)
+  uint32_t* sz = reinterpret_cast<uint32_t*>(ws_all + (PRE ? 0 : WV * NW * WP));  // [G][N_T] (absent when SZR)
   int* slot_s = reinterpret_cast<int*>(sz + (SZR ? 0 : p.G * N_T));  // [M_T]
 
   // A workgroup owns one block of M_T slots and `tiles_per_wg` consecutive feature tiles; it
@@ -436,11 +447,11 @@ w4a16_gemm_kernel(const GemmParams p) {
   // (operand-order layout: the k0 / 128 leading blocks of a row set are 1 KiB each)
   const unsigned char* const wbase = reinterpret_cast<const unsigned char*>(p.qweight) +
                                      (size_t)e * p.N_out * (size_t)(K_in >> 1) +
-                                     (PRE ? (size_t)(k0 >> 7) * 1024 : (size_t)(k0 >> 1));
+                                     (PRE == 1 ? (size_t)(k0 >> 7) * 1024 : (size_t)(k0 >> 1));
   uint32_t woff[WPASS];      // rows of the tile the LOAD cursor is in
   const int wl_row = lane / LPR, wl_chunk = lane % LPR;
   auto set_w_rows = [&](int tile) __attribute__((always_inline)) {
-    if constexpr (PRE) {
+    if constexpr (PRE == 1) {
       // load q = s * UCH + u fetches chunk-step u of the stage for sub-tile s: block of the
       // sub-tile's row set, 1 KiB per chunk-step, the lane's own 16 bytes
 #pragma unroll
@@ -448,10 +459,20 @@ w4a16_gemm_kernel(const GemmParams p) {
         const int sub = q / UCH;
         int wrow, ocol;
         bool ok;
-        feature_of<NT, FUSE>(tile, wave, sub, 0, p, wrow, ocol, ok);
+        feature_of<NT, FUSE, WV>(tile, wave, sub, 0, p, wrow, ocol, ok);
         if (!ok) wrow = 0;
         const uint32_t blk = FUSE ? (uint32_t)wrow >> 4 : (((uint32_t)wrow >> 5) << 1) | (uint32_t)(sub & 1);
         woff[q] = (blk * (uint32_t)(K_in >> 7) + (uint32_t)(q % UCH)) * 1024u + (uint32_t)(lane * 16);
+      }
+    } else if constexpr (PRE == 2) {
+      // row-major weights in operand order: lane (n, j) fetches bytes [64u + 16j, +16) of row n of sub-tile s
+#pragma unroll
+      for (int q = 0; q < WPASS; ++q) {
+        int wrow, ocol;
+        bool ok;
+        feature_of<NT, FUSE, WV>(tile, wave, q / UCH, ln, p, wrow, ocol, ok);
+        if (!ok) wrow = 0;
+        woff[q] = (uint32_t)wrow * (uint32_t)(K_in >> 1) + (uint32_t)((q % UCH) * 64 + lj * 16);
       }
     } else {
 #pragma unroll
@@ -459,7 +480,7 @@ w4a16_gemm_kernel(const GemmParams p) {
         const int rw = q * RPI + wl_row;
         int wrow, ocol;
         bool ok;
-        feature_of<NT, FUSE>(tile, wave, rw >> 4, rw & 15, p, wrow, ocol, ok);
+        feature_of<NT, FUSE, WV>(tile, wave, rw >> 4, rw & 15, p, wrow, ocol, ok);
         if (!ok) wrow = 0;
         woff[q] = (uint32_t)wrow * (uint32_t)(K_in >> 1) + (uint32_t)(wl_chunk * 16);
       }
@@ -492,10 +513,14 @@ w4a16_gemm_kernel(const GemmParams p) {
   // (512-k stages -- 256-byte row segments, one stage ahead, single activation buffer, three
   // workgroups per CU -- were measured 3-5 % slower than 256-k stages on the decode shapes; the
   // geometry below still covers them)
+  // (two stages ahead for the large tiles as well was measured 1-2 % slower: their stalls are not load latency)
   constexpr int PDW = (MT >= 4 || KS >= 512) ? 1 : 2;
   constexpr int PDX = (MT >= 4 || XBUFS == 1) ? 1 : 2;
   static_assert(UNR % PDW == 0 && UNR % PDX == 0, "ring slots must repeat with the unrolled trip");
   u32x4 xr[PDX][XPASS], wr[PDW][WPASS];
+  // activation passes that carry live rows: all of them here; the main loop of the 128-slot
+  // eight-wave tile is specialised on its live 16-row sub-tiles and shadows this constant
+  constexpr int XLIVE = XPASS;
   // A stage past the end still issues its loads (onto the last stage, which was just fetched) so
   // the loop body is branch-free and the compiler can count the outstanding loads exactly.
   // The per-lane offsets pass through an empty asm so that they stay opaque 32-bit VGPR values:
@@ -504,7 +529,7 @@ w4a16_gemm_kernel(const GemmParams p) {
 #define MOE_LOAD_W(ST, WV)                                                                      \
   {                                                                                             \
     const int stc_ = (ST) < nst ? (ST) : nst - 1;                                               \
-    const unsigned char* wb_ = wbase + (size_t)stc_ * (PRE ? UCH * 1024 : KS / 2);              \
+    const unsigned char* wb_ = wbase + (size_t)stc_ * (PRE == 1 ? UCH * 1024 : KS / 2);         \
     uint32_t wsub_ = 0;                                                                         \
     if (has_tail && stc_ == nst - 1) wsub_ = wback;                                             \
     _Pragma("unroll") for (int q = 0; q < WPASS; ++q) {                                         \
@@ -518,7 +543,7 @@ w4a16_gemm_kernel(const GemmParams p) {
     const unsigned char* xb_ = xbase + (size_t)stc_ * (KS * 2);                                 \
     uint32_t xsub_ = 0;                                                                         \
     if (has_tail && stc_ == nst - 1) xsub_ = xback;                                             \
-    _Pragma("unroll") for (int ps = 0; ps < XPASS; ++ps) {                                      \
+    _Pragma("unroll") for (int ps = 0; ps < XLIVE; ++ps) {                                      \
       asm("" : "+v"(xoff[ps]));                                                                 \
       XV[ps] = *reinterpret_cast<const u32x4*>(xb_ + (xoff[ps] - xsub_));                       \
     }                                                                                           \
@@ -532,7 +557,7 @@ w4a16_gemm_kernel(const GemmParams p) {
             t_;                                                                                 \
       }                                                                                         \
     }                                                                                           \
-    _Pragma("unroll") for (int ps = 0; ps < XPASS; ++ps)                                        \
+    _Pragma("unroll") for (int ps = 0; ps < XLIVE; ++ps)                                        \
         *reinterpret_cast<u32x4*>((XBUF) + (ps * RPP + xr_row) * XP + xw_pos * 16) =            \
             interleave8(XV[ps]);                                                                \
   }
@@ -554,7 +579,8 @@ w4a16_gemm_kernel(const GemmParams p) {
       } else { /* past the last tile: re-read row 0 of the expert; the lane keeps its own  */ \
                /* chunk offset so that subtracting wback (<= wl_chunk*16) cannot underflow  */ \
         _Pragma("unroll") for (int q = 0; q < WPASS; ++q)                                   \
-            woff[q] = PRE ? (uint32_t)((q % UCH) * 1024 + lane * 16) : (uint32_t)(wl_chunk * 16); \
+            woff[q] = PRE == 1 ? (uint32_t)((q % UCH) * 1024 + lane * 16)                   \
+                      : PRE == 2 ? (uint32_t)((q % UCH) * 64 + lj * 16) : (uint32_t)(wl_chunk * 16); \
       }                                                             \
     }                                                               \
   }
@@ -612,7 +638,7 @@ w4a16_gemm_kernel(const GemmParams p) {
     for (int s = 0; s < NT; ++s) {
       int wrow, ocol;
       bool ok;
-      feature_of<NT, FUSE>(tile, wave, s, ln, p, wrow, ocol, ok);
+      feature_of<NT, FUSE, WV>(tile, wave, s, ln, p, wrow, ocol, ok);
       if (!ok) wrow = 0;
       sz_row[s] = ((uint32_t)e * (uint32_t)p.N_out + (uint32_t)wrow) * (uint32_t)p.G + (uint32_t)(k0 / 128);
     }
@@ -631,11 +657,11 @@ w4a16_gemm_kernel(const GemmParams p) {
   if constexpr (!SZR) {
     const uint16_t* sc = reinterpret_cast<const uint16_t*>(p.scales);
     const int G = p.G, G8 = (G + 7) >> 3;
-    for (int idx = tid; idx < N_T * G8; idx += 256) {
+    for (int idx = tid; idx < N_T * G8; idx += THREADS) {
       const int lf = idx % N_T, gb = (idx / N_T) * 8;
       int wrow, ocol;
       bool ok;
-      feature_of<NT, FUSE>(tile0, lf / NW, (lf % NW) >> 4, lf & 15, p, wrow, ocol, ok);
+      feature_of<NT, FUSE, WV>(tile0, lf / NW, (lf % NW) >> 4, lf & 15, p, wrow, ocol, ok);
       uint16_t sv[8];
       uint8_t zv[8];
       if (!ok) wrow = 0;      // fetched but never used: the row's outputs are not stored
@@ -664,9 +690,29 @@ w4a16_gemm_kernel(const GemmParams p) {
     }
   }
 
-  floatx4_t acc[MT][NT];
+  // Live 16-row sub-tiles of this tile.  The slots of a block are packed at its front, so the
+  // count follows from the first row of every sub-tile (workgroup-uniform scalar loads).  The
+  // eight-wave tile runs a main loop compiled for exactly that many sub-tiles: padding sub-tiles
+  // cost no matrix instruction, no rescale, no LDS traffic (the weights' unpack is shared by all
+  // live sub-tiles and is what the large tile amortises).
+  constexpr bool SPEC = PRE == 2 && MT == 8;
+  int live = MT;
+  if constexpr (SPEC) {
+    live = 0;
 #pragma unroll
-  for (int mt = 0; mt < MT; ++mt)
+    for (int mt = 0; mt < MT; ++mt) {
+      const int sl = slot_at(row0 + 16 * mt);
+      live += (sl >= 0 && sl < p.num_slots) ? 1 : 0;
+    }
+    live = __builtin_amdgcn_readfirstlane(live);      // uniform by construction: keep the dispatch a scalar branch
+  }
+
+  auto tile_body = [&](auto mlc) __attribute__((always_inline)) {
+  constexpr int ML = decltype(mlc)::value;               // live sub-tiles this instance computes
+  constexpr int XLIVE = (16 * ML + RPP - 1) / RPP;       // activation passes that hold them
+  floatx4_t acc[ML][NT];
+#pragma unroll
+  for (int mt = 0; mt < ML; ++mt)
 #pragma unroll
     for (int s = 0; s < NT; ++s) acc[mt][s] = floatx4_t{0.f, 0.f, 0.f, 0.f};
   float unit[NT];      // RS: scale the accumulator of each sub-tile is currently expressed in
@@ -735,26 +781,26 @@ w4a16_gemm_kernel(const GemmParams p) {
         // activation fragments one packed word ahead of the MFMAs that use them (the reads of
         // word i+1 are in flight while word i multiplies), so the LDS latency is not exposed
         // MT times per word
-        u32x4 a_nxt[MT];
+        u32x4 a_nxt[ML];
+#define MOE_AREAD(MT_, OFF_) *reinterpret_cast<const u32x4*>(xbuf + ((MT_) * 16 + ln) * XP + 16 * (OFF_))
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
-          a_nxt[mt] = *reinterpret_cast<const u32x4*>(xbuf + (mt * 16 + ln) * XP + 16 * (4 * KW * u + lj));
+        for (int mt = 0; mt < ML; ++mt)
+          a_nxt[mt] = MOE_AREAD(mt, 4 * KW * u + lj);
 #pragma unroll
         for (int i = 0; i < KW; ++i) {
-          u32x4 a_cur[MT];
+          u32x4 a_cur[ML];
 #pragma unroll
-          for (int mt = 0; mt < MT; ++mt) a_cur[mt] = a_nxt[mt];
+          for (int mt = 0; mt < ML; ++mt) a_cur[mt] = a_nxt[mt];
           if (i + 1 < KW) {
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt)
-              a_nxt[mt] = *reinterpret_cast<const u32x4*>(
-                  xbuf + (mt * 16 + ln) * XP + 16 * (4 * KW * u + lj + 4 * (i + 1)));
+            for (int mt = 0; mt < ML; ++mt)
+              a_nxt[mt] = MOE_AREAD(mt, 4 * KW * u + lj + 4 * (i + 1));
           }
           u32x4 b[NT];
 #pragma unroll
           for (int s = 0; s < NT; ++s) b[s] = dequant_word<DT, ZM>(wv[s].w[i], ctx[s], uk);
 #pragma unroll
-          for (int mt = 0; mt < MT; ++mt) {
+          for (int mt = 0; mt < ML; ++mt) {
             const u32x4 a = a_cur[mt];
 #pragma unroll
             for (int s = 0; s < NT; ++s) {
@@ -773,14 +819,14 @@ w4a16_gemm_kernel(const GemmParams p) {
           }
         }
       } else {
-        floatx4_t part[MT][NT];
+        floatx4_t part[ML][NT];
 #pragma unroll
         for (int i = 0; i < KW; ++i) {
           u32x4 b[NT];
 #pragma unroll
           for (int s = 0; s < NT; ++s) b[s] = dequant_word<DT, ZM>(wv[s].w[i], ctx[s], uk);
 #pragma unroll
-          for (int mt = 0; mt < MT; ++mt) {
+          for (int mt = 0; mt < ML; ++mt) {
             const u32x4 a = *reinterpret_cast<const u32x4*>(
                 xbuf + (mt * 16 + ln) * XP + 16 * (4 * KW * u + lj + 4 * i));
 #pragma unroll
@@ -795,7 +841,7 @@ w4a16_gemm_kernel(const GemmParams p) {
 #pragma unroll
         for (int s = 0; s < NT; ++s) {
 #pragma unroll
-          for (int mt = 0; mt < MT; ++mt)
+          for (int mt = 0; mt < ML; ++mt)
 #pragma unroll
             for (int i = 0; i < 4; ++i) acc[mt][s][i] = __builtin_fmaf(scl[s], part[mt][s][i], acc[mt][s][i]);
         }
@@ -810,7 +856,7 @@ w4a16_gemm_kernel(const GemmParams p) {
   auto store_tile = [&](int tile) __attribute__((always_inline)) {
     if constexpr (RS) {
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt)
+      for (int mt = 0; mt < ML; ++mt)
 #pragma unroll
         for (int s = 0; s < NT; ++s)
 #pragma unroll
@@ -818,7 +864,7 @@ w4a16_gemm_kernel(const GemmParams p) {
     }
     uint16_t* C16 = reinterpret_cast<uint16_t*>(p.C);
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
+    for (int mt = 0; mt < ML; ++mt) {
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const int slot = slot_s[mt * 16 + lj * 4 + i];
@@ -826,7 +872,7 @@ w4a16_gemm_kernel(const GemmParams p) {
         uint16_t* crow = C16 + (size_t)slot * p.ldc;
         if constexpr (FUSE == 0 && NT == 1) {
           int wrow, ocol; bool ok;
-          feature_of<NT, FUSE>(tile, wave, 0, ln, p, wrow, ocol, ok);
+          feature_of<NT, FUSE, WV>(tile, wave, 0, ln, p, wrow, ocol, ok);
           if (ok) {
             if (p.out_f32) (reinterpret_cast<float*>(p.C) + (size_t)split * p.split_stride)[(size_t)slot * p.ldc + ocol] = acc[mt][0][i];
             else crow[ocol] = to_bits16<DT>(acc[mt][0][i]);
@@ -836,7 +882,7 @@ w4a16_gemm_kernel(const GemmParams p) {
           for (int s = 0; s < NT; s += 2) {
             // columns ocol (even) and ocol + 1 belong to this lane: one 8-byte / 4-byte store
             int wrow, ocol; bool ok;
-            feature_of<NT, FUSE>(tile, wave, s, ln, p, wrow, ocol, ok);
+            feature_of<NT, FUSE, WV>(tile, wave, s, ln, p, wrow, ocol, ok);
             if (ok) {
               if (p.out_f32) {
                 float* dst = reinterpret_cast<float*>(p.C) + (size_t)split * p.split_stride + (size_t)slot * p.ldc + ocol;
@@ -851,7 +897,7 @@ w4a16_gemm_kernel(const GemmParams p) {
 #pragma unroll
           for (int s = 0; s < NT; s += 2) {
             int wrow, ocol; bool ok;
-            feature_of<NT, FUSE>(tile, wave, s, ln, p, wrow, ocol, ok);
+            feature_of<NT, FUSE, WV>(tile, wave, s, ln, p, wrow, ocol, ok);
             if (ok) {
               // round gate/up to the storage type first so the fused path equals the staged one
               const float g = from_bits16<DT>(to_bits16<DT>(acc[mt][s][i]));
@@ -863,7 +909,7 @@ w4a16_gemm_kernel(const GemmParams p) {
       }
     }
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
+    for (int mt = 0; mt < ML; ++mt)
 #pragma unroll
       for (int s = 0; s < NT; ++s) acc[mt][s] = floatx4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -923,7 +969,26 @@ w4a16_gemm_kernel(const GemmParams p) {
       ++c_t;
     }
   }
+  };   // tile_body
+
+  if constexpr (SPEC) {
+    static_assert(MT == 8, "the live-sub-tile dispatch is written for 128-slot tiles");
+    switch (live) {      // workgroup-uniform
+      case 1: tile_body(std::integral_constant<int, 1>{}); break;
+      case 2: tile_body(std::integral_constant<int, 2>{}); break;
+      case 3: tile_body(std::integral_constant<int, 3>{}); break;
+      case 4: tile_body(std::integral_constant<int, 4>{}); break;
+      case 5: tile_body(std::integral_constant<int, 5>{}); break;
+      case 6: tile_body(std::integral_constant<int, 6>{}); break;
+      case 7: tile_body(std::integral_constant<int, 7>{}); break;
+      case 8: tile_body(std::integral_constant<int, 8>{}); break;
+      default: break;    // no live row (second half of a 256-slot block): nothing to do
+    }
+  } else {
+    tile_body(std::integral_constant<int, MT>{});
+  }
 #undef MOE_LOAD_W
+#undef MOE_AREAD
 #undef MOE_LOAD_X
 #undef MOE_STORE_STAGE
 #undef MOE_ADVANCE_W_CURSOR
@@ -931,7 +996,7 @@ w4a16_gemm_kernel(const GemmParams p) {
 }
 
 // Host-side launcher, one per instantiation.  Returns hipError_t as int.
-template <int DT, int MT, int NT, int KS, int KW, int FUSE, int SZR, int PRE = 0>
+template <int DT, int MT, int NT, int KS, int KW, int FUSE, int SZR, int PRE = 0, int WV = 4>
 int launch_w4a16_gemm(const GemmParams& p, int grid, hipStream_t stream);
 
 }  // namespace moe

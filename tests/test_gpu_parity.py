@@ -221,6 +221,49 @@ def test_grouped_gemm_block_256_register_scales(dtype, which):
     assert M.moe_last_gemm_plan()["mt"] == 8
 
 
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("block_m", [128, 256])
+def test_wide_tile_every_live_sub_tile_count(dtype, block_m):
+    """The eight-wave 128-token tile runs a main loop compiled per number of live 16-row
+    sub-tiles: experts sized so that tiles with 1, 2, ... 8 live sub-tiles all occur (full and
+    ragged last sub-tiles, a 129-row expert, an empty expert), staged GEMMs and the layer."""
+    counts = [5, 16, 17, 40, 0, 64, 70, 96, 100, 113, 128, 129, 260]
+    E, T = len(counts), sum(counts)
+    cfg = MoEConfig(name="live", T=T, K=1024, N=1024, E=E, topk=1, group=128, dtype=dtype, seed=33)
+    say(f"wide tile live sub-tile counts dtype={dtype} block_m={block_m}")
+    inp = make_inputs(cfg)
+    ids = np.repeat(np.arange(E), counts).astype(np.int32)
+    np.random.default_rng(5).shuffle(ids)
+    inp.topk_ids = ids.reshape(T, 1)
+    inp.topk_weights = np.full((T, 1), 0.75, np.float32)
+    d = U.DevInputs(inp)
+    al = U.run_align(d.ids, E, block_m)
+    tables = (al["sorted_slot_ids"], al["block_expert_ids"], al["num_padded"])
+    H = torch.full((T, 2 * cfg.N), 777.0, dtype=U.TORCH_DT[dtype], device="cuda")
+    M.moe_w4a16_grouped_gemm(d.X, 1, d.qw1, d.s1, d.z1, *tables, T, cfg.group, block_m, H)
+    torch.cuda.synchronize()
+    assert M.moe_last_gemm_plan()["waves"] == 8
+    want = O.grouped_gemm(O.decode_bits(inp.x_bits, dtype), 1, inp.qw1, O.decode_bits(inp.s1_bits, dtype), inp.z1,
+                          ids, cfg.group, dtype, fill=777.0)
+    U.assert_close(U.dev_to_f64(H), want, "wide tile gate/up GEMM")
+    M.moe_set_block_m_override(block_m)
+    try:
+        out = U.run_layer(d)
+    finally:
+        M.moe_set_block_m_override(0)
+    U.assert_close(U.dev_to_f64(out), oracle_layer(inp), "wide tile layer")
+    # the four-wave tiles on the same blocks give the same numbers up to fp32 summation order
+    M.moe_set_wide_tiles(1)
+    try:
+        H4 = torch.full((T, 2 * cfg.N), 777.0, dtype=U.TORCH_DT[dtype], device="cuda")
+        M.moe_w4a16_grouped_gemm(d.X, 1, d.qw1, d.s1, d.z1, *tables, T, cfg.group, block_m, H4)
+        torch.cuda.synchronize()
+        assert M.moe_last_gemm_plan()["waves"] == 4
+    finally:
+        M.moe_set_wide_tiles(0)
+    U.assert_close(U.dev_to_f64(H4), want, "four-wave tile on 128-slot blocks")
+
+
 @pytest.mark.parametrize("dtype,group", [("f16", 128), ("bf16", 64)])
 def test_layer_forced_to_block_256(dtype, group):
     cfg = MoEConfig("bm256_layer", T=400, K=1024, N=1024, E=3, topk=2, group=group, dtype=dtype, seed=32)
@@ -400,7 +443,7 @@ def stratified_samples(slot_expert, E, block_m, N_out, plan, rng, per_expert=8):
     block), paired with features taken in rotation from: column 0, column N_out - 1, and the first
     and last column of the first and last feature tile of every workgroup's tile group; plus two
     uniformly random entries per expert."""
-    tile_w = 64 * plan["nt"]
+    tile_w = 16 * plan["nt"] * plan["waves"]
     group_w = tile_w * plan["tiles_per_workgroup"]
     cols = {0, N_out - 1}
     for g0 in range(0, N_out, group_w):
@@ -499,7 +542,7 @@ def test_full_size_config_elementwise(name):
     d = U.DevInputs(inp)
     say(f"full-size elementwise {name}: oracle (whole layer with intermediates)")
     want, mid = oracle_layer(inp, return_intermediates=True)
-    block_m = M.moe_layer_block_m(cfg.T, cfg.E, cfg.topk)
+    block_m = M.moe_layer_block_m_for(cfg.T, cfg.K, cfg.N, cfg.E, cfg.topk, cfg.group)
     al = U.run_align(d.ids, cfg.E, block_m)
     U.assert_align_equal(al, O.align_by_expert(inp.topk_ids, cfg.E, block_m), block_m)
     tables = (al["sorted_slot_ids"], al["block_expert_ids"], al["num_padded"])
@@ -541,7 +584,7 @@ def test_full_size_config_stratified(name, n_tokens):
     inp = make_inputs(cfg)
     d = U.DevInputs(inp)
     rng = np.random.default_rng(123)
-    block_m = M.moe_layer_block_m(cfg.T, cfg.E, cfg.topk)
+    block_m = M.moe_layer_block_m_for(cfg.T, cfg.K, cfg.N, cfg.E, cfg.topk, cfg.group)
     say(f"full-size stratified {name}: staged GEMM samples (block_m={block_m})")
     sampled_gemm_check(inp, d, "w1", block_m, rng)
     sampled_gemm_check(inp, d, "w2", block_m, rng)
