@@ -30,8 +30,8 @@ int launch_combine(const void*, int, int, const float*, const int32_t*, int, voi
   extern template int launch_w4a16_gemm<DT, MT, NT, KS, KW, F, Z, 0, 4>(const GemmParams&, int, hipStream_t);
 #define MOE_DECL_PRE(DT, MT, NT, KS, F) \
   extern template int launch_w4a16_gemm<DT, MT, NT, KS, 4, F, 1, 1, 4>(const GemmParams&, int, hipStream_t);
-#define MOE_DECL_WIDE(DT, MT, NT, KS, F) \
-  extern template int launch_w4a16_gemm<DT, MT, NT, KS, 4, F, 1, 2, 8>(const GemmParams&, int, hipStream_t);
+#define MOE_DECL_WIDE(DT, MT, NT, KS, F, WV) \
+  extern template int launch_w4a16_gemm<DT, MT, NT, KS, 4, F, 1, 2, WV>(const GemmParams&, int, hipStream_t);
 #define MOE_ALL_DT_KW(M, MT, NT, KS, F) \
   M(0, MT, NT, KS, 1, F, 0) M(0, MT, NT, KS, 2, F, 0) M(0, MT, NT, KS, 4, F, 0) \
   M(1, MT, NT, KS, 1, F, 0) M(1, MT, NT, KS, 2, F, 0) M(1, MT, NT, KS, 4, F, 0)
@@ -44,8 +44,8 @@ int launch_combine(const void*, int, int, const float*, const int32_t*, int, voi
 #define MOE_TILE_PRE(MT, NT, KS) MOE_DECL_PRE(0, MT, NT, KS, 0) MOE_DECL_PRE(1, MT, NT, KS, 0)
 #define MOE_TILE_PRE_FUSE(MT, NT, KS) MOE_DECL_PRE(0, MT, NT, KS, 1) MOE_DECL_PRE(1, MT, NT, KS, 1)
 #include "gemm_variants_pre.def"
-#define MOE_TILE_WIDE(MT, NT, KS) MOE_DECL_WIDE(0, MT, NT, KS, 0) MOE_DECL_WIDE(1, MT, NT, KS, 0)
-#define MOE_TILE_WIDE_FUSE(MT, NT, KS) MOE_DECL_WIDE(0, MT, NT, KS, 1) MOE_DECL_WIDE(1, MT, NT, KS, 1)
+#define MOE_TILE_WIDE(MT, NT, KS, WV) MOE_DECL_WIDE(0, MT, NT, KS, 0, WV) MOE_DECL_WIDE(1, MT, NT, KS, 0, WV)
+#define MOE_TILE_WIDE_FUSE(MT, NT, KS, WV) MOE_DECL_WIDE(0, MT, NT, KS, 1, WV) MOE_DECL_WIDE(1, MT, NT, KS, 1, WV)
 #include "gemm_variants_wide.def"
 
 typedef int (*GemmLaunchFn)(const GemmParams&, int, hipStream_t);
@@ -54,7 +54,7 @@ typedef int (*GemmLaunchFn)(const GemmParams&, int, hipStream_t);
 struct GemmVariant { int dt, mt, nt, ks, kw, fuse, szr, pre, wv; GemmLaunchFn fn; };
 #define MOE_ENTRY(DT, MT, NT, KS, KW, F, Z) {DT, MT, NT, KS, KW, F, Z, 0, 4, &launch_w4a16_gemm<DT, MT, NT, KS, KW, F, Z, 0, 4>},
 #define MOE_ENTRY_PRE(DT, MT, NT, KS, F) {DT, MT, NT, KS, 4, F, 1, 1, 4, &launch_w4a16_gemm<DT, MT, NT, KS, 4, F, 1, 1, 4>},
-#define MOE_ENTRY_WIDE(DT, MT, NT, KS, F) {DT, MT, NT, KS, 4, F, 1, 2, 8, &launch_w4a16_gemm<DT, MT, NT, KS, 4, F, 1, 2, 8>},
+#define MOE_ENTRY_WIDE(DT, MT, NT, KS, F, WV) {DT, MT, NT, KS, 4, F, 1, 2, WV, &launch_w4a16_gemm<DT, MT, NT, KS, 4, F, 1, 2, WV>},
 static const GemmVariant kVariants[] = {
 #define MOE_TILE(MT, NT, KS) MOE_ALL_DT_KW(MOE_ENTRY, MT, NT, KS, 0)
 #define MOE_TILE_FUSE(MT, NT, KS) MOE_ALL_DT_KW(MOE_ENTRY, MT, NT, KS, 1)
@@ -65,8 +65,8 @@ static const GemmVariant kVariants[] = {
 #define MOE_TILE_PRE(MT, NT, KS) MOE_ENTRY_PRE(0, MT, NT, KS, 0) MOE_ENTRY_PRE(1, MT, NT, KS, 0)
 #define MOE_TILE_PRE_FUSE(MT, NT, KS) MOE_ENTRY_PRE(0, MT, NT, KS, 1) MOE_ENTRY_PRE(1, MT, NT, KS, 1)
 #include "gemm_variants_pre.def"
-#define MOE_TILE_WIDE(MT, NT, KS) MOE_ENTRY_WIDE(0, MT, NT, KS, 0) MOE_ENTRY_WIDE(1, MT, NT, KS, 0)
-#define MOE_TILE_WIDE_FUSE(MT, NT, KS) MOE_ENTRY_WIDE(0, MT, NT, KS, 1) MOE_ENTRY_WIDE(1, MT, NT, KS, 1)
+#define MOE_TILE_WIDE(MT, NT, KS, WV) MOE_ENTRY_WIDE(0, MT, NT, KS, 0, WV) MOE_ENTRY_WIDE(1, MT, NT, KS, 0, WV)
+#define MOE_TILE_WIDE_FUSE(MT, NT, KS, WV) MOE_ENTRY_WIDE(0, MT, NT, KS, 1, WV) MOE_ENTRY_WIDE(1, MT, NT, KS, 1, WV)
 #include "gemm_variants_wide.def"
 };
 
@@ -255,7 +255,9 @@ static int run_gemm(const GemmArgs& a, hipStream_t stream) {
     for (int t = tpw; t <= tpw + 2 && t <= 8 && t <= p.n_tiles; ++t)
       if (p.n_tiles % t == 0) { tpw = t; break; }
     const long long est_blocks = (a.num_slots + 16 * mt - 1) / (16 * mt) + (a.num_slots < a.E ? a.num_slots : a.E) / 2;
-    while (tpw > 1 && est_blocks * ((p.n_tiles + tpw - 1) / tpw) * ksp < 2048) --tpw;
+    // (measured on the 256-expert decode shape: seven or eight 8-stage tiles per workgroup beat five,
+    // as long as about 1500 workgroups remain)
+    while (tpw > 1 && est_blocks * ((p.n_tiles + tpw - 1) / tpw) * ksp < 1536) --tpw;
   }
   if (g_force_tpw > 0) tpw = szr ? (g_force_tpw < p.n_tiles ? g_force_tpw : p.n_tiles) : 1;
   p.tiles_per_wg = tpw;

@@ -63,10 +63,10 @@ int launch_w4a16_gemm(const GemmParams& p, int grid, hipStream_t stream) {
 // eight-wave workgroups on row-major weights loaded in operand order (large token tiles, group 128):
 // own translation unit (-DMOE_WIDE)
 #if defined(MOE_WIDE) && MOE_KW == 4
-#define MOE_TILE_WIDE(MT, NT, KS) \
-  template int launch_w4a16_gemm<MOE_DT, MT, NT, KS, 4, 0, 1, 2, 8>(const GemmParams&, int, hipStream_t);
-#define MOE_TILE_WIDE_FUSE(MT, NT, KS) \
-  template int launch_w4a16_gemm<MOE_DT, MT, NT, KS, 4, 1, 1, 2, 8>(const GemmParams&, int, hipStream_t);
+#define MOE_TILE_WIDE(MT, NT, KS, WV) \
+  template int launch_w4a16_gemm<MOE_DT, MT, NT, KS, 4, 0, 1, 2, WV>(const GemmParams&, int, hipStream_t);
+#define MOE_TILE_WIDE_FUSE(MT, NT, KS, WV) \
+  template int launch_w4a16_gemm<MOE_DT, MT, NT, KS, 4, 1, 1, 2, WV>(const GemmParams&, int, hipStream_t);
 #include "gemm_variants_wide.def"
 #endif
 
