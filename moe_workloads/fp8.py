@@ -72,3 +72,79 @@ def make_fp8_inputs(cfg: Fp8GemmConfig) -> Fp8GemmInputs:
     b_scale = (np.maximum(bmax, 1e-12) / np.float32(448.0)).astype(np.float32)
     b_codes = _cast_e4m3(w / np.repeat(np.repeat(b_scale, BLOCK, axis=0)[:N], BLOCK, axis=1))
     return Fp8GemmInputs(cfg, a_codes, a_scale, b_codes, b_scale)
+
+
+# --------------------------------------------------------------------------
+# FP8 mixture-of-experts layer workloads
+# --------------------------------------------------------------------------
+# Activations, routing and sizes as in the 16-bit MoE workloads (moe_workloads.make_inputs);
+# expert weights are e4m3 codes with one float32 scale per 128 x 128 block.  Drawing Gaussian
+# weights and casting them would need tens of GB of float32 temporaries at 256 experts, so the
+# codes are drawn directly: a byte u uniform in 0..255 is mapped through a 256-entry table to the
+# e4m3 code of the ((u + 0.5) / 256)-quantile of a Gaussian whose 4.5-sigma point sits at 448 (what
+# scaling a 128 x 128 Gaussian block by its maximum gives, to within the block-to-block spread);
+# block scales are uniform in [0.5, 1.5] * sigma_w * 4.5 / 448 with sigma_w = 0.02.  The table is
+# built with a library cast: input preparation, none of the layer's arithmetic.
+@dataclass(frozen=True)
+class Fp8MoEConfig:
+    name: str
+    T: int
+    K: int
+    N: int
+    E: int
+    topk: int
+    dtype: str = "bf16"
+    seed: int = 0
+
+    @property
+    def S(self) -> int:
+        return self.T * self.topk
+
+
+@dataclass
+class Fp8MoEInputs:
+    cfg: Fp8MoEConfig
+    x_bits: np.ndarray        # [T, K] uint16 patterns of cfg.dtype
+    topk_ids: np.ndarray      # [T, topk] int32
+    topk_weights: np.ndarray  # [T, topk] float32
+    w1_codes: np.ndarray      # [E, 2N, K] uint8
+    w1_scale: np.ndarray      # [E, 2N/128, K/128] float32
+    w2_codes: np.ndarray      # [E, K, N] uint8
+    w2_scale: np.ndarray      # [E, K/128, N/128] float32
+
+
+FP8_MOE_CONFIGS: Dict[str, Fp8MoEConfig] = {c.name: c for c in [
+    Fp8MoEConfig("fp8_moe_tiny", T=16, K=256, N=256, E=8, topk=2),
+    Fp8MoEConfig("fp8_moe_decode", T=128, K=7168, N=2048, E=256, topk=8),
+    Fp8MoEConfig("fp8_moe_prefill", T=4096, K=7168, N=2048, E=256, topk=8),
+]}
+
+SIGMA_W = 0.02
+
+
+def _gaussian_code_table() -> np.ndarray:
+    from scipy.special import ndtri
+    z = ndtri((np.arange(256) + 0.5) / 256.0)
+    return _cast_e4m3((z / 4.5 * 448.0).astype(np.float32))
+
+
+def _draw_fp8_weight(rng: np.random.Generator, table: np.ndarray, E: int, rows: int, red: int):
+    codes = np.empty((E, rows, red), dtype=np.uint8)
+    for e in range(E):      # per expert to bound temporaries
+        codes[e] = table[rng.integers(0, 256, size=(rows, red), dtype=np.uint8)]
+    scale = (rng.uniform(0.5, 1.5, size=(E, -(-rows // BLOCK), red // BLOCK)) * (SIGMA_W * 4.5 / 448.0))
+    return codes, scale.astype(np.float32)
+
+
+def make_fp8_moe_inputs(cfg: Fp8MoEConfig) -> Fp8MoEInputs:
+    """Draw order: X, logits, W1 (codes, scales), W2 (codes, scales); numpy PCG64 seeded with cfg.seed."""
+    from . import route_topk, to_bits
+    assert cfg.K % BLOCK == 0 and cfg.N % BLOCK == 0
+    rng = np.random.default_rng(cfg.seed)
+    x = (0.5 * rng.standard_normal((cfg.T, cfg.K))).astype(np.float32)
+    logits = rng.standard_normal((cfg.T, cfg.E)).astype(np.float32)
+    ids, w = route_topk(logits, cfg.topk)
+    table = _gaussian_code_table()
+    w1c, w1s = _draw_fp8_weight(rng, table, cfg.E, 2 * cfg.N, cfg.K)
+    w2c, w2s = _draw_fp8_weight(rng, table, cfg.E, cfg.K, cfg.N)
+    return Fp8MoEInputs(cfg, to_bits(x, cfg.dtype), ids, w, w1c, w1s, w2c, w2s)

@@ -226,3 +226,200 @@ def test_oracle_reproduces_golden_fixture():
     assert [[float(v).hex() for v in r] for r in inp.b_scale] == doc["b_scale"]
     out = F.blockwise_gemm(inp.a_codes, inp.a_scale, inp.b_codes, inp.b_scale, "bf16")
     assert O.encode_bits(out, "bf16").tolist() == doc["out_bits"]
+
+
+# ------------------------------------------------------------------ e4m3 encoder, activation quantiser
+def all_positive_e4m3():
+    """(value as Fraction, code) for the 127 non-negative finite codes, from the format definition."""
+    return [(frac_decode(c), c) for c in range(0x7F)]
+
+
+def frac_encode(y: Fraction) -> int:
+    """Nearest e4m3 value by exact comparison, ties to the even mantissa, saturating at 448."""
+    table = all_positive_e4m3()
+    a = abs(y)
+    best = min(table, key=lambda vc: (abs(vc[0] - a), vc[1] & 1))      # on a tie the even code wins
+    return best[1] | (0x80 if y < 0 else 0)
+
+
+def test_encode_matches_library_cast_and_inverts_decode():
+    rng = np.random.default_rng(11)
+    y = (rng.standard_normal(300000) * np.exp(rng.uniform(-14, 6.2, 300000))).astype(np.float32)
+    y = y[np.abs(y) <= 448.0]
+    lib = torch.from_numpy(y).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    np.testing.assert_array_equal(F.encode_e4m3(y.astype(np.float64)), lib)
+    finite = np.array([c for c in range(256) if (c & 0x7F) != 0x7F], dtype=np.uint8)
+    np.testing.assert_array_equal(F.encode_e4m3(F.decode_e4m3(finite)), finite)
+
+
+def test_encode_hand_values_and_ties():
+    cases = {1.0: 0x38, 1.0625: 0x38, 1.1875: 0x3A, 1.125: 0x39, 448.0: 0x7E, 500.0: 0x7E, -448.0: 0xFE,
+             2.0 ** -9: 0x01, 2.0 ** -10: 0x00, 3 * 2.0 ** -10: 0x02, 2.0 ** -6: 0x08, 7.5 * 2.0 ** -9: 0x08,
+             0.0: 0x00, 224.0: 0x76, 112.0: 0x6E, -3.0: 0xC4}
+    for v, code in cases.items():
+        assert F.encode_e4m3(np.array([v]))[0] == code, (v, hex(code))
+    assert F.encode_e4m3(np.array([-0.0]))[0] == 0x80
+    assert F.encode_e4m3(np.array([np.nan]))[0] == 0x7F
+
+
+def test_encode_against_exact_rational_nearest_value():
+    rng = np.random.default_rng(12)
+    ys = np.concatenate([(rng.standard_normal(400) * np.exp(rng.uniform(-9, 6, 400))).astype(np.float32),
+                         np.array([1.0625, 1.1875, 17.0, 19.0, 2.0 ** -10, 3 * 2.0 ** -10, 447.9, 0.0], np.float32)])
+    ys = ys[np.abs(ys) <= 448.0]
+    got = F.encode_e4m3(ys.astype(np.float64))
+    for y, c in zip(ys, got):
+        assert int(c) == frac_encode(Fraction(float(y))) or (y == 0 and int(c) & 0x7F == 0), float(y)
+
+
+def test_quantize_rows_hand_example_and_zero_tile():
+    x = np.array([[1.0, -2.0, 0.5, 0.0, 0.0, 0.0, 0.0, 0.0]])
+    codes, scale = F.quantize_rows(x, block=4)
+    assert scale.dtype == np.float32
+    assert scale[0, 0] == np.float32(2.0) / np.float32(448.0)
+    np.testing.assert_array_equal(codes[0, :4], [0x76, 0xFE, 0x6E, 0x00])      # 224, -448, 112, 0
+    assert scale[0, 1] == np.float32(1e-4) / np.float32(448.0)                  # all-zero tile: clamped maximum
+    np.testing.assert_array_equal(codes[0, 4:], 0)
+
+
+@pytest.mark.parametrize("dt", ["bf16", "f16"])
+def test_quantize_rows_invariants_and_scalar_walk(dt):
+    rng = np.random.default_rng(13)
+    x = O.rnd(rng.standard_normal((6, 256)) * np.exp(rng.uniform(-6, 3, (6, 1))), dt)
+    x[2, :128] = 0.0
+    x[3, 5] = 0.0
+    codes, scale = F.quantize_rows(x)
+    t = x.reshape(6, 2, 128)
+    # the largest element of every non-zero tile maps to +-448
+    for r in range(6):
+        for b in range(2):
+            if np.abs(t[r, b]).max() > 1e-4:
+                i = int(np.argmax(np.abs(t[r, b])))
+                assert codes[r, 128 * b + i] & 0x7F == 0x7E
+    # decode(code) * scale is within half an e4m3 step of x (step 2^-3 relative below the binade top,
+    # 2^-9 of the scaled range in the subnormals), plus the float32 roundings of the two scale operations
+    back = F.decode_e4m3(codes) * np.repeat(scale.astype(np.float64), 128, axis=1)
+    assert np.all(np.abs(back - x) <= np.abs(x) * (2.0 ** -4 + 2.0 ** -20) + np.repeat(scale, 128, axis=1) * 2.0 ** -10)
+    # scalar walk of the stated float32 steps, nearest value found in exact rationals
+    for r, b in [(0, 0), (1, 1), (2, 0), (3, 0), (5, 1)]:
+        m = np.float32(max(float(np.abs(t[r, b]).max()), 1e-4))
+        m = max(m, np.float32(1e-4))
+        ratio = np.float32(448.0) / m
+        assert scale[r, b] == m / np.float32(448.0)
+        for i in range(0, 128, 7):
+            y = np.float32(t[r, b, i]) * ratio
+            assert int(codes[r, 128 * b + i]) & 0x7F == frac_encode(Fraction(float(y))) & 0x7F
+
+
+# ------------------------------------------------------------------ the FP8 mixture-of-experts layer
+def brute_fp8_layer(X, ids, w, w1c, w1s, w2c, w2s, dt, block):
+    """Scalar walk of the layer: per token and routed expert, quantise (float32 steps, nearest code by
+    exact comparison), both products in exact rationals, float64 SiLU, roundings by the 16-bit oracle."""
+    import math
+    T, K = X.shape
+    E, N2, _ = w1c.shape
+    N = N2 // 2
+
+    def quant(row):
+        codes, scales = [], []
+        for b0 in range(0, len(row), block):
+            tile = [np.float32(v) for v in row[b0:b0 + block]]
+            m = max(max(abs(v) for v in tile), np.float32(1e-4))
+            ratio = np.float32(448.0) / np.float32(m)
+            scales.append(np.float32(m) / np.float32(448.0))
+            codes += [frac_encode(Fraction(float(np.float32(v) * ratio))) | (0x80 if np.signbit(v) else 0) for v in tile]
+        return codes, scales
+
+    def product(codes, scales, wc, ws, n):
+        acc = Fraction(0)
+        for k in range(len(codes)):
+            kb = k // block
+            acc += (Fraction(float(scales[kb])) * Fraction(float(ws[n // block, kb])) *
+                    frac_decode(codes[k]) * frac_decode(int(wc[n, k])))
+        return acc
+
+    out = np.zeros((T, K))
+    for t in range(T):
+        xq, sx = quant(X[t])
+        tot = [0.0] * K
+        for j in range(ids.shape[1]):
+            e = int(ids[t, j])
+            if e < 0 or e >= E:
+                continue
+            H = [float(O.rnd(float(product(xq, sx, w1c[e], w1s[e], n)), dt)) for n in range(2 * N)]
+            act = [float(O.rnd(H[n] / (1.0 + math.exp(-H[n])) * H[N + n], dt)) for n in range(N)]
+            aq, sa = quant(act)
+            for c in range(K):
+                tot[c] += float(w[t, j]) * float(product(aq, sa, w2c[e], w2s[e], c))
+        out[t] = O.rnd(np.array(tot), dt)
+    return out
+
+
+def tiny_fp8_layer_case(seed, T=3, K=8, N=8, E=3, topk=2, block=4, dt="bf16"):
+    rng = np.random.default_rng(seed)
+    X = O.rnd(rng.standard_normal((T, K)) * 0.7, dt)
+    ids = np.stack([rng.permutation(E)[:topk] for _ in range(T)]).astype(np.int32)
+    w = rng.dirichlet(np.ones(topk), T).astype(np.float32)
+    w1c, w2c = valid_codes(rng, (E, 2 * N, K)), valid_codes(rng, (E, K, N))
+    # keep magnitudes modest: exponent field at most 9 (|v| < 8)
+    w1c = (w1c & 0x87) | (((w1c >> 3) & 15) % 10 << 3)
+    w2c = (w2c & 0x87) | (((w2c >> 3) & 15) % 10 << 3)
+    w1s = rng.uniform(0.05, 0.2, (E, 2 * N // block, K // block)).astype(np.float32)
+    w2s = rng.uniform(0.05, 0.2, (E, K // block, N // block)).astype(np.float32)
+    return X, ids, w, w1c.astype(np.uint8), w1s, w2c.astype(np.uint8), w2s, dt, block
+
+
+@pytest.mark.parametrize("seed,dt", [(21, "bf16"), (22, "f16"), (23, "bf16")])
+def test_fp8_layer_against_scalar_brute_force(seed, dt):
+    X, ids, w, w1c, w1s, w2c, w2s, dt, block = tiny_fp8_layer_case(seed, dt=dt)
+    got = F.moe_layer(X, ids, w, w1c, w1s, w2c, w2s, dt, block=block)
+    want = brute_fp8_layer(X, ids, w, w1c, w1s, w2c, w2s, dt, block)
+    # the two sum the same exact products in a different order: equal up to float64 rounding of the sums,
+    # which can flip a final 16-bit rounding only on an exact near-tie
+    np.testing.assert_allclose(got, want, rtol=2.0 ** -7, atol=1e-12)
+    assert np.mean(got == want) > 0.9
+
+
+def test_fp8_layer_brute_force_catches_plausible_mistakes():
+    X, ids, w, w1c, w1s, w2c, w2s, dt, block = tiny_fp8_layer_case(24)
+    want = brute_fp8_layer(X, ids, w, w1c, w1s, w2c, w2s, dt, block)
+    swapped = np.concatenate([w1c[:, w1c.shape[1] // 2:], w1c[:, :w1c.shape[1] // 2]], axis=1)   # gate <-> up
+    assert not np.allclose(F.moe_layer(X, ids, w, swapped, w1s, w2c, w2s, dt, block=block), want, rtol=1e-2)
+    assert not np.allclose(F.moe_layer(X, ids, w, w1c, w1s[:, ::-1], w2c, w2s, dt, block=block), want, rtol=1e-2)
+    assert not np.allclose(F.moe_layer(X, ids[:, ::-1], w, w1c, w1s, w2c, w2s, dt, block=block), want, rtol=1e-2)
+
+
+def test_fp8_layer_one_hot_routing_is_the_dense_chain():
+    rng = np.random.default_rng(25)
+    T, K, N, E = 5, 256, 128, 3
+    X = O.rnd(rng.standard_normal((T, K)) * 0.5, "bf16")
+    w1c, w2c = valid_codes(rng, (E, 2 * N, K)), valid_codes(rng, (E, K, N))
+    w1c, w2c = (w1c & 0xB7).astype(np.uint8), (w2c & 0xB7).astype(np.uint8)      # exponent field <= 6: |v| < 1
+    w1s = rng.uniform(0.01, 0.03, (E, 2, 2)).astype(np.float32)
+    w2s = rng.uniform(0.01, 0.03, (E, 2, 1)).astype(np.float32)
+    ids = np.full((T, 1), 1, np.int32)
+    got = F.moe_layer(X, ids, np.ones((T, 1), np.float32), w1c, w1s, w2c, w2s, "bf16")
+    xq, sx = F.quantize_rows(X)
+    H = F.blockwise_gemm(xq, sx, w1c[1], w1s[1], "bf16")
+    act = O.silu_mul(H, "bf16")
+    aq, sa = F.quantize_rows(act)
+    np.testing.assert_array_equal(got, F.blockwise_gemm(aq, sa, w2c[1], w2s[1], "bf16"))
+
+
+def test_fp8_layer_token_permutation_and_ignored_slots():
+    from moe_workloads.fp8 import FP8_MOE_CONFIGS, make_fp8_moe_inputs
+    inp = make_fp8_moe_inputs(FP8_MOE_CONFIGS["fp8_moe_tiny"])
+    c = inp.cfg
+    X = O.decode_bits(inp.x_bits, c.dtype)
+    args = (inp.w1_codes, inp.w1_scale, inp.w2_codes, inp.w2_scale, c.dtype)
+    base = F.moe_layer(X, inp.topk_ids, inp.topk_weights, *args)
+    perm = np.random.default_rng(2).permutation(c.T)
+    np.testing.assert_array_equal(F.moe_layer(X[perm], inp.topk_ids[perm], inp.topk_weights[perm], *args), base[perm])
+    np.testing.assert_array_equal(F.moe_layer(X, inp.topk_ids, inp.topk_weights, *args, tokens=[3, 9]), base[[3, 9]])
+    ids = inp.topk_ids.copy()
+    ids[4, :] = c.E + 5
+    assert np.all(F.moe_layer(X, ids, inp.topk_weights, *args)[4] == 0)
+    # the workload's codes hold no NaN pattern and its weights have the stated spread
+    assert not ((inp.w1_codes & 0x7F) == 0x7F).any() and not ((inp.w2_codes & 0x7F) == 0x7F).any()
+    wd = F.decode_e4m3(inp.w1_codes[0]) * np.repeat(np.repeat(inp.w1_scale[0], 128, 0), 128, 1)
+    assert 0.015 < wd.std() < 0.025
