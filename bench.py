@@ -71,6 +71,10 @@ def main():
     if args.config in FP8_CONFIGS:
         fp8_main(args, FP8_CONFIGS[args.config])
         return
+    from moe_workloads.fp8 import FP8_MOE_CONFIGS
+    if args.config in FP8_MOE_CONFIGS:
+        fp8_moe_main(args, FP8_MOE_CONFIGS[args.config])
+        return
     cfg = CONFIGS[args.config]
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
@@ -311,6 +315,110 @@ def fp8_main(args, cfg):
                                 else result["achievable"]["mfma_fp8_TFLOPs"]), 4)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = fp8_cpu_baseline(cfg, inp)
+    print(json.dumps(result), flush=True)
+
+
+def fp8_moe_main(args, cfg):
+    """One step = one fp8_moe_layer call (bucketing, activation quantiser, grouped FP8 gate/up product,
+    SiLU-and-multiply quantiser, grouped FP8 down product, combine) on a seeded workload resident in HBM."""
+    import torch
+    import paper_2504_16214_amd as M
+    from moe_workloads.fp8 import make_fp8_moe_inputs
+
+    torch.cuda.set_device(0)
+    t0 = time.time()
+    inp = make_fp8_moe_inputs(cfg)
+    print(f"[bench] generated {cfg.name} in {time.time() - t0:.1f}s", file=sys.stderr, flush=True)
+    tdt = torch.float16 if cfg.dtype == "f16" else torch.bfloat16
+    X = torch.from_numpy(np.ascontiguousarray(inp.x_bits).view(np.int16)).cuda().view(tdt)
+    ids, w = torch.from_numpy(inp.topk_ids).cuda(), torch.from_numpy(inp.topk_weights).cuda()
+    w1, s1 = torch.from_numpy(inp.w1_codes).cuda(), torch.from_numpy(inp.w1_scale).cuda()
+    w2, s2 = torch.from_numpy(inp.w2_codes).cuda(), torch.from_numpy(inp.w2_scale).cuda()
+    out = torch.empty((cfg.T, cfg.K), dtype=tdt, device="cuda")
+    ws = torch.empty(M.fp8_moe_layer_workspace_bytes(cfg.T, cfg.K, cfg.N, cfg.E, cfg.topk), dtype=torch.uint8, device="cuda")
+    if args.tile:
+        M.fp8_set_layer_block_m(int(args.tile.split(",")[0]) * 16)
+
+    def step():
+        M.fp8_moe_layer(X, ids, w, w1, s1, w2, s2, out, ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    K_steps = args.steps
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(7)] for _ in range(K_steps)]
+    for row in evs:
+        for e in row:
+            e.record()
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for i in range(K_steps):
+        M.moe_set_stage_events([e.cuda_event for e in evs[i]])
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t_start
+    M.moe_set_stage_events(None)
+    ms_per_step = elapsed * 1e3 / K_steps
+    stage = np.array([[row[j].elapsed_time(row[j + 1]) for j in range(6)] for row in evs]).mean(axis=0)
+    E_act = int(np.unique(inp.topk_ids[(inp.topk_ids >= 0) & (inp.topk_ids < cfg.E)]).size)
+    K, N, T, S = cfg.K, cfg.N, cfg.T, cfg.S
+    w1_bytes = 2 * N * K + 4 * (2 * N // 128) * (K // 128)
+    w2_bytes = K * N + 4 * (K // 128) * (N // 128)
+    layer_bytes = E_act * (w1_bytes + w2_bytes) + 2 * T * K + 2 * T * K + 8 * S
+    gemm1_bytes = E_act * w1_bytes + T * K + 4 * T * (K // 128) + 2 * S * 2 * N + 4 * S
+    flops = 6.0 * K * N * S
+    gbs = layer_bytes / (ms_per_step * 1e-3) / 1e9
+    tflops = flops / (ms_per_step * 1e-3) / 1e12
+    hbm_bound = (flops / layer_bytes) < (FP8_MFMA_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9))
+    g1_ms = float(stage[2])
+    if hbm_bound:
+        ach = gemm1_bytes / (g1_ms * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": None}
+    else:
+        ach = 4.0 * K * N * S / (g1_ms * 1e-3) / 1e12
+        roofline = {"bound": "mfma", "achieved": round(ach, 1), "peak": FP8_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                    "frac": round(ach / FP8_MFMA_PEAK_TFLOPS, 4), "traffic": None}
+    roofline["kernel"] = "fp8_blockwise_gemm_kernel (grouped gate/up product)"
+    roofline["kernel_ms"] = round(g1_ms, 4)
+    result = {
+        "metric": "FP8 MoE layer TFLOP/s + HBM GB/s (% of MI355X roofline), 1 GPU",
+        "value": round(gbs, 1) if hbm_bound else round(tflops, 1), "unit": "GB/s" if hbm_bound else "TFLOP/s",
+        "n_gpus": 1, "steps": K_steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "fp8_e4m3", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: T={T} K={K} N={N} E={cfg.E} top{cfg.topk}, e4m3 weights with 128x128 float32 "
+                               f"block scales, {cfg.dtype} activations quantised 1x128 on the fly, seed {cfg.seed}",
+                   "active_experts": E_act, "algorithmic_bytes": layer_bytes, "flop": flops},
+        "tflops": round(tflops, 2), "gbs": round(gbs, 1), "hbm_frac": round(gbs / HBM_PEAK_GBS, 4),
+        "mfma_frac": round(tflops / FP8_MFMA_PEAK_TFLOPS, 4),
+        "stage_ms": {k: round(float(v), 4) for k, v in zip(
+            ("align", "quantize_x", "gemm1", "silu_quantize", "gemm2", "combine"), stage)},
+        "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        from oracle import fp8_oracle as F
+        from oracle import moe_oracle as O
+        try:
+            from threadpoolctl import threadpool_info
+            threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+        except Exception:
+            threads = os.cpu_count() or 1
+        Xv = O.decode_bits(inp.x_bits, cfg.dtype)
+
+        def run(tokens):
+            t0 = time.perf_counter()
+            F.moe_layer(Xv, inp.topk_ids, inp.topk_weights, inp.w1_codes, inp.w1_scale, inp.w2_codes, inp.w2_scale,
+                        cfg.dtype, tokens=tokens)
+            return time.perf_counter() - t0
+
+        probe = run([0])
+        n_tok = int(max(1, min(cfg.T, 12.0 / max(probe, 1e-3))))
+        dt_s = run(list(range(n_tok)))
+        touched = int(np.unique(inp.topk_ids[:n_tok]).size)
+        result["cpu_baseline"] = {"value": round(touched * (w1_bytes + w2_bytes) / dt_s / 1e9, 4), "unit": "GB/s",
+                                  "cores": int(threads), "kind": "oracle", "seconds": round(dt_s, 2),
+                                  "sample": f"first {n_tok} tokens ({touched} distinct experts) of {cfg.name}, NumPy fp64 "
+                                            f"oracle, whole-layer definition"}
     print(json.dumps(result), flush=True)
 
 

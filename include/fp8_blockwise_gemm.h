@@ -69,6 +69,45 @@ int fp8_moe_grouped_gemm(const uint8_t* A, const float* a_scale, int row_div,
                          int out_dtype, void* C, void* stream);
 
 /*
+ * FP8 mixture-of-experts layer: the gated expert MLP of the 16-bit layer (include/moe_w4a16.h)
+ * with e4m3 weights (128 x 128 block scales) and activations quantised on the fly, the FP8
+ * workload family of the paper's serving evaluation (Section VII-D; the grouped kernel structure
+ * is that of Section VII-B).  The paper does not write the operator down; the quantisation rule
+ * is the published fine-grained FP8 recipe:
+ *
+ *   quantise (fp8_quantize_rows): per row and per 128 reduction indices, in float32,
+ *       m = max(max |x|, 1e-4);  scale = m / 448;  code = e4m3(x * (448 / m))   (round to nearest even)
+ *   X [rows, K] dt -> codes [rows, K] uint8, scales [rows, K/128] float32; K % 128 == 0.
+ *
+ *   fp8_silu_mul_quantize: act = round_dt(silu(H[:, :N]) * H[:, N:]) quantised the same way,
+ *       H [S, 2N] dt -> codes [S, N], scales [S, N/128]; N % 128 == 0.  The 16-bit activation never
+ *       goes to memory.
+ *
+ *   fp8_moe_layer: bucketing -> quantise X -> grouped FP8 product with W1 [E, 2N, K] (rows [0, N)
+ *       gate, [N, 2N) up; w1_scale [E, 2N/128, K/128]) rounded to dt -> SiLU-and-multiply + quantise
+ *       -> grouped FP8 product with W2 [E, K, N] (w2_scale [E, K/128, N/128]) kept in float32 ->
+ *       weighted combine in j order, one rounding to dt.  X [T, K] dt, topk_ids [T, topk] int32,
+ *       topk_weights [T, topk] float32, out [T, K] dt.  Slots with an expert id outside [0, E)
+ *       contribute zero.  K % 128 == 0, N % 128 == 0, E <= 1024.  Six launches on `stream`, no
+ *       allocation; `workspace`: at least fp8_moe_layer_workspace_bytes(...) bytes, 256-byte aligned.
+ *
+ * All pointers are caller-owned device memory; X, H, out and the weight tensors 16-byte aligned.
+ * dt is a moe_dtype (0 = fp16, 1 = bf16).  Each returns a moe_status.
+ * fp8_set_layer_block_m: force the token tile of the layer's two grouped products (0 = choose);
+ * thread-local tuning hook.  With moe_set_stage_events(events, 7) the layer records seven events:
+ * before the bucketing, the quantiser, the first product, the SiLU quantiser, the second
+ * product, the combine, and after it.
+ */
+int fp8_quantize_rows(const void* X, int rows, int K, int dt, uint8_t* codes, float* scales, void* stream);
+int fp8_silu_mul_quantize(const void* H, int S, int N, int dt, uint8_t* codes, float* scales, void* stream);
+size_t fp8_moe_layer_workspace_bytes(int T, int K, int N, int E, int topk);
+int fp8_moe_layer(const void* X, const int32_t* topk_ids, const float* topk_weights,
+                  const uint8_t* w1, const float* w1_scale, const uint8_t* w2, const float* w2_scale,
+                  void* out, int T, int K, int N, int E, int topk, int dt,
+                  void* workspace, size_t workspace_bytes, void* stream);
+int fp8_set_layer_block_m(int block_m);
+
+/*
  * Tuning hook (thread-local, not part of the operator): force the tile (mt in {1,2,4,8,16} = rows
  * of A per workgroup / 16, nt in {1,2,4} = rows of B per workgroup / 64; mt = 16 not with nt = 1)
  * and the number of

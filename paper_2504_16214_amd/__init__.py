@@ -12,7 +12,8 @@ from .binding import (  # noqa: F401
     moe_w4a16_routed_layer_workspace_bytes, moe_w4a16_routed_layer,
     moe_repack_qweight, moe_w4a16_layer_prepacked, moe_import_awq,
     fp8_blockwise_gemm_workspace_bytes, fp8_blockwise_gemm, fp8_moe_grouped_gemm, fp8_set_plan_override,
-    fp8_probe_mfma,
+    fp8_probe_mfma, fp8_quantize_rows, fp8_silu_mul_quantize, fp8_moe_layer_workspace_bytes, fp8_moe_layer,
+    fp8_set_layer_block_m,
     moe_set_tile_override, moe_set_scale_path, moe_set_tiles_per_workgroup, moe_set_reduction_splits, moe_set_stage_events, moe_last_error,
     moe_set_block_m_override, moe_last_gemm_plan, moe_w4a16_layer_noalloc, moe_layer_block_m_for, moe_set_wide_tiles,
 )

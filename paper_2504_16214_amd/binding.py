@@ -23,6 +23,8 @@ EXPORTS = [
     "fp8_blockwise_gemm_workspace_bytes", "fp8_blockwise_gemm", "fp8_moe_grouped_gemm", "fp8_set_plan_override",
     "fp8_probe_mfma", "moe_set_block_m_override", "moe_last_gemm_plan",
     "moe_w4a16_layer_noalloc", "moe_layer_block_m_for", "moe_set_wide_tiles",
+    "fp8_quantize_rows", "fp8_silu_mul_quantize", "fp8_moe_layer_workspace_bytes", "fp8_moe_layer",
+    "fp8_set_layer_block_m",
 ]
 
 
@@ -105,6 +107,16 @@ def load_library() -> ctypes.CDLL:
     lib.moe_layer_block_m.argtypes = [i32, i32, i32]
     lib.moe_w4a16_layer_noalloc.restype = i32
     lib.moe_w4a16_layer_noalloc.argtypes = [vp] * 10 + [i32] * 7 + [vp]
+    lib.fp8_quantize_rows.restype = i32
+    lib.fp8_quantize_rows.argtypes = [vp, i32, i32, i32, vp, vp, vp]
+    lib.fp8_silu_mul_quantize.restype = i32
+    lib.fp8_silu_mul_quantize.argtypes = [vp, i32, i32, i32, vp, vp, vp]
+    lib.fp8_moe_layer_workspace_bytes.restype = sz
+    lib.fp8_moe_layer_workspace_bytes.argtypes = [i32] * 5
+    lib.fp8_moe_layer.restype = i32
+    lib.fp8_moe_layer.argtypes = [vp] * 8 + [i32] * 6 + [vp, sz, vp]
+    lib.fp8_set_layer_block_m.restype = i32
+    lib.fp8_set_layer_block_m.argtypes = [i32]
     lib.moe_layer_block_m_for.restype = i32
     lib.moe_layer_block_m_for.argtypes = [i32] * 6
     lib.moe_set_wide_tiles.restype = i32
@@ -304,6 +316,37 @@ def fp8_moe_grouped_gemm(A, a_scale, row_div: int, B, b_scale, sorted_slot_ids, 
     _check(load_library().fp8_moe_grouped_gemm(_ptr(A), _ptr(a_scale), row_div, _ptr(B), _ptr(b_scale),
                                                _ptr(sorted_slot_ids), _ptr(block_expert_ids), _ptr(num_padded),
                                                num_slots, E, N, K, block_m, out_dtype, _ptr(C), _stream(stream)))
+
+
+def fp8_quantize_rows(X, codes, scales, stream=None) -> None:
+    """X [rows, K] fp16/bf16 -> codes [rows, K] uint8 (e4m3), scales [rows, K/128] float32 (preallocated)."""
+    rows, K = X.shape
+    _check(load_library().fp8_quantize_rows(_ptr(X), rows, K, _dt(X), _ptr(codes), _ptr(scales), _stream(stream)))
+
+
+def fp8_silu_mul_quantize(H, codes, scales, stream=None) -> None:
+    """H [S, 2N] fp16/bf16 -> e4m3 codes [S, N] and scales [S, N/128] of round(silu(gate) * up)."""
+    S, N2 = H.shape
+    _check(load_library().fp8_silu_mul_quantize(_ptr(H), S, N2 // 2, _dt(H), _ptr(codes), _ptr(scales), _stream(stream)))
+
+
+def fp8_moe_layer_workspace_bytes(T: int, K: int, N: int, E: int, topk: int) -> int:
+    return int(load_library().fp8_moe_layer_workspace_bytes(T, K, N, E, topk))
+
+
+def fp8_moe_layer(X, topk_ids, topk_weights, w1, w1_scale, w2, w2_scale, out, workspace, stream=None) -> None:
+    """X [T, K] fp16/bf16, w1 [E, 2N, K] uint8 + w1_scale [E, 2N/128, K/128] float32, w2 [E, K, N] uint8 +
+    w2_scale [E, K/128, N/128], out [T, K] (preallocated), workspace uint8 tensor."""
+    T, K = X.shape
+    E, N2, _ = w1.shape
+    topk = topk_ids.shape[1]
+    _check(load_library().fp8_moe_layer(
+        _ptr(X), _ptr(topk_ids), _ptr(topk_weights), _ptr(w1), _ptr(w1_scale), _ptr(w2), _ptr(w2_scale), _ptr(out),
+        T, K, N2 // 2, E, topk, _dt(X), _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+def fp8_set_layer_block_m(block_m: int) -> None:
+    _check(load_library().fp8_set_layer_block_m(block_m))
 
 
 def fp8_set_plan_override(mt: int, nt: int, k_splits: int, group_m: int = 0) -> None:

@@ -32,7 +32,7 @@ def _units():
         units.append(("gemm_inst.hip", f"gemm_inst_pre_dt{dt}.o", [f"-DMOE_DT={dt}", "-DMOE_KW=4", "-DMOE_PRE=1"]))
     for dt in (0, 1):      # eight-wave workgroups (128-token tiles), group 128 only
         units.append(("gemm_inst.hip", f"gemm_inst_wide_dt{dt}.o", [f"-DMOE_DT={dt}", "-DMOE_KW=4", "-DMOE_WIDE=1"]))
-    for src in ("align.hip", "elementwise.hip", "router.hip", "fp8_gemm.hip", "api.hip"):
+    for src in ("align.hip", "elementwise.hip", "router.hip", "fp8_gemm.hip", "fp8_quant.hip", "api.hip"):
         units.append((src, src.replace(".hip", ".o"), []))
     return units
 

@@ -24,6 +24,11 @@ int launch_stream_read(const void*, size_t, uint32_t*, int, hipStream_t);
 int launch_mfma_loop(float*, int, int, hipStream_t);
 int launch_combine(const void*, int, int, const float*, const int32_t*, int, void*, long long, int, int, int,
                    hipStream_t);
+}  // namespace moe
+namespace fp8 {
+int launch_fp8_quantize(const void*, long long, int, int, int, uint8_t*, float*, hipStream_t);
+}
+namespace moe {
 
 // ---- table of compiled GEMM variants ------------------------------------------------------
 #define MOE_DECL(DT, MT, NT, KS, KW, F, Z) \
@@ -80,7 +85,7 @@ static const GemmVariant* find_variant(int dt, int mt, int nt, int kw, int fuse,
 
 // ---- thread-local state -----------------------------------------------------------------
 static thread_local char g_err[512] = "";
-static thread_local void* g_events[5] = {nullptr, nullptr, nullptr, nullptr, nullptr};
+static thread_local void* g_events[7] = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
 static thread_local int g_nevents = 0;
 static thread_local int g_force_mt = 0, g_force_nt = 0;
 static thread_local int g_scale_path = 0;   // 0 auto, 1 LDS table, 2 registers
@@ -688,9 +693,9 @@ int moe_w4a16_routed_layer(const void* X, const float* logits, const float* bias
 
 int moe_set_stage_events(void* const* events, int n) {
   if (n == 0 || events == nullptr) { g_nevents = 0; return MOE_OK; }
-  if (n != 5) return fail(MOE_INVALID_ARGUMENT, "expected 5 events");
-  for (int i = 0; i < 5; ++i) g_events[i] = events[i];
-  g_nevents = 5;
+  if (n != 5 && n != 7) return fail(MOE_INVALID_ARGUMENT, "expected 5 events (16-bit layer) or 7 (FP8 layer)");
+  for (int i = 0; i < n; ++i) g_events[i] = events[i];
+  g_nevents = n;
   return MOE_OK;
 }
 
@@ -828,6 +833,138 @@ int fp8_moe_grouped_gemm(const uint8_t* A, const float* a_scale, int row_div, co
   const int err = fp8::launch_fp8_gemm(p, block_m, bn, (hipStream_t)stream);
   if (err == -1) return fail(MOE_UNSUPPORTED_SHAPE, "no FP8 GEMM variant for tile %d x %d", block_m, bn);
   if (err != 0) return hip_fail(err, "grouped FP8 GEMM launch");
+  return MOE_OK;
+}
+
+// ---- FP8 mixture-of-experts layer ------------------------------------------------------------
+int fp8_quantize_rows(const void* X, int rows, int K, int dt, uint8_t* codes, float* scales, void* stream) {
+  if (rows < 0 || K < 1) return fail(MOE_INVALID_ARGUMENT, "need rows >= 0 and K >= 1");
+  if (dt != MOE_F16 && dt != MOE_BF16) return fail(MOE_INVALID_ARGUMENT, "dt must be MOE_F16 or MOE_BF16");
+  if (K % 128 != 0) return fail(MOE_UNSUPPORTED_SHAPE, "the activation quantiser needs K %% 128 == 0 (got %d)", K);
+  if (rows == 0) return MOE_OK;
+  if (!X || !codes || !scales) return fail(MOE_INVALID_ARGUMENT, "null pointer argument");
+  if ((uintptr_t)X % 16 != 0 || (uintptr_t)codes % 8 != 0 || (uintptr_t)scales % 4 != 0)
+    return fail(MOE_INVALID_ARGUMENT, "X must be 16-byte, codes 8-byte, scales 4-byte aligned");
+  const int err = fp8::launch_fp8_quantize(X, rows, K, (int)dt, 0, codes, scales, (hipStream_t)stream);
+  if (err != 0) return hip_fail(err, "activation quantiser launch");
+  return MOE_OK;
+}
+
+int fp8_silu_mul_quantize(const void* H, int S, int N, int dt, uint8_t* codes, float* scales, void* stream) {
+  if (S < 0 || N < 1) return fail(MOE_INVALID_ARGUMENT, "need S >= 0 and N >= 1");
+  if (dt != MOE_F16 && dt != MOE_BF16) return fail(MOE_INVALID_ARGUMENT, "dt must be MOE_F16 or MOE_BF16");
+  if (N % 128 != 0) return fail(MOE_UNSUPPORTED_SHAPE, "the activation quantiser needs N %% 128 == 0 (got %d)", N);
+  if (S == 0) return MOE_OK;
+  if (!H || !codes || !scales) return fail(MOE_INVALID_ARGUMENT, "null pointer argument");
+  if ((uintptr_t)H % 16 != 0 || (uintptr_t)codes % 8 != 0 || (uintptr_t)scales % 4 != 0)
+    return fail(MOE_INVALID_ARGUMENT, "H must be 16-byte, codes 8-byte, scales 4-byte aligned");
+  const int err = fp8::launch_fp8_quantize(H, S, N, (int)dt, 1, codes, scales, (hipStream_t)stream);
+  if (err != 0) return hip_fail(err, "SiLU-and-multiply quantiser launch");
+  return MOE_OK;
+}
+
+static thread_local int g_fp8_layer_block_m = 0;
+
+static int fp8_pick_block_m(long long S, int E) {
+  if (g_fp8_layer_block_m > 0) return g_fp8_layer_block_m;
+  const long long avg = S / (E > 0 ? E : 1);
+  if (avg <= 32) return 32;      // measured: 32-token tiles stream the weights fastest at a few rows per expert
+  return 64;
+}
+
+struct Fp8Workspace { size_t counts, offsets, num_padded, sorted, blocks, xq, sx, H, aq, sa, Y, total; };
+static Fp8Workspace fp8_carve(long long T, int K, int N, int E, int topk) {
+  const long long S = T * topk;
+  Fp8Workspace w;
+  size_t o = 0;
+  w.counts = o;      o += round_up((size_t)E * 4, 256);
+  w.offsets = o;     o += round_up((size_t)(E + 1) * 4, 256);
+  w.num_padded = o;  o += 256;
+  w.sorted = o;      o += round_up(align_capacity(S, E, 256) * 4, 256);
+  w.blocks = o;      o += round_up((align_capacity(S, E, 16) / 16 + 1) * 4, 256);
+  w.xq = o;          o += round_up((size_t)T * K, 256);
+  w.sx = o;          o += round_up((size_t)T * (K / 128) * 4, 256);
+  w.H = o;           o += round_up((size_t)S * 2 * N * 2, 256);
+  w.aq = o;          o += round_up((size_t)S * N, 256);
+  w.sa = o;          o += round_up((size_t)S * (N / 128) * 4, 256);
+  w.Y = o;           o += round_up((size_t)S * K * 4, 256);
+  w.total = o;
+  return w;
+}
+
+size_t fp8_moe_layer_workspace_bytes(int T, int K, int N, int E, int topk) {
+  if (T < 0 || K < 128 || N < 128 || E < 1 || topk < 1 || K % 128 != 0 || N % 128 != 0) return 0;
+  return fp8_carve(T, K, N, E, topk).total;
+}
+
+int fp8_set_layer_block_m(int block_m) {
+  if (block_m != 0 && !valid_block_m(block_m))
+    return fail(MOE_INVALID_ARGUMENT, "block_m override must be 0, 16, 32, 64, 128 or 256");
+  g_fp8_layer_block_m = block_m;
+  return MOE_OK;
+}
+
+int fp8_moe_layer(const void* X, const int32_t* topk_ids, const float* topk_weights,
+                  const uint8_t* w1, const float* w1_scale, const uint8_t* w2, const float* w2_scale,
+                  void* out, int T, int K, int N, int E, int topk, int dt,
+                  void* workspace, size_t workspace_bytes, void* stream_v) {
+  hipStream_t stream = (hipStream_t)stream_v;
+  if (T < 0 || K < 1 || N < 1 || E < 1 || topk < 1)
+    return fail(MOE_INVALID_ARGUMENT, "need T >= 0 and positive K, N, E, topk");
+  if (dt != MOE_F16 && dt != MOE_BF16) return fail(MOE_INVALID_ARGUMENT, "dt must be MOE_F16 or MOE_BF16");
+  if (E > 1024) return fail(MOE_UNSUPPORTED_SHAPE, "E = %d exceeds 1024", E);
+  if (K % 128 != 0 || N % 128 != 0)
+    return fail(MOE_UNSUPPORTED_SHAPE, "the FP8 layer needs K %% 128 == 0 and N %% 128 == 0 (got K=%d N=%d)", K, N);
+  if (T == 0) return MOE_OK;
+  if (!X || !topk_ids || !topk_weights || !w1 || !w1_scale || !w2 || !w2_scale || !out || !workspace)
+    return fail(MOE_INVALID_ARGUMENT, "null pointer argument");
+  if (((uintptr_t)workspace % 256) != 0) return fail(MOE_INVALID_ARGUMENT, "workspace must be 256-byte aligned");
+  if (((uintptr_t)X | (uintptr_t)out | (uintptr_t)w1 | (uintptr_t)w2) % 16 != 0)
+    return fail(MOE_INVALID_ARGUMENT, "X, out and the weight tensors must be 16-byte aligned");
+  const long long S = (long long)T * topk;
+  if (S > 0x7fffffffLL / 2) return fail(MOE_UNSUPPORTED_SHAPE, "T*topk too large");
+  const Fp8Workspace w = fp8_carve(T, K, N, E, topk);
+  if (workspace_bytes < w.total)
+    return fail(MOE_WORKSPACE_TOO_SMALL, "workspace has %zu bytes, %zu needed", workspace_bytes, w.total);
+  unsigned char* base = (unsigned char*)workspace;
+  int32_t* counts = (int32_t*)(base + w.counts);
+  int32_t* offsets = (int32_t*)(base + w.offsets);
+  int32_t* num_padded = (int32_t*)(base + w.num_padded);
+  int32_t* sorted = (int32_t*)(base + w.sorted);
+  int32_t* blocks = (int32_t*)(base + w.blocks);
+  uint8_t* xq = base + w.xq;
+  float* sx = (float*)(base + w.sx);
+  void* H = base + w.H;
+  uint8_t* aq = base + w.aq;
+  float* sa = (float*)(base + w.sa);
+  float* Y = (float*)(base + w.Y);
+  const int block_m = fp8_pick_block_m(S, E);
+  const bool ev = g_nevents == 7;
+  auto mark = [&](int i) { if (ev) (void)hipEventRecord((hipEvent_t)g_events[i], stream); };
+
+  mark(0);
+  int err = launch_align(topk_ids, (int)S, E, block_m, (int)align_capacity(S, E, block_m), counts, offsets, sorted,
+                         blocks, num_padded, stream);
+  if (err != 0) return hip_fail(err, "align launch");
+  mark(1);
+  err = fp8::launch_fp8_quantize(X, T, K, (int)dt, 0, xq, sx, stream);
+  if (err != 0) return hip_fail(err, "activation quantiser launch");
+  mark(2);
+  int st = fp8_moe_grouped_gemm(xq, sx, topk, w1, w1_scale, sorted, blocks, num_padded, (int)S, E, 2 * N, K, block_m,
+                                (int)dt, H, stream);
+  if (st != MOE_OK) return st;
+  mark(3);
+  // rows of slots that were not bucketed hold stale bytes: they are quantised like any other row
+  // and never read again (the second product only gathers bucketed slots)
+  err = fp8::launch_fp8_quantize(H, S, N, (int)dt, 1, aq, sa, stream);
+  if (err != 0) return hip_fail(err, "SiLU-and-multiply quantiser launch");
+  mark(4);
+  st = fp8_moe_grouped_gemm(aq, sa, 1, w2, w2_scale, sorted, blocks, num_padded, (int)S, E, K, N, block_m, 2, Y, stream);
+  if (st != MOE_OK) return st;
+  mark(5);
+  err = launch_combine(Y, 1, 1, topk_weights, topk_ids, E, out, T, topk, K, (int)dt, stream);
+  if (err != 0) return hip_fail(err, "combine launch");
+  mark(6);
   return MOE_OK;
 }
 
