@@ -220,9 +220,23 @@ int moe_import_awq(const int32_t* awq_qweight, const int32_t* awq_qzeros, const 
                    int32_t* qweight, void* scales, uint8_t* zeros, void* stream);
 
 /*
- * Router + layer on one stream: moe_route_topk into tables held in the workspace, then
- * moe_w4a16_layer.  Arguments as for the two; `workspace` of at least
- * moe_w4a16_routed_layer_workspace_bytes(...) bytes, 256-byte aligned.
+ * Router fused with the expert bucketing: moe_route_topk followed by moe_align_by_expert with the
+ * ids staying on the device, as ONE launch for batches of up to 64 tokens (the 16 waves of the
+ * bucketing workgroup route the tokens first, four tokens per wave when E <= 256 and topk <= 16),
+ * as the two kernels back to back beyond that (one compute unit routing more tokens is slower
+ * than the extra launch).  Outputs
+ * are those of the two calls, bit for bit: topk_ids / topk_weights [T, topk] and the five tables
+ * of moe_align_by_expert.  Same limits as the two.
+ */
+int moe_route_align(const float* logits, const float* bias, int T, int E, int topk, int block_m,
+                    int32_t* topk_ids, float* topk_weights, int32_t* expert_counts, int32_t* expert_offsets,
+                    int32_t* sorted_slot_ids, int32_t* block_expert_ids, int32_t* num_padded, void* stream);
+
+/*
+ * Router + layer on one stream: moe_route_align into tables held in the workspace, then the two
+ * grouped GEMMs and the combine of moe_w4a16_layer (four launches up to 64 tokens, five beyond).
+ * Arguments as for the two; `workspace` of at least moe_w4a16_routed_layer_workspace_bytes(...)
+ * bytes, 256-byte aligned.
  */
 size_t moe_w4a16_routed_layer_workspace_bytes(int T, int K, int N, int E, int topk, moe_dtype dt);
 int moe_w4a16_routed_layer(const void* X, const float* logits, const float* bias,

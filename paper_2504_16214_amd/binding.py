@@ -24,7 +24,7 @@ EXPORTS = [
     "fp8_probe_mfma", "moe_set_block_m_override", "moe_last_gemm_plan",
     "moe_w4a16_layer_noalloc", "moe_layer_block_m_for", "moe_set_wide_tiles",
     "fp8_quantize_rows", "fp8_silu_mul_quantize", "fp8_moe_layer_workspace_bytes", "fp8_moe_layer",
-    "fp8_set_layer_block_m",
+    "fp8_set_layer_block_m", "moe_route_align",
 ]
 
 
@@ -107,6 +107,8 @@ def load_library() -> ctypes.CDLL:
     lib.moe_layer_block_m.argtypes = [i32, i32, i32]
     lib.moe_w4a16_layer_noalloc.restype = i32
     lib.moe_w4a16_layer_noalloc.argtypes = [vp] * 10 + [i32] * 7 + [vp]
+    lib.moe_route_align.restype = i32
+    lib.moe_route_align.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.fp8_quantize_rows.restype = i32
     lib.fp8_quantize_rows.argtypes = [vp, i32, i32, i32, vp, vp, vp]
     lib.fp8_silu_mul_quantize.restype = i32
@@ -200,6 +202,17 @@ def moe_route_topk(logits, bias, topk_ids, topk_weights, stream=None) -> None:
     T, E = logits.shape
     _check(load_library().moe_route_topk(_ptr(logits), _ptr(bias), T, E, topk_ids.shape[1], _ptr(topk_ids),
                                          _ptr(topk_weights), _stream(stream)))
+
+
+def moe_route_align(logits, bias, block_m, topk_ids, topk_weights, expert_counts, expert_offsets, sorted_slot_ids,
+                    block_expert_ids, num_padded, stream=None) -> None:
+    """Router + bucketing: logits [T, E] float32 (+ bias [E] or None) -> topk_ids / topk_weights [T, topk] and
+    the five tables of moe_align_by_expert (all preallocated)."""
+    T, E = logits.shape
+    _check(load_library().moe_route_align(_ptr(logits), _ptr(bias), T, E, topk_ids.shape[1], block_m, _ptr(topk_ids),
+                                          _ptr(topk_weights), _ptr(expert_counts), _ptr(expert_offsets),
+                                          _ptr(sorted_slot_ids), _ptr(block_expert_ids), _ptr(num_padded),
+                                          _stream(stream)))
 
 
 def moe_probe_stream_read(src, sink, stream=None) -> None:

@@ -12,19 +12,28 @@
 //      bit yields the mask of lanes holding the same expert, popcount of the lower lanes is
 //      the rank inside the tile, the LDS counter supplies the running base.  Ascending slot
 //      order inside every expert segment follows by construction.
+//
+// route_align_kernel is the same workgroup with the router in front (small batches): each of the
+// 16 waves first routes its share of the tokens (top-k ids and softmax weights, written for the
+// later steps of the layer), then the bucketing runs on the ids the workgroup has just written.
+// One launch instead of two; the ids and tables are bit for bit those of the separate kernels.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+
+#include "router_device.hpp"
 
 namespace moe {
 
 constexpr int kAlignWaves = 16;
 constexpr int kAlignThreads = 64 * kAlignWaves;
 
-__global__ void __launch_bounds__(kAlignThreads)
-align_kernel(const int32_t* __restrict__ topk_ids, int S, int E, int block_m, int capacity, int id_bits,
-             int32_t* __restrict__ expert_counts, int32_t* __restrict__ expert_offsets,
-             int32_t* __restrict__ sorted_slot_ids, int32_t* __restrict__ block_expert_ids,
-             int32_t* __restrict__ num_padded) {
+// The bucketing proper; every thread of the (single) workgroup calls it.  `topk_ids` is not
+// restrict-qualified: in the fused kernel the same workgroup wrote it just before.
+__device__ __forceinline__ void
+align_body(const int32_t* topk_ids, int S, int E, int block_m, int capacity, int id_bits,
+           int32_t* __restrict__ expert_counts, int32_t* __restrict__ expert_offsets,
+           int32_t* __restrict__ sorted_slot_ids, int32_t* __restrict__ block_expert_ids,
+           int32_t* __restrict__ num_padded) {
   extern __shared__ int lds[];
   int* hist = lds;                         // [kAlignWaves][E]
   int* off = lds + kAlignWaves * E;        // [E + 1] padded exclusive offsets
@@ -127,19 +136,89 @@ align_kernel(const int32_t* __restrict__ topk_ids, int S, int E, int block_m, in
   }
 }
 
+__global__ void __launch_bounds__(kAlignThreads)
+align_kernel(const int32_t* __restrict__ topk_ids, int S, int E, int block_m, int capacity, int id_bits,
+             int32_t* __restrict__ expert_counts, int32_t* __restrict__ expert_offsets,
+             int32_t* __restrict__ sorted_slot_ids, int32_t* __restrict__ block_expert_ids,
+             int32_t* __restrict__ num_padded) {
+  align_body(topk_ids, S, E, block_m, capacity, id_bits, expert_counts, expert_offsets, sorted_slot_ids,
+             block_expert_ids, num_padded);
+}
+
+__global__ void __launch_bounds__(kAlignThreads)
+route_align_kernel(const float* __restrict__ logits, const float* __restrict__ bias, int T, int E, int topk,
+                   int32_t* topk_ids, float* __restrict__ topk_weights, int block_m, int capacity, int id_bits,
+                   int32_t* __restrict__ expert_counts, int32_t* __restrict__ expert_offsets,
+                   int32_t* __restrict__ sorted_slot_ids, int32_t* __restrict__ block_expert_ids,
+                   int32_t* __restrict__ num_padded) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  if (E <= kRouter16MaxE && topk <= kRouter16MaxTopk) {
+    // one token per 16-lane row: 64 tokens of the workgroup in flight at a time
+    for (int t = wave * 4 + (lane >> 4); t < T; t += kAlignWaves * 4)      // uniform inside a row
+      route_token_row16(logits + (size_t)t * E, bias, E, topk, lane, topk_ids + (size_t)t * topk,
+                        topk_weights + (size_t)t * topk);
+  } else {
+    for (int t = wave; t < T; t += kAlignWaves)      // wave-uniform trip count
+      route_token(logits + (size_t)t * E, bias, E, topk, lane, topk_ids + (size_t)t * topk,
+                  topk_weights + (size_t)t * topk);
+  }
+  // the ids go to memory for the combine and are read back by this same workgroup: make the
+  // writes visible to its other waves before anyone reads them
+  __threadfence_block();
+  __syncthreads();
+  align_body(topk_ids, T * topk, E, block_m, capacity, id_bits, expert_counts, expert_offsets, sorted_slot_ids,
+             block_expert_ids, num_padded);
+}
+
+static int raise_align_lds(const void* kern, size_t lds, size_t& allowed) {
+  if (lds > allowed) {
+    hipError_t err = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (err != hipSuccess) return (int)err;
+    allowed = lds;
+  }
+  return 0;
+}
+
+// Dynamic LDS beyond 64 KiB needs the per-kernel attribute, remembered per device (the attribute
+// is per device; a process may drive several GPUs).
+constexpr int kAlignMaxDev = 64;
+static size_t g_align_lds[2][kAlignMaxDev];
+
+static int prepare_align_lds(int which, const void* kern, size_t lds) {
+  if (lds <= 64 * 1024) return 0;
+  int dev = 0;
+  hipError_t err = hipGetDevice(&dev);
+  if (err != hipSuccess) return (int)err;
+  if (dev < 0 || dev >= kAlignMaxDev) {
+    size_t none = 0;
+    return raise_align_lds(kern, lds, none);
+  }
+  return raise_align_lds(kern, lds, g_align_lds[which][dev]);
+}
+
+int launch_route_align(const float* logits, const float* bias, int T, int E, int topk, int32_t* topk_ids,
+                       float* topk_weights, int block_m, int capacity, int32_t* expert_counts,
+                       int32_t* expert_offsets, int32_t* sorted_slot_ids, int32_t* block_expert_ids,
+                       int32_t* num_padded, hipStream_t stream) {
+  int id_bits = 0;
+  while ((1 << id_bits) < E) ++id_bits;
+  const size_t lds = (size_t)(kAlignWaves * E + E + 1) * sizeof(int);
+  const int perr = prepare_align_lds(1, reinterpret_cast<const void*>(route_align_kernel), lds);
+  if (perr != 0) return perr;
+  hipLaunchKernelGGL(route_align_kernel, dim3(1), dim3(kAlignThreads), lds, stream, logits, bias, T, E, topk,
+                     topk_ids, topk_weights, block_m, capacity, id_bits, expert_counts, expert_offsets,
+                     sorted_slot_ids, block_expert_ids, num_padded);
+  return (int)hipGetLastError();
+}
+
 int launch_align(const int32_t* topk_ids, int S, int E, int block_m, int capacity,
                  int32_t* expert_counts, int32_t* expert_offsets, int32_t* sorted_slot_ids,
                  int32_t* block_expert_ids, int32_t* num_padded, hipStream_t stream) {
   int id_bits = 0;
   while ((1 << id_bits) < E) ++id_bits;
   const size_t lds = (size_t)(kAlignWaves * E + E + 1) * sizeof(int);
-  static size_t lds_allowed = 64 * 1024;
-  if (lds > lds_allowed) {
-    hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(align_kernel),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (err != hipSuccess) return (int)err;
-    lds_allowed = lds;
-  }
+  const int perr = prepare_align_lds(0, reinterpret_cast<const void*>(align_kernel), lds);
+  if (perr != 0) return perr;
   hipLaunchKernelGGL(align_kernel, dim3(1), dim3(kAlignThreads), lds, stream, topk_ids, S, E, block_m,
                      capacity, id_bits, expert_counts, expert_offsets, sorted_slot_ids,
                      block_expert_ids, num_padded);

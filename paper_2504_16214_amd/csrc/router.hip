@@ -7,25 +7,9 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "router_device.hpp"
+
 namespace moe {
-
-constexpr int kRouterMaxPerLane = 16;   // E <= 64 * 16
-
-__device__ __forceinline__ unsigned long long wave_max_u64(unsigned long long v) {
-#pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) {
-    const unsigned long long o = __shfl_xor(v, off, 64);
-    v = o > v ? o : v;
-  }
-  return v;
-}
-
-__device__ __forceinline__ float wave_sum_f32_lanes_below(float v, int n) {
-  // sum of lanes [0, n) in lane order 0, 1, 2, ... (sequential: k is small and the order is fixed)
-  float s = 0.f;
-  for (int j = 0; j < n; ++j) s += __shfl(v, j, 64);
-  return s;
-}
 
 // grid: ceil(T / 4) workgroups of 256 threads (4 waves = 4 tokens)
 __global__ void __launch_bounds__(256)
@@ -34,46 +18,7 @@ route_topk_kernel(const float* __restrict__ logits, const float* __restrict__ bi
   const int lane = threadIdx.x & 63;
   const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (t >= T) return;                       // whole wave exits together
-  const float* row = logits + (size_t)t * E;
-  // key of element e = lane + 64 i: ordered(float) << 32 | ~e ; 0 marks "absent or taken"
-  unsigned long long key[kRouterMaxPerLane];
-#pragma unroll
-  for (int i = 0; i < kRouterMaxPerLane; ++i) {
-    const int e = lane + 64 * i;
-    key[i] = 0ull;
-    if (e < E) {
-      float v = row[e];
-      if (bias) v = v + bias[e];            // one float32 rounding, as the definition states
-      v = v + 0.0f;                         // -0.0 -> +0.0: signed zeros compare equal
-      uint32_t u = __float_as_uint(v);
-      u = (u & 0x80000000u) ? ~u : (u | 0x80000000u);
-      key[i] = ((unsigned long long)u << 32) | (unsigned long long)(0xffffffffu - (uint32_t)e);
-    }
-  }
-  float my_val = 0.f;                       // lane j keeps the j-th selected logit (j < topk <= 64)
-  int my_id = 0;
-  for (int j = 0; j < topk; ++j) {
-    unsigned long long best = 0ull;
-#pragma unroll
-    for (int i = 0; i < kRouterMaxPerLane; ++i) best = key[i] > best ? key[i] : best;
-    best = wave_max_u64(best);
-    const uint32_t e = 0xffffffffu - (uint32_t)(best & 0xffffffffull);
-    uint32_t u = (uint32_t)(best >> 32);
-    u = (u & 0x80000000u) ? (u & 0x7fffffffu) : ~u;
-    if (lane == j) { my_val = __uint_as_float(u); my_id = (int)e; }
-    // the owner lane retires the element
-#pragma unroll
-    for (int i = 0; i < kRouterMaxPerLane; ++i)
-      if ((int)e == lane + 64 * i) key[i] = 0ull;
-  }
-  // softmax over the k selected logits; the first selected one is the maximum
-  const float m = __shfl(my_val, 0, 64);
-  const float p = lane < topk ? expf(my_val - m) : 0.f;
-  const float denom = wave_sum_f32_lanes_below(p, topk);
-  if (lane < topk) {
-    ids[(size_t)t * topk + lane] = my_id;
-    weights[(size_t)t * topk + lane] = p / denom;
-  }
+  route_token(logits + (size_t)t * E, bias, E, topk, lane, ids + (size_t)t * topk, weights + (size_t)t * topk);
 }
 
 int launch_route_topk(const float* logits, const float* bias, int T, int E, int topk, int32_t* ids,

@@ -89,6 +89,72 @@ def test_router_reproduces_the_workload_routing(name):
     assert np.max(np.abs(w.astype(np.float64) - w_o)) <= W_ATOL
 
 
+def run_route_align(logits, bias, topk, block_m):
+    T, E = logits.shape
+    ld = torch.from_numpy(np.ascontiguousarray(logits, dtype=np.float32)).cuda()
+    bd = None if bias is None else torch.from_numpy(np.ascontiguousarray(bias, dtype=np.float32)).cuda()
+    cap = M.moe_align_capacity(T, topk, E, block_m)
+    ids = torch.full((T, topk), -7, dtype=torch.int32, device="cuda")
+    w = torch.full((T, topk), float("nan"), dtype=torch.float32, device="cuda")
+    out = {
+        "expert_counts": torch.full((E,), -7, dtype=torch.int32, device="cuda"),
+        "expert_offsets": torch.full((E + 1,), -7, dtype=torch.int32, device="cuda"),
+        "sorted_slot_ids": torch.full((max(cap, 1),), -7, dtype=torch.int32, device="cuda"),
+        "block_expert_ids": torch.full((max(cap // block_m, 1),), -7, dtype=torch.int32, device="cuda"),
+        "num_padded": torch.full((1,), -7, dtype=torch.int32, device="cuda"),
+    }
+    M.moe_route_align(ld, bd, block_m, ids, w, out["expert_counts"], out["expert_offsets"], out["sorted_slot_ids"],
+                      out["block_expert_ids"], out["num_padded"])
+    torch.cuda.synchronize()
+    out["capacity"] = cap
+    return ids.cpu().numpy(), w.cpu().numpy(), out
+
+
+def config_logits(cfg):
+    """The logits of a seeded configuration (drawn after X), raw: the skew bias is handed to the router."""
+    rng = np.random.default_rng(cfg.seed)
+    rng.standard_normal((cfg.T, cfg.K))
+    return rng.standard_normal((cfg.T, cfg.E)).astype(np.float32), (skew_bias(cfg.E) if cfg.skew else None)
+
+
+@pytest.mark.parametrize("name", ["tiny", "mixtral_decode", "deepseek_decode", "deepseek_prefill", "skewed_bf16"])
+def test_route_align_on_the_five_configurations(name):
+    """Router fused with the bucketing (one launch up to 64 tokens, the two kernels beyond): ids and
+    tables bit for bit those of the oracle's router followed by its bucketing, on the logits of the
+    five seeded configurations, in the block size the layer uses for them."""
+    cfg = CONFIGS[name]
+    block_m = M.moe_layer_block_m_for(cfg.T, cfg.K, cfg.N, cfg.E, cfg.topk, cfg.group)
+    say(f"route + align on {name} (T={cfg.T}, block_m={block_m})")
+    logits, bias = config_logits(cfg)
+    ids, w, tables = run_route_align(logits, bias, cfg.topk, block_m)
+    ids_o, w_o = O.route_topk(logits, cfg.topk, bias=bias)
+    np.testing.assert_array_equal(ids, ids_o)
+    assert np.max(np.abs(w.astype(np.float64) - w_o)) <= W_ATOL
+    U.assert_align_equal(tables, O.align_by_expert(ids_o, cfg.E, block_m), block_m)
+
+
+@pytest.mark.parametrize("T,E,topk,block_m,with_bias", [
+    (1, 8, 2, 16, False), (63, 100, 5, 32, True), (64, 256, 8, 16, False), (65, 256, 8, 16, False),
+    (50, 256, 16, 16, True), (50, 256, 17, 32, False), (33, 257, 8, 16, False),      # 16-lane rows / whole-wave routing
+    (60, 1024, 64, 64, False), (300, 1024, 64, 64, False), (40, 1, 1, 256, False), (0, 4, 2, 16, False),
+])
+def test_route_align_edges(T, E, topk, block_m, with_bias):
+    say(f"route + align T={T} E={E} topk={topk} block_m={block_m} bias={with_bias}")
+    rng = np.random.default_rng(2000 + T + E)
+    logits = rng.standard_normal((T, E)).astype(np.float32)
+    if T > 2:
+        logits[1, :] = 0.25                                # an all-tie row
+    bias = skew_bias(E) if with_bias else None
+    ids, w, tables = run_route_align(logits, bias, topk, block_m)
+    if T == 0:
+        assert tables["num_padded"].item() == 0
+        return
+    ids_o, w_o = O.route_topk(logits, topk, bias=bias)
+    np.testing.assert_array_equal(ids, ids_o)
+    assert np.max(np.abs(w.astype(np.float64) - w_o)) <= W_ATOL
+    U.assert_align_equal(tables, O.align_by_expert(ids_o, E, block_m), block_m)
+
+
 def test_router_error_paths():
     say("router errors")
     ld = torch.zeros((4, 8), dtype=torch.float32, device="cuda")
