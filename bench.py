@@ -54,6 +54,9 @@ def main():
     ap.add_argument("--prepacked", action="store_true",
                     help="time moe_w4a16_layer_prepacked on weights repacked offline into operand order "
                          "(a different weight format than the benchmark statement's: reported, never the default)")
+    ap.add_argument("--issue-model", action="store_true",
+                    help="time the issue-mix probe (matrix instructions with VALU work and LDS fragment reads "
+                         "per instruction) and print the table the design notes' cost model is fitted to")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run 5 plain 1 GiB device-to-device copies and exit (known-size traffic "
                          "for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE readings)")
@@ -75,9 +78,12 @@ def main():
     if args.config in FP8_MOE_CONFIGS:
         fp8_moe_main(args, FP8_MOE_CONFIGS[args.config])
         return
-    cfg = CONFIGS[args.config]
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+    if args.issue_model:
+        issue_model(M, torch)
+        return
+    cfg = CONFIGS[args.config]
     if args.copy_calibration:
         src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")      # 1 GiB
         dst = torch.empty_like(src)
@@ -166,6 +172,11 @@ def main():
     else:
         roofline = {"bound": "mfma", "achieved": round(g1_tflops, 1), "peak": MFMA_PEAK_TFLOPS,
                     "unit": "TFLOP/s", "frac": round(g1_tflops / MFMA_PEAK_TFLOPS, 4), "traffic": traffic}
+    # `traffic` is NOT measured in this run: it is the FETCH_SIZE + WRITE_SIZE reading of a separate
+    # rocprofv3 --pmc run of this same command, stored in profiles/hbm_traffic.json (null when no
+    # such run was recorded for the configuration)
+    roofline["traffic_source"] = ("profiles/hbm_traffic.json (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, separate run)"
+                                  if traffic is not None else None)
     roofline["kernel"] = "w4a16_gemm_kernel (gate/up projection + SiLU-and-multiply)"
     roofline["kernel_ms"] = round(float(stage_avg[1]), 4)
 
@@ -217,6 +228,36 @@ def main():
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, inp)
     print(json.dumps(result), flush=True)
+
+
+def issue_model(M, torch):
+    """ns per matrix instruction and SIMD for a grid of (VALU operations per instruction, LDS fragment
+    reads per 8 instructions), two waves per SIMD; `ratio` is against the matrix-only rate of the
+    same run (16 cycles per v_mfma_f32_16x16x32_f16), so ratio * 16 is the cost in SIMD cycles."""
+    sink = torch.zeros(1 << 18, dtype=torch.int32, device="cuda")
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    iters = 10000
+
+    def ns_per_mfma(nv, nd):
+        best = 1e30
+        for rep in range(4):
+            e0.record(); M.moe_probe_issue_mix(sink, iters, nv, nd); e1.record(); e1.synchronize()
+            if rep:
+                best = min(best, e0.elapsed_time(e1) * 1e6 / (iters * 8 * 2))       # two waves per SIMD
+        return best
+
+    for _ in range(10):
+        M.moe_probe_issue_mix(sink, iters, 0, 0)      # clocks up
+    base = ns_per_mfma(0, 0)
+    table = []
+    for nv in (0, 1, 2, 3, 4, 6):
+        for nd in (0, 2, 4, 8):
+            t = ns_per_mfma(nv, nd)
+            table.append({"valu_per_mfma": nv, "lds_reads_per_mfma": nd / 8.0, "ns_per_mfma": round(t, 3),
+                          "ratio": round(t / base, 3), "simd_cycles": round(16.0 * t / base, 1),
+                          "model_8_4v_20r": round(max(16.0, 8 + 4 * nv) + 20.0 * nd / 8.0, 1)})
+    print(json.dumps({"issue_model": {"matrix_only_ns_per_mfma": round(base, 3),
+                                      "matrix_only_TFLOPs": round(16384.0 / base * 1024 / 1e3, 1), "table": table}}))
 
 
 FP8_MFMA_PEAK_TFLOPS = 5000.0  # dense fp8 MFMA, published

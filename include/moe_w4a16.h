@@ -125,18 +125,27 @@ int moe_route_topk(const float* logits, const float* bias, int T, int E, int top
 
 /*
  * act[s, n] = silu(H[s, n]) * H[s, N + n],  silu(x) = x / (1 + exp(-x)).
- * H [S, 2N] dt (columns [0,N) gate, [N,2N) up), act [S, N] dt; fp32 math.
- * The gated activation between the two projections of each expert.
+ * H [S, 2N] dt (columns [0,N) gate, [N,2N) up), act [S, N] dt; fp32 math, one rounding.
+ * The gated activation between the two projections of each expert.  The paper is silent on it
+ * (it times the layer as a whole, Section VII-B / Fig. 10); the definition is the benchmark
+ * statement's "SiLU-and-multiply".
  */
 int moe_silu_mul(const void* H, void* act, int S, int N, moe_dtype dt, void* stream);
 
 /*
  * out[t, c] = sum_{j<topk} topk_weights[t, j] * Y[t*topk + j, c]
  * Y [T*topk, K] dt, topk_weights [T, topk] float32, out [T, K] dt;
- * fp32 accumulation in j order, one rounding.
+ * fp32 accumulation in j order, one rounding.  The paper is silent on this step as well (the
+ * benchmark statement's "top-k-weighted combine").
+ * moe_combine reads every row of Y: in a staged chain with expert ids outside [0, E) the rows
+ * of those slots were never written by moe_w4a16_grouped_gemm, so either clear Y first or use
+ * moe_combine_masked, which takes the ids and lets such slots contribute zero (what the fused
+ * layer does).
  */
 int moe_combine(const void* Y, const float* topk_weights, void* out,
                 int T, int topk, int K, moe_dtype dt, void* stream);
+int moe_combine_masked(const void* Y, const float* topk_weights, const int32_t* topk_ids, int E, void* out,
+                       int T, int topk, int K, moe_dtype dt, void* stream);
 
 /* Bytes of workspace moe_w4a16_layer needs for these sizes (0 if invalid). */
 size_t moe_w4a16_layer_workspace_bytes(int T, int K, int N, int E, int topk, moe_dtype dt);
@@ -303,9 +312,19 @@ int moe_set_stage_events(void* const* events, int n);
  *
  * moe_probe_mfma: 512 workgroups x 4 waves each issue iters x 16 register-resident
  * v_mfma_f32_16x16x32_f16 (16384 flop each).  sink: >= 512 KiB of device scratch.
+ *
+ * moe_probe_issue_mix: 256 workgroups x 8 waves (two waves per SIMD) each issue iters x 8
+ * v_mfma_f32_16x16x32_f16 with valu_per_mfma independent VALU operations after every one and
+ * lds_reads_per_8_mfma ds_read_b128 (the GEMM's fragment-read pattern) per eight: the instruction
+ * mix of the mixed-type GEMM's inner loop without its memory traffic.  valu_per_mfma in
+ * {0, 1, 2, 3, 4, 6}, lds_reads_per_8_mfma in {0, 2, 4, 8}.  sink: >= 512 KiB of device scratch.
+ * `bench.py --issue-model` times the grid of combinations; the cost model the design notes use
+ * (time per matrix instruction = 8 + 4 x VALU + about 20 x LDS reads, in SIMD cycles) is fitted
+ * to its output.
  */
 int moe_probe_stream_read(const void* src, size_t bytes, void* sink, void* stream);
 int moe_probe_mfma(void* sink, int iters, void* stream);
+int moe_probe_issue_mix(void* sink, int iters, int valu_per_mfma, int lds_reads_per_8_mfma, void* stream);
 int moe_set_tile_override(int mt, int nt);
 int moe_set_scale_path(int mode);
 int moe_set_tiles_per_workgroup(int n);

@@ -6,9 +6,9 @@ library.  There is no CPU fallback: if the library has not been built the bindin
 """
 from .binding import (  # noqa: F401
     MOE_F16, MOE_BF16, MoEError, library_path, load_library,
-    moe_align_capacity, moe_align_by_expert, moe_w4a16_grouped_gemm, moe_silu_mul, moe_combine,
+    moe_align_capacity, moe_align_by_expert, moe_w4a16_grouped_gemm, moe_silu_mul, moe_combine, moe_combine_masked,
     moe_w4a16_layer_workspace_bytes, moe_w4a16_layer, moe_layer_block_m,
-    moe_w4a16_dense_gemm, moe_route_topk, moe_route_align, moe_probe_stream_read, moe_probe_mfma,
+    moe_w4a16_dense_gemm, moe_route_topk, moe_route_align, moe_probe_stream_read, moe_probe_mfma, moe_probe_issue_mix,
     moe_w4a16_routed_layer_workspace_bytes, moe_w4a16_routed_layer,
     moe_repack_qweight, moe_w4a16_layer_prepacked, moe_import_awq,
     fp8_blockwise_gemm_workspace_bytes, fp8_blockwise_gemm, fp8_moe_grouped_gemm, fp8_set_plan_override,

@@ -24,7 +24,8 @@ EXPORTS = [
     "fp8_probe_mfma", "moe_set_block_m_override", "moe_last_gemm_plan",
     "moe_w4a16_layer_noalloc", "moe_layer_block_m_for", "moe_set_wide_tiles",
     "fp8_quantize_rows", "fp8_silu_mul_quantize", "fp8_moe_layer_workspace_bytes", "fp8_moe_layer",
-    "fp8_set_layer_block_m", "moe_route_align",
+    "fp8_set_layer_block_m", "moe_route_align", "moe_combine_masked",
+    "moe_probe_issue_mix",
 ]
 
 
@@ -63,6 +64,8 @@ def load_library() -> ctypes.CDLL:
     lib.moe_route_topk.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp]
     lib.moe_probe_stream_read.restype = i32
     lib.moe_probe_stream_read.argtypes = [vp, sz, vp, vp]
+    lib.moe_probe_issue_mix.restype = i32
+    lib.moe_probe_issue_mix.argtypes = [vp, i32, i32, i32, vp]
     lib.moe_probe_mfma.restype = i32
     lib.moe_probe_mfma.argtypes = [vp, i32, vp]
     lib.moe_w4a16_routed_layer_workspace_bytes.restype = sz
@@ -87,6 +90,8 @@ def load_library() -> ctypes.CDLL:
     lib.moe_w4a16_layer_prepacked.argtypes = [vp] * 10 + [i32] * 7 + [vp, sz, vp]
     lib.moe_silu_mul.restype = i32
     lib.moe_silu_mul.argtypes = [vp, vp, i32, i32, i32, vp]
+    lib.moe_combine_masked.restype = i32
+    lib.moe_combine_masked.argtypes = [vp, vp, vp, i32, vp, i32, i32, i32, i32, vp]
     lib.moe_combine.restype = i32
     lib.moe_combine.argtypes = [vp, vp, vp, i32, i32, i32, i32, vp]
     lib.moe_w4a16_layer_workspace_bytes.restype = sz
@@ -146,6 +151,57 @@ def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
     return t.data_ptr()
 
 
+def _expect(t, name: str, dtype=None, shape=None, min_numel=None) -> None:
+    """Argument checks the C ABI cannot make (it sees raw pointers): raise ValueError before any
+    launch on a wrong element type, a wrong shape or a buffer that is too small.  A dimension given
+    as None is not checked."""
+    if t is None:
+        raise ValueError(f"{name}: a tensor is required")
+    if dtype is not None:
+        allowed = dtype if isinstance(dtype, (tuple, list)) else (dtype,)
+        if t.dtype not in allowed:
+            raise ValueError(f"{name}: dtype {t.dtype}, expected {' or '.join(str(d) for d in allowed)}")
+    if shape is not None:
+        if t.dim() != len(shape) or any(w is not None and int(g) != int(w) for g, w in zip(t.shape, shape)):
+            raise ValueError(f"{name}: shape {tuple(t.shape)}, expected {tuple('*' if w is None else w for w in shape)}")
+    if min_numel is not None and t.numel() < min_numel:
+        raise ValueError(f"{name}: {t.numel()} elements, at least {min_numel} needed")
+
+
+_F16 = (torch.float16, torch.bfloat16)
+
+
+def _expect_weights(qweight, scales, zeros, group_size: int, act_dtype, what: str):
+    """qweight [E, rows, red/8] int32 with scales / zeros [E, rows, red/group]."""
+    _expect(qweight, f"{what} qweight", torch.int32)
+    if qweight.dim() != 3:
+        raise ValueError(f"{what} qweight: expected [E, rows, K/8], got shape {tuple(qweight.shape)}")
+    E, rows, kw = qweight.shape
+    if group_size < 1 or (kw * 8) % group_size != 0:
+        return          # the library reports unsupported group sizes with its own status and message
+    G = kw * 8 // group_size
+    _expect(scales, f"{what} scales", act_dtype, (E, rows, G))
+    _expect(zeros, f"{what} zeros", torch.uint8, (E, rows, G))
+
+
+def _expect_layer(X, topk_ids, topk_weights, qw1, s1, z1, qw2, s2, z2, out, group_size):
+    _expect(X, "X", _F16)
+    if X.dim() != 2:
+        raise ValueError(f"X: expected [T, K], got shape {tuple(X.shape)}")
+    T, K = X.shape
+    _expect_weights(qw1, s1, z1, group_size, X.dtype, "W1")
+    E, N2, kw1 = qw1.shape
+    if kw1 * 8 != K or N2 % 2 != 0:
+        raise ValueError(f"W1 qweight: shape {tuple(qw1.shape)} does not match X [T, {K}] (expected [E, 2N, {K // 8}])")
+    _expect_weights(qw2, s2, z2, group_size, X.dtype, "W2")
+    if tuple(qw2.shape) != (E, K, N2 // 2 // 8):
+        raise ValueError(f"W2 qweight: shape {tuple(qw2.shape)}, expected {(E, K, N2 // 2 // 8)}")
+    if topk_ids is not None:
+        _expect(topk_ids, "topk_ids", torch.int32, (T, None))
+        _expect(topk_weights, "topk_weights", torch.float32, tuple(topk_ids.shape))
+    _expect(out, "out", X.dtype, (T, K))
+
+
 def _stream(stream) -> int:
     if stream is None:
         return torch.cuda.current_stream().cuda_stream
@@ -175,7 +231,16 @@ def moe_layer_block_m(T: int, E: int, topk: int) -> int:
 def moe_align_by_expert(topk_ids, E, block_m, expert_counts, expert_offsets, sorted_slot_ids,
                         block_expert_ids, num_padded, stream=None) -> None:
     """topk_ids [T, topk] int32; outputs are preallocated int32 device tensors."""
+    _expect(topk_ids, "topk_ids", torch.int32)
+    if topk_ids.dim() != 2:
+        raise ValueError(f"topk_ids: expected [T, topk], got shape {tuple(topk_ids.shape)}")
     T, topk = topk_ids.shape
+    cap = moe_align_capacity(T, topk, E, block_m)
+    _expect(expert_counts, "expert_counts", torch.int32, min_numel=E)
+    _expect(expert_offsets, "expert_offsets", torch.int32, min_numel=E + 1)
+    _expect(sorted_slot_ids, "sorted_slot_ids", torch.int32, min_numel=cap)
+    _expect(block_expert_ids, "block_expert_ids", torch.int32, min_numel=cap // max(block_m, 1))
+    _expect(num_padded, "num_padded", torch.int32, min_numel=1)
     _check(load_library().moe_align_by_expert(_ptr(topk_ids), T, topk, E, block_m, _ptr(expert_counts),
                                               _ptr(expert_offsets), _ptr(sorted_slot_ids),
                                               _ptr(block_expert_ids), _ptr(num_padded), _stream(stream)))
@@ -183,7 +248,17 @@ def moe_align_by_expert(topk_ids, E, block_m, expert_counts, expert_offsets, sor
 
 def moe_w4a16_grouped_gemm(A, row_div, qweight, scales, zeros, sorted_slot_ids, block_expert_ids,
                            num_padded, num_slots, group_size, block_m, C, stream=None) -> None:
+    _expect(A, "A", _F16)
+    _expect_weights(qweight, scales, zeros, group_size, A.dtype, "W")
     E, N_out, kw = qweight.shape
+    if A.dim() != 2 or A.shape[1] != kw * 8 or A.shape[0] * row_div < num_slots:
+        raise ValueError(f"A: shape {tuple(A.shape)}, expected [>= ceil({num_slots} / {row_div}), {kw * 8}]")
+    _expect(C, "C", (A.dtype,), (None, N_out), min_numel=num_slots * N_out)
+    if block_m in (16, 32, 64, 128, 256):
+        cap = moe_align_capacity(num_slots, 1, E, block_m)        # depends on T * topk only
+        _expect(sorted_slot_ids, "sorted_slot_ids", torch.int32, min_numel=cap)
+        _expect(block_expert_ids, "block_expert_ids", torch.int32, min_numel=cap // block_m)
+    _expect(num_padded, "num_padded", torch.int32, min_numel=1)
     _check(load_library().moe_w4a16_grouped_gemm(
         _ptr(A), row_div, _ptr(qweight), _ptr(scales), _ptr(zeros), _ptr(sorted_slot_ids),
         _ptr(block_expert_ids), _ptr(num_padded), num_slots, E, N_out, kw * 8, group_size, block_m,
@@ -192,14 +267,23 @@ def moe_w4a16_grouped_gemm(A, row_div, qweight, scales, zeros, sorted_slot_ids, 
 
 def moe_w4a16_dense_gemm(A, qweight, scales, zeros, group_size, C, stream=None) -> None:
     """A [M, K] fp16/bf16, qweight [N, K/8] int32, scales [N, K/g], zeros [N, K/g] uint8, C [M, N]."""
+    _expect(A, "A", _F16)
+    _expect_weights(qweight[None], scales[None], zeros[None], group_size, A.dtype, "W")
     N_out, kw = qweight.shape
+    _expect(A, "A", shape=(None, kw * 8))
+    _expect(C, "C", (A.dtype,), (A.shape[0], N_out))
     _check(load_library().moe_w4a16_dense_gemm(_ptr(A), _ptr(qweight), _ptr(scales), _ptr(zeros), A.shape[0],
                                                N_out, kw * 8, group_size, _dt(A), _ptr(C), _stream(stream)))
 
 
 def moe_route_topk(logits, bias, topk_ids, topk_weights, stream=None) -> None:
     """logits [T, E] float32, bias [E] float32 or None; outputs [T, topk] int32 / float32."""
+    _expect(logits, "logits", torch.float32)
     T, E = logits.shape
+    if bias is not None:
+        _expect(bias, "bias", torch.float32, (E,))
+    _expect(topk_ids, "topk_ids", torch.int32, (T, None))
+    _expect(topk_weights, "topk_weights", torch.float32, tuple(topk_ids.shape))
     _check(load_library().moe_route_topk(_ptr(logits), _ptr(bias), T, E, topk_ids.shape[1], _ptr(topk_ids),
                                          _ptr(topk_weights), _stream(stream)))
 
@@ -224,15 +308,35 @@ def moe_probe_mfma(sink, iters: int, stream=None) -> None:
     _check(load_library().moe_probe_mfma(_ptr(sink), iters, _stream(stream)))
 
 
+def moe_probe_issue_mix(sink, iters: int, valu_per_mfma: int, lds_reads_per_8_mfma: int, stream=None) -> None:
+    _check(load_library().moe_probe_issue_mix(_ptr(sink), iters, valu_per_mfma, lds_reads_per_8_mfma, _stream(stream)))
+
+
 def moe_silu_mul(H, act, stream=None) -> None:
+    _expect(H, "H", _F16)
     S, N2 = H.shape
+    _expect(act, "act", (H.dtype,), (S, N2 // 2))
     _check(load_library().moe_silu_mul(_ptr(H), _ptr(act), S, N2 // 2, _dt(H), _stream(stream)))
 
 
 def moe_combine(Y, topk_weights, out, stream=None) -> None:
+    _expect(topk_weights, "topk_weights", torch.float32)
     T, topk = topk_weights.shape
+    _expect(Y, "Y", _F16, (T * topk, None))
+    _expect(out, "out", (Y.dtype,), (T, Y.shape[1]))
     _check(load_library().moe_combine(_ptr(Y), _ptr(topk_weights), _ptr(out), T, topk, Y.shape[1], _dt(Y),
                                       _stream(stream)))
+
+
+def moe_combine_masked(Y, topk_weights, topk_ids, E: int, out, stream=None) -> None:
+    """moe_combine in which slots whose expert id lies outside [0, E) contribute zero."""
+    _expect(topk_weights, "topk_weights", torch.float32)
+    T, topk = topk_weights.shape
+    _expect(topk_ids, "topk_ids", torch.int32, (T, topk))
+    _expect(Y, "Y", _F16, (T * topk, None))
+    _expect(out, "out", (Y.dtype,), (T, Y.shape[1]))
+    _check(load_library().moe_combine_masked(_ptr(Y), _ptr(topk_weights), _ptr(topk_ids), E, _ptr(out), T, topk,
+                                             Y.shape[1], _dt(Y), _stream(stream)))
 
 
 def moe_w4a16_layer_workspace_bytes(T, K, N, E, topk, dt) -> int:
@@ -241,6 +345,8 @@ def moe_w4a16_layer_workspace_bytes(T, K, N, E, topk, dt) -> int:
 
 def moe_w4a16_layer(X, topk_ids, topk_weights, qw1, s1, z1, qw2, s2, z2, out, group_size, workspace,
                     stream=None) -> None:
+    _expect_layer(X, topk_ids, topk_weights, qw1, s1, z1, qw2, s2, z2, out, group_size)
+    _expect(workspace, "workspace", torch.uint8)
     T, K = X.shape
     E, N2, _ = qw1.shape
     topk = topk_ids.shape[1]
@@ -252,6 +358,7 @@ def moe_w4a16_layer(X, topk_ids, topk_weights, qw1, s1, z1, qw2, s2, z2, out, gr
 
 def moe_w4a16_layer_noalloc(X, topk_ids, topk_weights, qw1, s1, z1, qw2, s2, z2, out, group_size, stream=None) -> None:
     """moe_w4a16_layer on the library's built-in scratch array: no workspace, no allocation."""
+    _expect_layer(X, topk_ids, topk_weights, qw1, s1, z1, qw2, s2, z2, out, group_size)
     T, K = X.shape
     E, N2, _ = qw1.shape
     topk = topk_ids.shape[1]
@@ -266,6 +373,11 @@ def moe_w4a16_routed_layer_workspace_bytes(T, K, N, E, topk, dt) -> int:
 
 def moe_w4a16_routed_layer(X, logits, bias, qw1, s1, z1, qw2, s2, z2, out, topk, group_size, workspace,
                            stream=None) -> None:
+    _expect_layer(X, None, None, qw1, s1, z1, qw2, s2, z2, out, group_size)
+    _expect(logits, "logits", torch.float32, (X.shape[0], qw1.shape[0]))
+    if bias is not None:
+        _expect(bias, "bias", torch.float32, (qw1.shape[0],))
+    _expect(workspace, "workspace", torch.uint8)
     T, K = X.shape
     E, N2, _ = qw1.shape
     _check(load_library().moe_w4a16_routed_layer(

@@ -24,6 +24,7 @@ int launch_route_align(const float*, const float*, int, int, int, int32_t*, floa
                        int32_t*, int32_t*, int32_t*, hipStream_t);
 int launch_stream_read(const void*, size_t, uint32_t*, int, hipStream_t);
 int launch_mfma_loop(float*, int, int, hipStream_t);
+int launch_issue_mix(float*, int, int, int, hipStream_t);
 int launch_combine(const void*, int, int, const float*, const int32_t*, int, void*, long long, int, int, int,
                    hipStream_t);
 }  // namespace moe
@@ -447,6 +448,16 @@ int moe_probe_mfma(void* sink, int iters, void* stream) {
   return MOE_OK;
 }
 
+int moe_probe_issue_mix(void* sink, int iters, int valu_per_mfma, int lds_reads_per_8_mfma, void* stream) {
+  if (!sink || iters < 1) return fail(MOE_INVALID_ARGUMENT, "probe needs a sink and iters >= 1");
+  const int err = launch_issue_mix((float*)sink, iters, valu_per_mfma, lds_reads_per_8_mfma, (hipStream_t)stream);
+  if (err == -1)
+    return fail(MOE_UNSUPPORTED_SHAPE, "issue-mix probe: valu_per_mfma must be 0, 1, 2, 3, 4 or 6 and "
+                "lds_reads_per_8_mfma 0, 2, 4 or 8");
+  if (err != 0) return hip_fail(err, "issue-mix probe launch");
+  return MOE_OK;
+}
+
 int moe_silu_mul(const void* H, void* act, int S, int N, moe_dtype dt, void* stream) {
   if (S < 0 || N < 1) return fail(MOE_INVALID_ARGUMENT, "need S >= 0 and N >= 1");
   if (dt != MOE_F16 && dt != MOE_BF16) return fail(MOE_INVALID_ARGUMENT, "dt must be MOE_F16 or MOE_BF16");
@@ -468,6 +479,19 @@ int moe_combine(const void* Y, const float* topk_weights, void* out, int T, int 
   if (K % 8 == 0 && ((uintptr_t)Y | (uintptr_t)out) % 16 != 0)
     return fail(MOE_INVALID_ARGUMENT, "Y and out must be 16-byte aligned");
   const int err = launch_combine(Y, 0, 1, topk_weights, nullptr, 0, out, T, topk, K, (int)dt, (hipStream_t)stream);
+  if (err != 0) return hip_fail(err, "combine launch");
+  return MOE_OK;
+}
+
+int moe_combine_masked(const void* Y, const float* topk_weights, const int32_t* topk_ids, int E, void* out, int T,
+                       int topk, int K, moe_dtype dt, void* stream) {
+  if (T < 0 || topk < 1 || K < 1 || E < 1) return fail(MOE_INVALID_ARGUMENT, "need T >= 0, topk >= 1, K >= 1, E >= 1");
+  if (dt != MOE_F16 && dt != MOE_BF16) return fail(MOE_INVALID_ARGUMENT, "dt must be MOE_F16 or MOE_BF16");
+  if (T == 0) return MOE_OK;
+  if (!Y || !topk_weights || !topk_ids || !out) return fail(MOE_INVALID_ARGUMENT, "null pointer argument");
+  if (K % 8 == 0 && ((uintptr_t)Y | (uintptr_t)out) % 16 != 0)
+    return fail(MOE_INVALID_ARGUMENT, "Y and out must be 16-byte aligned");
+  const int err = launch_combine(Y, 0, 1, topk_weights, topk_ids, E, out, T, topk, K, (int)dt, (hipStream_t)stream);
   if (err != 0) return hip_fail(err, "combine launch");
   return MOE_OK;
 }

@@ -293,7 +293,7 @@ __device__ __forceinline__ WordVec<KW> lds_read_words(const unsigned char* p) {
 constexpr int kXRowPad = 32;
 constexpr int kWRowPad(int ks) { return ks >= 512 ? 16 : 32; }   // 512-k stages: LDS room for three workgroups
 // activation tile buffers in LDS per token-tile size (see TileGeom::XBUFS)
-constexpr int kXBufs(int mt, int ks) { return (mt == 2 || ks >= 512) ? 1 : 2; }
+constexpr int kXBufs(int mt, int ks, int wv = 4) { return wv == 8 ? 3 : (mt == 2 || ks >= 512) ? 1 : 2; }
 
 template <int MT, int NT, int KS, int WV = 4>
 struct TileGeom {
@@ -311,8 +311,9 @@ struct TileGeom {
   static constexpr int WPASS = NW / RPI;     // weight load instructions per stage per wave
   static_assert(XPASS >= 1 && WPASS >= 1, "tile too small for the load mapping");
   // Activation tile buffers: two (one barrier per stage) except for 32-slot tiles, where a single
-  // buffer (two barriers per stage) is what lets a third workgroup fit on a CU.
-  static constexpr int XBUFS = kXBufs(MT, KS);
+  // buffer (two barriers per stage) is what lets a third workgroup fit on a CU, and for the
+  // eight-wave tile, whose skewed pipeline rotates three.
+  static constexpr int XBUFS = kXBufs(MT, KS, WV);
   static size_t lds_bytes(int G, int szr, int pre = 0) {
     return (size_t)XBUFS * M_T * XP + (pre ? 0 : (size_t)WV * NW * WP) + (szr ? 0 : (size_t)G * N_T * 4) +
            (size_t)M_T * 4;
@@ -916,6 +917,133 @@ w4a16_gemm_kernel(const GemmParams p) {
     for (int s = 0; s < NT; ++s) unit[s] = 1.f;
   };
 
+  if constexpr (WV == 8) {
+    // ---- skewed pipeline of the eight-wave tile --------------------------------------------
+    // All eight waves of the workgroup run in step, so whatever one wave waits for, the whole CU
+    // waits for.  Three activation buffers take every wait off the critical path:
+    //   step g:  store stage g+1 (fetched during step g-1) into its buffer; fetch stage g+2 (X) and
+    //            g+1 (weights); multiply words 0 and 1 of stage g; BARRIER; multiply words 2 and 3,
+    //            and while word 3 multiplies read the first fragments of stage g+1.
+    // The barrier sits in the middle of a stage's matrix work: the stores it publishes were issued
+    // half a stage earlier, the fragments read after it are needed half a stage later, and the
+    // buffer a step writes was last read two steps before (its readers passed the previous
+    // barrier), so nothing waits on LDS latency, on the store, or on the global loads.
+    static_assert(PRE == 2 && SZR == 1 && KS == 128 && KW == 4 && UCH == 1 && UNR == 4 && PDW == 1 && PDX == 1 &&
+                  RS == 1 && XBUFS == 3 && WPASS == NT, "the skewed pipeline is written for the 128-k register-scale tile");
+    constexpr int XBYTES = M_T * XP;
+    MOE_LOAD_X(lx_st, xr[0])          // stage 1 (stage 0 is in buffer 0 already)
+    MOE_ADVANCE_X_CURSOR()
+    unsigned char* xb_cur = xs;
+    unsigned char* xb_nxt = xs + XBYTES;
+    unsigned char* xb_fre = xs + 2 * XBYTES;
+    u32x4 a_pf[ML];                   // activation fragments of the next word, one word ahead
+#pragma unroll
+    for (int mt = 0; mt < ML; ++mt)
+      a_pf[mt] = *reinterpret_cast<const u32x4*>(xb_cur + (mt * 16 + ln) * XP + 16 * lj);
+    DeqCtx<DT, ZM> ctx[NT];
+    float rs[NT];
+    u32x4 zop[NT];
+    // word i of the stage: its fragments are in a_pf; start the reads of the following word (word 0
+    // of the next stage after word 3) from rd_buf, unpack, multiply.
+    auto word = [&](auto ic, auto rc, const unsigned char* rd_buf) __attribute__((always_inline)) {
+      constexpr int i = decltype(ic)::value;
+      constexpr int R = decltype(rc)::value;
+      u32x4 a_cur[ML];
+#pragma unroll
+      for (int mt = 0; mt < ML; ++mt) a_cur[mt] = a_pf[mt];
+#pragma unroll
+      for (int mt = 0; mt < ML; ++mt)
+        a_pf[mt] = *reinterpret_cast<const u32x4*>(rd_buf + (mt * 16 + ln) * XP + 16 * (lj + 4 * ((i + 1) & 3)));
+      if constexpr (i == 0) {
+        bool zero_scale[NT];
+        bool any_zero = false;
+#pragma unroll
+        for (int s = 0; s < NT; ++s) {
+          constexpr int gp = R % PG;
+          ctx[s] = DeqCtx<DT, ZM>::from_panel(gp, s_cur[s][gp >> 1], z_cur[s][gp >> 2], z4_cur[s][gp >> 2], uk);
+          if constexpr (ZM) zop[s] = ctx[s].zoperand();
+          zero_scale[s] = ctx[s].s == 0.f;
+          any_zero |= zero_scale[s];
+          rs[s] = zero_scale[s] ? 1.f : unit[s] * __builtin_amdgcn_rcpf(ctx[s].s);
+          unit[s] = zero_scale[s] ? unit[s] : ctx[s].s;
+        }
+        if (__builtin_expect(__ballot(any_zero) != 0ull, 0)) {
+          asm volatile("" ::: "memory");      // rare: a real branch (see the four-wave path)
+#pragma unroll
+          for (int s = 0; s < NT; ++s) {
+            const uint32_t zword = ctx[s].zero_point() * 0x11111111u;
+            if (zero_scale[s]) wcur[s] = u32x4{zword, zword, zword, zword};
+          }
+        }
+      }
+      u32x4 b[NT];
+#pragma unroll
+      for (int s = 0; s < NT; ++s) {
+        const uint32_t w = i == 0 ? wcur[s].x : i == 1 ? wcur[s].y : i == 2 ? wcur[s].z : wcur[s].w;
+        b[s] = dequant_word<DT, ZM>(w, ctx[s], uk);
+      }
+#pragma unroll
+      for (int mt = 0; mt < ML; ++mt) {
+#pragma unroll
+        for (int s = 0; s < NT; ++s) {
+          if constexpr (i == 0) {
+#pragma unroll
+            for (int c = 0; c < 4; ++c) acc[mt][s][c] *= rs[s];
+          }
+          acc[mt][s] = mfma16x16x32<DT>(a_cur[mt], b[s], acc[mt][s]);
+        }
+        if constexpr (ZM) {
+#pragma unroll
+          for (int s = 0; s < NT; ++s) acc[mt][s] = mfma16x16x32<DT>(a_cur[mt], zop[s], acc[mt][s]);
+        }
+      }
+    };
+    int c_t = 0, c_st = 0;
+    const int trips = ntl * npan;
+    for (int trip = 0; trip < trips; ++trip) {
+      load_sz(sp_pan * PG, s_nxt, z_nxt);
+      if (__builtin_expect(++sp_pan == npan, 0)) {
+        asm volatile("");
+        sp_pan = 0;
+        if (++sp_t < ntl) set_sz_rows(tile0 + sp_t);
+      }
+      [&]<int... Rs>(std::integer_sequence<int, Rs...>) {
+        (([&] {
+           constexpr int r = Rs;
+           // the stage fetched during the previous step goes to the buffer nobody reads any more
+#pragma unroll
+           for (int ps = 0; ps < XLIVE; ++ps)
+             *reinterpret_cast<u32x4*>(xb_nxt + (ps * RPP + xr_row) * XP + xw_pos * 16) = interleave8(xr[0][ps]);
+#pragma unroll
+           for (int q = 0; q < WPASS; ++q) wcur[q] = wr[0][q];
+           MOE_LOAD_X(lx_st, xr[0])
+           MOE_ADVANCE_X_CURSOR()
+           MOE_LOAD_W(ld_st, wr[0])
+           MOE_ADVANCE_W_CURSOR()
+           word(std::integral_constant<int, 0>{}, std::integral_constant<int, r>{}, xb_cur);
+           word(std::integral_constant<int, 1>{}, std::integral_constant<int, r>{}, xb_cur);
+           __syncthreads();
+           word(std::integral_constant<int, 2>{}, std::integral_constant<int, r>{}, xb_cur);
+           word(std::integral_constant<int, 3>{}, std::integral_constant<int, r>{}, xb_nxt);
+           unsigned char* const t_ = xb_cur;
+           xb_cur = xb_nxt; xb_nxt = xb_fre; xb_fre = t_;
+         }()),
+         ...);
+      }(std::make_integer_sequence<int, UNR>{});
+#pragma unroll
+      for (int s = 0; s < NT; ++s) {
+#pragma unroll
+        for (int i = 0; i < PG / 2; ++i) s_cur[s][i] = s_nxt[s][i];
+      }
+      adopt_zero_points(z_nxt);
+      c_st += UNR;
+      if (c_st == nst_pad) {
+        store_tile(tile0 + c_t);
+        c_st = 0;
+        ++c_t;
+      }
+    }
+  } else {
   // Step: issue the loads PD stages ahead into the ring slot whose stage went to LDS in the
   // previous step, compute the current stage from LDS, move the next stage from its ring slot
   // into LDS, barrier.  UNR steps per trip so ring slots, activation buffers and (SZR) the scale
@@ -969,6 +1097,7 @@ w4a16_gemm_kernel(const GemmParams p) {
       ++c_t;
     }
   }
+  }    // four-wave pipeline
   };   // tile_body
 
   if constexpr (SPEC) {

@@ -78,6 +78,64 @@ mfma_loop_kernel(float* __restrict__ sink, int iters) {
   sink[(size_t)blockIdx.x * 256 + threadIdx.x] = c0[0] + c1[1] + c2[2] + c3[3];
 }
 
+// Issue-mix probe: what one SIMD sustains when matrix instructions share it with VALU work and LDS
+// fragment reads, the three things the mixed-type GEMM's inner loop is made of.  Per 8 independent
+// v_mfma_f32_16x16x32_f16 a wave issues 8 * NV independent VALU operations and ND ds_read_b128 in
+// the GEMM's fragment-read pattern (row pitch 18 chunks).  256 workgroups of 8 waves = two waves
+// per SIMD on every CU.  The instruction order is fixed by inline assembly; results are not
+// meaningful numbers (nothing waits for a matrix result before it is overwritten by a later one
+// of the same chain, and the LDS is never initialised): the probe measures issue rates only.
+template <int NV, int ND>
+__global__ void __launch_bounds__(512)
+issue_mix_kernel(float* __restrict__ sink, int iters) {
+  extern __shared__ __align__(16) unsigned char mix_lds[];
+  f32x4_t acc[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) acc[i] = f32x4_t{0, 0, 0, 0};
+  u32x4_t a = {0x3c003c00u + threadIdx.x, 0x3c003c00u, 0x3c003c00u, 0x3c003c00u}, b = a;
+  uint32_t x[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) x[i] = threadIdx.x * 7 + i;
+  uint32_t m1 = 0x000F000Fu, o1 = 0x64006400u;
+  asm volatile("" : "+v"(m1), "+v"(o1));
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const uint32_t addr = wave * 8192 + ((lane & 15) * 18 + (lane >> 4)) * 16;
+  u32x4_t r[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) r[i] = a;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      asm volatile("v_mfma_f32_16x16x32_f16 %0, %1, %2, %0" : "+v"(acc[u]) : "v"(r[u]), "v"(b));
+#pragma unroll
+      for (int v = 0; v < NV; ++v)
+        asm volatile("v_and_or_b32 %0, %0, %1, %2" : "+v"(x[(u * NV + v) % 8]) : "v"(m1), "v"(o1));
+      if (u < ND) asm volatile("ds_read_b128 %0, %1" : "=v"(r[(u + 4) % 8]) : "v"(addr));
+    }
+    if (ND > 0) asm volatile("s_waitcnt lgkmcnt(0)");
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) s += acc[i][0] + (float)x[i] + (float)r[i].x;
+  sink[(size_t)blockIdx.x * 512 + threadIdx.x] = s;
+}
+
+template <int NV, int ND>
+static int launch_issue_mix_t(float* sink, int iters, hipStream_t stream) {
+  hipLaunchKernelGGL((issue_mix_kernel<NV, ND>), dim3(256), dim3(512), 64 * 1024, stream, sink, iters);
+  return (int)hipGetLastError();
+}
+
+// NV in {0, 1, 2, 3, 4, 6}, ND in {0, 2, 4, 8}; -1 for any other combination
+int launch_issue_mix(float* sink, int iters, int nv, int nd, hipStream_t stream) {
+#define MOE_MIX(NV, ND) if (nv == NV && nd == ND) return launch_issue_mix_t<NV, ND>(sink, iters, stream);
+#define MOE_MIX_ROW(NV) MOE_MIX(NV, 0) MOE_MIX(NV, 2) MOE_MIX(NV, 4) MOE_MIX(NV, 8)
+  MOE_MIX_ROW(0) MOE_MIX_ROW(1) MOE_MIX_ROW(2) MOE_MIX_ROW(3) MOE_MIX_ROW(4) MOE_MIX_ROW(6)
+#undef MOE_MIX_ROW
+#undef MOE_MIX
+  return -1;
+}
+
 int launch_stream_read(const void* src, size_t bytes, uint32_t* sink, int grid, hipStream_t stream) {
   hipLaunchKernelGGL(stream_read_kernel, dim3(grid), dim3(256), 0, stream, (const u32x4_t*)src, bytes / 16, sink);
   return (int)hipGetLastError();

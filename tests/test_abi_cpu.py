@@ -141,3 +141,67 @@ def test_product_path_does_not_import_the_oracle():
         "CPU oracle and the HIP path alike", "")
     assert "oracle" not in open(os.path.join(ROOT, "moe_workloads", "fp8.py")).read().replace(
         "The oracle and the HIP path read", "")
+
+
+# ------------------------------------------------------------------ binding-side argument checks
+def _layer_args(torch, T=4, K=256, N=128, E=3, topk=2, g=128, dt=None):
+    dt = dt or torch.float16
+    return dict(
+        X=torch.zeros(T, K, dtype=dt), topk_ids=torch.zeros(T, topk, dtype=torch.int32),
+        topk_weights=torch.zeros(T, topk, dtype=torch.float32),
+        qw1=torch.zeros(E, 2 * N, K // 8, dtype=torch.int32), s1=torch.zeros(E, 2 * N, K // g, dtype=dt),
+        z1=torch.zeros(E, 2 * N, K // g, dtype=torch.uint8),
+        qw2=torch.zeros(E, K, N // 8, dtype=torch.int32), s2=torch.zeros(E, K, N // g, dtype=dt),
+        z2=torch.zeros(E, K, N // g, dtype=torch.uint8), out=torch.zeros(T, K, dtype=dt))
+
+
+@pytest.mark.parametrize("field,make_bad,needle", [
+    ("topk_ids", lambda t, torch: t.to(torch.int64), "topk_ids: dtype"),              # what torch.topk returns
+    ("topk_weights", lambda t, torch: t.to(torch.float64), "topk_weights: dtype"),
+    ("z1", lambda t, torch: t.to(torch.int32), "W1 zeros: dtype"),
+    ("s1", lambda t, torch: t[:, :, :1].contiguous(), "W1 scales: shape"),             # wrong group_size for the scale shape
+    ("s2", lambda t, torch: t.to(torch.float32), "W2 scales: dtype"),
+    ("out", lambda t, torch: t[:2].contiguous(), "out: shape"),                         # undersized result
+    ("qw2", lambda t, torch: t[:, :, :4].contiguous(), "W2"),
+])
+def test_binding_rejects_wrong_dtypes_and_shapes_before_any_launch(binding, field, make_bad, needle):
+    import torch
+    a = _layer_args(torch)
+    a[field] = make_bad(a[field], torch)
+    ws = torch.zeros(1 << 20, dtype=torch.uint8)
+    with pytest.raises(ValueError) as e:          # raised on CPU tensors: no pointer is ever taken
+        binding.moe_w4a16_layer(a["X"], a["topk_ids"], a["topk_weights"], a["qw1"], a["s1"], a["z1"], a["qw2"],
+                                a["s2"], a["z2"], a["out"], 128, ws)
+    assert needle in str(e.value), str(e.value)
+
+
+def test_binding_rejects_short_tables_and_mismatched_outputs(binding):
+    import torch
+    T, topk, E, bm = 8, 2, 4, 16
+    ids = torch.zeros(T, topk, dtype=torch.int32)
+    cap = binding.moe_align_capacity(T, topk, E, bm)
+    ok = dict(expert_counts=torch.zeros(E, dtype=torch.int32), expert_offsets=torch.zeros(E + 1, dtype=torch.int32),
+              sorted_slot_ids=torch.zeros(cap, dtype=torch.int32), block_expert_ids=torch.zeros(cap // bm, dtype=torch.int32),
+              num_padded=torch.zeros(1, dtype=torch.int32))
+    with pytest.raises(ValueError) as e:
+        binding.moe_align_by_expert(ids, E, bm, ok["expert_counts"], ok["expert_offsets"],
+                                    torch.zeros(cap - 1, dtype=torch.int32), ok["block_expert_ids"], ok["num_padded"])
+    assert "sorted_slot_ids" in str(e.value)
+    A = torch.zeros(T, 256, dtype=torch.float16)
+    qw = torch.zeros(E, 64, 32, dtype=torch.int32)
+    s = torch.zeros(E, 64, 2, dtype=torch.float16)
+    z = torch.zeros(E, 64, 2, dtype=torch.uint8)
+    with pytest.raises(ValueError) as e:          # C with the wrong number of columns
+        binding.moe_w4a16_grouped_gemm(A, topk, qw, s, z, ok["sorted_slot_ids"], ok["block_expert_ids"],
+                                       ok["num_padded"], T * topk, 128, bm, torch.zeros(T * topk, 32, dtype=torch.float16))
+    assert "C:" in str(e.value)
+    with pytest.raises(ValueError) as e:          # bf16 scales with fp16 activations
+        binding.moe_w4a16_grouped_gemm(A, topk, qw, s.to(torch.bfloat16), z, ok["sorted_slot_ids"],
+                                       ok["block_expert_ids"], ok["num_padded"], T * topk, 128, bm,
+                                       torch.zeros(T * topk, 64, dtype=torch.float16))
+    assert "scales: dtype" in str(e.value)
+    with pytest.raises(ValueError):
+        binding.moe_silu_mul(torch.zeros(4, 64, dtype=torch.float16), torch.zeros(4, 16, dtype=torch.float16))
+    with pytest.raises(ValueError):
+        binding.moe_combine(torch.zeros(8, 64, dtype=torch.float16), torch.zeros(4, 2, dtype=torch.float64),
+                            torch.zeros(4, 64, dtype=torch.float16))

@@ -305,6 +305,42 @@ def test_combine_matches_oracle(dt, T, topk, K):
     U.assert_close(U.dev_to_f64(out), O.combine(Y, w, dt), "combine")
 
 
+def test_staged_chain_with_invalid_ids_uses_the_masked_combine():
+    """align -> GEMM -> SiLU-and-multiply -> GEMM -> combine through the staged entry points with
+    expert ids outside [0, E): the GEMMs leave the rows of such slots untouched (NaN here), the
+    masked combine lets them contribute zero, as the oracle's combine(slot_valid=...) does."""
+    cfg = MoEConfig("staged_inv", T=40, K=256, N=128, E=5, topk=3, group=128, dtype="f16", seed=44)
+    say(f"staged chain with invalid ids {cfg}")
+    inp = make_inputs(cfg)
+    inp.topk_ids[1, 0] = cfg.E
+    inp.topk_ids[6, 2] = -3
+    inp.topk_ids[9, :] = 77
+    d = U.DevInputs(inp)
+    block_m = 16
+    al = U.run_align(d.ids, cfg.E, block_m)
+    tables = (al["sorted_slot_ids"], al["block_expert_ids"], al["num_padded"])
+    nan = float("nan")
+    H = torch.full((cfg.S, 2 * cfg.N), nan, dtype=torch.float16, device="cuda")
+    M.moe_w4a16_grouped_gemm(d.X, cfg.topk, d.qw1, d.s1, d.z1, *tables, cfg.S, cfg.group, block_m, H)
+    act = torch.empty((cfg.S, cfg.N), dtype=torch.float16, device="cuda")
+    M.moe_silu_mul(H, act)
+    Y = torch.full((cfg.S, cfg.K), nan, dtype=torch.float16, device="cuda")
+    M.moe_w4a16_grouped_gemm(act, 1, d.qw2, d.s2, d.z2, *tables, cfg.S, cfg.group, block_m, Y)
+    out = torch.empty((cfg.T, cfg.K), dtype=torch.float16, device="cuda")
+    M.moe_combine_masked(Y, d.w, d.ids, cfg.E, out)
+    torch.cuda.synchronize()
+    got = U.dev_to_f64(out)
+    assert np.all(got[9] == 0)
+    # the staged chain rounds Y to 16 bits (the fused layer does not): build the reference from the staged oracles
+    X64 = O.decode_bits(inp.x_bits, "f16")
+    se = inp.topk_ids.reshape(-1)
+    Ho = O.grouped_gemm(X64, cfg.topk, inp.qw1, O.decode_bits(inp.s1_bits, "f16"), inp.z1, se, cfg.group, "f16", fill=0.0)
+    Yo = O.grouped_gemm(O.silu_mul(Ho, "f16"), 1, inp.qw2, O.decode_bits(inp.s2_bits, "f16"), inp.z2, se, cfg.group,
+                        "f16", fill=0.0)
+    want = O.combine(Yo, inp.topk_weights, "f16", slot_valid=(se >= 0) & (se < cfg.E))
+    U.assert_close(got, want, "staged chain, masked combine")
+
+
 # ------------------------------------------------------------------ whole layer, element by element
 def oracle_layer(inp, **kw):
     c = inp.cfg
@@ -430,10 +466,15 @@ def test_error_paths_report_status():
         M.moe_w4a16_layer(d.X, d.ids, d.w, d.qw1, d.s1, d.z1, d.qw2, d.s2, d.z2, out, 48, small)
     assert e.value.status == 2
     al = U.run_align(d.ids, 8, 16)
+    H = torch.empty((32, d.qw1.shape[1]), dtype=torch.float16, device="cuda")
     with pytest.raises(M.MoEError) as e:
         M.moe_w4a16_grouped_gemm(d.X, 2, d.qw1, d.s1, d.z1, al["sorted_slot_ids"], al["block_expert_ids"],
-                                 al["num_padded"], 32, 128, 24, out)
+                                 al["num_padded"], 32, 128, 24, H)
     assert e.value.status == 1
+    # a buffer of the wrong shape never reaches the library: the binding refuses it
+    with pytest.raises(ValueError):
+        M.moe_w4a16_grouped_gemm(d.X, 2, d.qw1, d.s1, d.z1, al["sorted_slot_ids"], al["block_expert_ids"],
+                                 al["num_padded"], 32, 128, 16, out)
 
 
 # ------------------------------------------------------------------ full-size seeded configurations
