@@ -189,7 +189,8 @@ def main():
         "config": {"workload": f"{cfg.name}: T={cfg.T} K={cfg.K} N={cfg.N} E={cfg.E} top{cfg.topk} "
                                f"g={cfg.group} {cfg.dtype}, seed {cfg.seed}",
                    "active_experts": E_act, "algorithmic_bytes": layer_bytes, "flop": flops,
-                   "block_m": M.moe_layer_block_m_for(cfg.T, cfg.K, cfg.N, cfg.E, cfg.topk, cfg.group), "tile_override": args.tile or None,
+                   "block_m": (M.moe_layer_block_m(cfg.T, cfg.E, cfg.topk) if args.prepacked else
+                               M.moe_layer_block_m_for(cfg.T, cfg.K, cfg.N, cfg.E, cfg.topk, cfg.group)), "tile_override": args.tile or None,
                    "weights": "operand-order repack (offline)" if args.prepacked else "as stated: [E, rows, K/8] int32"},
         "tflops": round(tflops, 2), "hbm_frac": round(gbs / HBM_PEAK_GBS, 4),
         "mfma_frac": round(tflops / MFMA_PEAK_TFLOPS, 4),
@@ -233,7 +234,8 @@ def main():
 def issue_model(M, torch):
     """ns per matrix instruction and SIMD for a grid of (VALU operations per instruction, LDS fragment
     reads per 8 instructions), two waves per SIMD; `ratio` is against the matrix-only rate of the
-    same run (16 cycles per v_mfma_f32_16x16x32_f16), so ratio * 16 is the cost in SIMD cycles."""
+    same run (16 cycles per v_mfma_f32_16x16x32_f16), so ratio * 16 is the cost in SIMD cycles;
+    `model_cycles` is the fit max(16, 8 + 4 v) + 6 r^2 the kernel design notes reason with."""
     sink = torch.zeros(1 << 18, dtype=torch.int32, device="cuda")
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     iters = 10000
@@ -255,7 +257,7 @@ def issue_model(M, torch):
             t = ns_per_mfma(nv, nd)
             table.append({"valu_per_mfma": nv, "lds_reads_per_mfma": nd / 8.0, "ns_per_mfma": round(t, 3),
                           "ratio": round(t / base, 3), "simd_cycles": round(16.0 * t / base, 1),
-                          "model_8_4v_20r": round(max(16.0, 8 + 4 * nv) + 20.0 * nd / 8.0, 1)})
+                          "model_cycles": round(max(16.0, 8 + 4 * nv) + 6.0 * (nd / 8.0) ** 2, 1)})
     print(json.dumps({"issue_model": {"matrix_only_ns_per_mfma": round(base, 3),
                                       "matrix_only_TFLOPs": round(16384.0 / base * 1024 / 1e3, 1), "table": table}}))
 

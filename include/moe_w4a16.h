@@ -319,8 +319,8 @@ int moe_set_stage_events(void* const* events, int n);
  * mix of the mixed-type GEMM's inner loop without its memory traffic.  valu_per_mfma in
  * {0, 1, 2, 3, 4, 6}, lds_reads_per_8_mfma in {0, 2, 4, 8}.  sink: >= 512 KiB of device scratch.
  * `bench.py --issue-model` times the grid of combinations; the cost model the design notes use
- * (time per matrix instruction = 8 + 4 x VALU + about 20 x LDS reads, in SIMD cycles) is fitted
- * to its output.
+ * (time per matrix instruction = max(16, 8 + 4 x VALU) SIMD cycles, plus 0.5 to 7 cycles for the
+ * LDS reads) is fitted to its output.
  */
 int moe_probe_stream_read(const void* src, size_t bytes, void* sink, void* stream);
 int moe_probe_mfma(void* sink, int iters, void* stream);
