@@ -362,7 +362,12 @@ __device__ __forceinline__ void feature_of(int n_tile, int wave, int sub, int n,
 // WV = 8: eight wavefronts per workgroup (two per SIMD) share one activation tile; wave w owns
 // features [w*16*NT, (w+1)*16*NT) of a tile of 128*NT features.
 template <int DT, int MT, int NT, int KS, int KW, int FUSE, int SZR, int PRE = 0, int WV = 4>
-__global__ void __launch_bounds__(64 * WV, (WV == 8 ? 1 : ((MT * NT <= 4 || (SZR && MT <= 4) || (PRE == 2 && NT <= 2)) ? 2 : 1)))
+// Minimum workgroups per CU: two wherever the tile's registers fit 256 per lane.  Besides the
+// occupancy this decides where the accumulators live: with a budget above 256 registers the
+// compiler keeps them in accumulation registers, which VALU instructions cannot address, and
+// every rescale of an accumulator becomes read + multiply + write back (the 64-row tile without
+// register scales spent a quarter of its VALU instructions on those copies).
+__global__ void __launch_bounds__(64 * WV, (WV == 8 ? 1 : ((MT * NT <= 4 || (MT * NT <= 8 && MT <= 4) || (SZR && MT <= 4) || (PRE == 2 && NT <= 2)) ? 2 : 1)))
 w4a16_gemm_kernel(const GemmParams p) {
   static_assert(SZR == 0 || KW == 4, "register-resident scales need 128-k chunk-steps (group 128)");
   static_assert(PRE == 0 || (SZR == 1 && (FUSE == 1 || NT >= 2)), "operand-order weights: register-scale, paired tiles");
