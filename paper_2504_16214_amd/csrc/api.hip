@@ -955,6 +955,7 @@ static int fp8_pick_block_m(long long S, int E) {
   if (g_fp8_layer_block_m > 0) return g_fp8_layer_block_m;
   const long long avg = S / (E > 0 ? E : 1);
   if (avg <= 32) return 32;      // measured: 32-token tiles stream the weights fastest at a few rows per expert
+  if (avg >= 96) return 128;     // about one row block per expert: its weights are fetched once (measured +2 %)
   return 64;
 }
 

@@ -83,14 +83,19 @@ fp8_blockwise_gemm_kernel(const GemmParams p) {
   const int ln = lane & 15, lj = lane >> 4;
 
   // hardware block id -> logical tile: consecutive ids go round the 8 XCDs, so give every XCD a
-  // contiguous range of tiles
-  const int total = gridDim.x;
+  // contiguous range of tiles.  The grouped launch is sized for the bucketing capacity; its ranges
+  // are cut over the row blocks that really exist (num_padded), so the unused capacity does not
+  // leave the last XCDs without work, and the surplus workgroups exit here.
+  const bool grouped = p.sorted_slot_ids != nullptr;
+  const int n_blocks = p.N / BN;
+  const int m_blocks = grouped ? *p.num_padded / BM : (p.M + BM - 1) / BM;
+  const int total = grouped ? m_blocks * n_blocks : (int)gridDim.x;
   int L;
   {
-    const int id = blockIdx.x, q = total >> 3, r = total & 7, x = id & 7;
-    L = x * q + (x < r ? x : r) + (id >> 3);
+    const int id = blockIdx.x, q = total >> 3, r = total & 7, x = id & 7, idx = id >> 3;
+    if (idx >= q + (x < r ? 1 : 0)) return;       // (uniform over the workgroup: nobody reaches a barrier)
+    L = x * q + (x < r ? x : r) + idx;
   }
-  const int m_blocks = (p.M + BM - 1) / BM, n_blocks = p.N / BN;
   const int split = L / (m_blocks * n_blocks);
   L -= split * (m_blocks * n_blocks);
   // inside a split, tiles are walked in groups of group_m row blocks: feature block by feature block
@@ -116,7 +121,6 @@ fp8_blockwise_gemm_kernel(const GemmParams p) {
   // therefore fetches chunk s ^ (r & 7) of that row.  Pass i of the workgroup covers tile rows
   // [RPP i, RPP (i + 1)), wave w rows 8 w .. 8 w + 7 of the pass.
   const int srow = tid >> 3, sc = tid & 7;
-  const bool grouped = p.sorted_slot_ids != nullptr;
   const uint8_t* Bmat = p.B;
   const float* bsmat = p.b_scale;
   if (grouped) {
