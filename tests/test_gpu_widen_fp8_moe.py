@@ -241,3 +241,26 @@ def test_fp8_layer_full_size_decode_sampled_tokens():
     want = oracle_fp8_layer(inp, tokens=tokens)
     assert_layer_close(got[tokens], want, "fp8_moe_decode sampled tokens")
     assert np.array_equal(got, run_fp8_layer(inp)), "layer is not run-to-run deterministic"
+
+
+def test_fp8_layer_full_size_prefill_sampled_tokens():
+    """The DeepSeek-shaped prefill batch (T = 4096, about 128 rows per expert: 128-slot blocks, most
+    experts own one full block and a second, partly filled one): the first and the last token plus
+    tokens chosen to cover many experts, in the launch configuration the benchmark times."""
+    cfg = FP8_MOE_CONFIGS["fp8_moe_prefill"]
+    say(f"fp8 layer full size {cfg}: generating")
+    inp = make_fp8_moe_inputs(cfg)
+    got = run_fp8_layer(inp)
+    chosen, seen = [0, cfg.T - 1], set()
+    for t in chosen:
+        seen.update(int(e) for e in inp.topk_ids[t])
+    while len(chosen) < 8:
+        gain = np.array([len(set(r.tolist()) - seen) for r in inp.topk_ids])
+        gain[chosen] = -1
+        t = int(np.argmax(gain))
+        chosen.append(t)
+        seen.update(int(e) for e in inp.topk_ids[t])
+    tokens = sorted(chosen)
+    say(f"fp8 layer full size: oracle for tokens {tokens} ({len(seen)} distinct experts)")
+    want = oracle_fp8_layer(inp, tokens=tokens)
+    assert_layer_close(got[tokens], want, "fp8_moe_prefill sampled tokens")
