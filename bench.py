@@ -50,6 +50,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=100)
     ap.add_argument("--config", default="deepseek_decode")
     ap.add_argument("--tile", default="", help="mt,nt override of the GEMM tile (tuning)")
+    ap.add_argument("--tokens", type=int, default=0,
+                    help="run the named W4A16 configuration with this many tokens instead of its own T (the paper's "
+                         "Fig. 10 sweeps the token number on one layer shape); the workload string says so")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--prepacked", action="store_true",
                     help="time moe_w4a16_layer_prepacked on weights repacked offline into operand order "
@@ -84,6 +87,9 @@ def main():
         issue_model(M, torch)
         return
     cfg = CONFIGS[args.config]
+    if args.tokens > 0:
+        import dataclasses
+        cfg = dataclasses.replace(cfg, T=args.tokens)
     if args.copy_calibration:
         src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")      # 1 GiB
         dst = torch.empty_like(src)
@@ -160,7 +166,7 @@ def main():
 
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
-    if os.path.exists(tpath):
+    if os.path.exists(tpath) and not args.tokens:
         try:
             key = cfg.name + ("_prepacked" if args.prepacked else "")
             traffic = json.load(open(tpath)).get(key, {}).get("gemm1_bytes_per_launch")
@@ -188,6 +194,7 @@ def main():
         "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": f"{cfg.name}: T={cfg.T} K={cfg.K} N={cfg.N} E={cfg.E} top{cfg.topk} "
                                f"g={cfg.group} {cfg.dtype}, seed {cfg.seed}",
+                   "tokens_override": bool(args.tokens),
                    "active_experts": E_act, "algorithmic_bytes": layer_bytes, "flop": flops,
                    "block_m": (M.moe_layer_block_m(cfg.T, cfg.E, cfg.topk) if args.prepacked else
                                M.moe_layer_block_m_for(cfg.T, cfg.K, cfg.N, cfg.E, cfg.topk, cfg.group)), "tile_override": args.tile or None,

@@ -288,7 +288,7 @@ int moe_w4a16_routed_layer(const void* X, const float* logits, const float* bias
  * the built-in choice; 0 restores it.  Thread-local.
  *
  * moe_layer_block_m_for: the same with the layer's shapes known (group-128 layers with
- * K % 1024 == 0 and N % 1024 == 0 and about 100 or more rows per expert take 128-slot blocks for
+ * K % 1024 == 0 and N % 1024 == 0 and more than 28 rows per expert take 128-slot blocks for
  * the eight-wave tile); honours moe_set_block_m_override.
  *
  * moe_set_wide_tiles: 0 = use the eight-wave 128-token tile whenever block_m >= 128 and the shape

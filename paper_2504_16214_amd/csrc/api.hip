@@ -282,10 +282,14 @@ static int run_gemm(const GemmArgs& a, hipStream_t stream) {
 static int pick_block_m(long long S, int E, bool wide_ok = false) {
   const long long avg = S / (E > 0 ? E : 1);
   if (avg <= 8) return 16;
-  if (avg <= 24) return 32;
-  // 128-slot blocks only for the eight-wave tile (every unpacked weight feeds eight matrix
-  // instructions); the four-wave 128-slot tiles run one workgroup per CU and lose to 64-slot ones
-  if (wide_ok && avg >= 96) return 128;
+  if (avg <= (wide_ok ? 28 : 24)) return 32;
+  // 128-slot blocks only for the eight-wave tile (every unpacked weight feeds up to eight matrix
+  // instructions and its main loop skips the block's empty 16-row sub-tiles, so a block that is a
+  // quarter full costs a quarter of the matrix work); the four-wave 128-slot tiles run one
+  // workgroup per CU and lose to 64-slot ones.  Measured on the 256-expert layer shape: 32 rows per
+  // expert 1.73 against 1.88 ms, 48 rows a tie, 64 rows 2.40 against 2.90 ms; up to 28 rows the
+  // 32-slot tile wins (28 rows: 1.65 ms for both, 64-slot blocks 1.86).
+  if (wide_ok) return 128;
   return 64;
 }
 

@@ -74,6 +74,14 @@ def test_layer_block_choice_tracks_rows_per_expert(binding):
     assert binding.moe_layer_block_m(128, 256, 8) == 16      # about 4 rows per expert
     assert binding.moe_layer_block_m(64, 8, 2) == 32         # 16 rows per expert
     assert binding.moe_layer_block_m(4096, 256, 8) == 64     # 128 rows per expert
+    # with the layer's shapes known: the eight-wave tile (group 128, K and N multiples of 1024)
+    # takes 128-slot blocks from 29 rows per expert on; other shapes keep 64-slot blocks
+    f = binding.moe_layer_block_m_for
+    assert f(128, 7168, 2048, 256, 8, 128) == 16
+    assert f(896, 7168, 2048, 256, 8, 128) == 32             # 28 rows per expert
+    assert f(1024, 7168, 2048, 256, 8, 128) == 128           # 32 rows per expert
+    assert f(4096, 7168, 2048, 256, 8, 128) == 128
+    assert f(1024, 2048, 1408, 64, 6, 64) == 64              # group 64: no eight-wave tile
 
 
 def test_validation_before_launch_returns_status(binding):
