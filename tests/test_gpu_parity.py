@@ -644,3 +644,20 @@ def test_full_size_config_stratified(name, n_tokens):
     assert np.array_equal(got, U.dev_to_f64(U.run_layer(d))), "layer is not run-to-run deterministic"
     say(f"full-size stratified {name}: layer on operand-order weights, same tokens")
     U.assert_close(U.dev_to_f64(prepacked_layer(d))[tokens], want, f"{name} prepacked layer tokens {tokens}")
+
+
+def test_layer_large_batch_byte_offsets_beyond_4_gib():
+    """T = 16384 on the 256-expert layer shape: 131072 slots, a float32 down-projection plane of
+    3.76 GB, i.e. byte offsets past 2^32 in the workspace.  The first token, one in the middle and
+    the last two (whose slots sit at the far end of every intermediate) against the oracle."""
+    import dataclasses
+    cfg = dataclasses.replace(CONFIGS["deepseek_prefill"], T=16384)
+    say(f"large batch {cfg}: generating")
+    inp = make_inputs(cfg)
+    d = U.DevInputs(inp)
+    got = U.dev_to_f64(U.run_layer(d))
+    tokens = [0, cfg.T // 2 + 1, cfg.T - 2, cfg.T - 1]
+    say(f"large batch: oracle for tokens {tokens}")
+    want = oracle_layer(inp, tokens=tokens)
+    worst = U.assert_close(got[tokens], want, f"T={cfg.T} layer tokens {tokens}")
+    say(f"  layer worst error / bound = {worst:.4f}")
