@@ -128,23 +128,55 @@ def _gaussian_code_table() -> np.ndarray:
     return _cast_e4m3((z / 4.5 * 448.0).astype(np.float32))
 
 
-def _draw_fp8_weight(rng: np.random.Generator, table: np.ndarray, E: int, rows: int, red: int):
+def _draw_fp8_weight(rng: np.random.Generator, table: np.ndarray, E: int, rows: int, red: int, seed_key=None):
+    """Codes: one generator per expert when seed_key is given (seed sequence seed_key + [e]), so the
+    experts can be drawn by several threads with the same result for any thread count; otherwise
+    from rng, expert after expert.  Scales: from rng."""
     codes = np.empty((E, rows, red), dtype=np.uint8)
-    for e in range(E):      # per expert to bound temporaries
-        codes[e] = table[rng.integers(0, 256, size=(rows, red), dtype=np.uint8)]
+
+    def draw(e, g):
+        u = g.integers(0, 256, size=(rows, red), dtype=np.uint8)
+        np.take(table, u, out=codes[e], mode="wrap")       # (wrap: no bounds pass; the indices are bytes)
+
+    if seed_key is None:
+        for e in range(E):      # per expert to bound temporaries
+            draw(e, rng)
+    else:
+        import os
+        from concurrent.futures import ThreadPoolExecutor
+        with ThreadPoolExecutor(max_workers=max(1, min(16, os.cpu_count() or 1))) as pool:
+            list(pool.map(lambda e: draw(e, np.random.default_rng(list(seed_key) + [e])), range(E)))
     scale = (rng.uniform(0.5, 1.5, size=(E, -(-rows // BLOCK), red // BLOCK)) * (SIGMA_W * 4.5 / 448.0))
     return codes, scale.astype(np.float32)
 
 
+_WEIGHT_CACHE: dict = {}      # the last weight set drawn, keyed by (E, K, N, seed)
+
+
+def _fp8_moe_weights(cfg: Fp8MoEConfig):
+    """The layer's weights come from generators of their own, so configurations that differ only in
+    the token number share them: the codes of expert e of W1 / W2 from the seed sequence
+    [cfg.seed, 1, 1 or 2, e], the block scales (W1 then W2) from [cfg.seed, 1].  The last set is
+    kept and handed out again (11 GB at 256 experts): callers must not write into the arrays."""
+    key = (cfg.E, cfg.K, cfg.N, cfg.seed)
+    if key not in _WEIGHT_CACHE:
+        _WEIGHT_CACHE.clear()
+        rng = np.random.default_rng([cfg.seed, 1])
+        table = _gaussian_code_table()
+        w1c, w1s = _draw_fp8_weight(rng, table, cfg.E, 2 * cfg.N, cfg.K, seed_key=(cfg.seed, 1, 1))
+        w2c, w2s = _draw_fp8_weight(rng, table, cfg.E, cfg.K, cfg.N, seed_key=(cfg.seed, 1, 2))
+        _WEIGHT_CACHE[key] = (w1c, w1s, w2c, w2s)
+    return _WEIGHT_CACHE[key]
+
+
 def make_fp8_moe_inputs(cfg: Fp8MoEConfig) -> Fp8MoEInputs:
-    """Draw order: X, logits, W1 (codes, scales), W2 (codes, scales); numpy PCG64 seeded with cfg.seed."""
+    """Activations and routing: numpy PCG64 seeded with the sequence [cfg.seed, 0], draw order X,
+    logits.  Weights: _fp8_moe_weights."""
     from . import route_topk, to_bits
     assert cfg.K % BLOCK == 0 and cfg.N % BLOCK == 0
-    rng = np.random.default_rng(cfg.seed)
+    rng = np.random.default_rng([cfg.seed, 0])
     x = (0.5 * rng.standard_normal((cfg.T, cfg.K))).astype(np.float32)
     logits = rng.standard_normal((cfg.T, cfg.E)).astype(np.float32)
     ids, w = route_topk(logits, cfg.topk)
-    table = _gaussian_code_table()
-    w1c, w1s = _draw_fp8_weight(rng, table, cfg.E, 2 * cfg.N, cfg.K)
-    w2c, w2s = _draw_fp8_weight(rng, table, cfg.E, cfg.K, cfg.N)
+    w1c, w1s, w2c, w2s = _fp8_moe_weights(cfg)
     return Fp8MoEInputs(cfg, to_bits(x, cfg.dtype), ids, w, w1c, w1s, w2c, w2s)

@@ -15,10 +15,17 @@ of H, act or out (one ulp = 2^-8 relative in bf16), and (c) wherever a flipped a
 an e4m3 rounding boundary, one code moving by one step (at most 2^-3 of that one product).  (c) has
 no useful worst case: it is bounded statistically.  With a fraction p of moved codes, the down
 projection moves by about sqrt(p * N) * 2^-3 * rms(product) = sqrt(p) * 2^-3 * rms(Y); p is
-measured (and asserted) below 2 %, giving 0.018 * rms(Y).  The test allows
-    |gpu - oracle| <= 2^-6 * |oracle| + 0.05 * rms(oracle),
-about three times that, and checks that planted mistakes (a neighbouring scale, swapped gate/up)
-miss it by an order of magnitude."""
+measured (and asserted) below 2 %, giving 0.018 * rms(Y); the test takes about three times that
+as the bound a correct output meets,
+    |gpu - oracle| <= 2^-6 * |oracle| + 0.05 * rms(oracle).
+Being statistical, the term has a tail: ONE moved code shifts an output by 2^-3 * |product|
+= 2^-3 * kappa / sqrt(N) of rms(Y) (kappa = |product| / rms(product)), and a product of two roughly
+Gaussian factors reaches kappa = 8 ... 10 somewhere in 10^5 ... 10^6 outputs, i.e. 0.06 ... 0.08 of
+rms(Y) at N = 256; a moved code touches every output of its slot (the ones with a large weight in
+that column stick out together), and a flipped tile maximum moves several codes of one tile at
+once.  So the test requires the bound above for all but one output in 10^3 (measured: at most one
+in 10^4), and five times the bound for every output; planted mistakes (a neighbouring scale,
+swapped gate/up) must leave more than a tenth of the outputs outside the bound (measured: 86 %)."""
 from __future__ import annotations
 
 import sys
@@ -124,8 +131,12 @@ def layer_bound(want):
 def assert_layer_close(got, want, what):
     assert np.all(np.isfinite(got)), f"{what}: non-finite output"
     ratio = np.abs(got - want) / layer_bound(want)
-    say(f"{what}: max err / bound = {ratio.max():.3f}, rms(ref) = {np.sqrt(np.mean(want ** 2)):.4g}")
-    assert ratio.max() <= 1.0, f"{what}: {int((ratio > 1).sum())} of {ratio.size} outside the bound"
+    outside = int((ratio > 1).sum())
+    allowed = max(1, int(np.ceil(1e-3 * ratio.size)))
+    say(f"{what}: max err / bound = {ratio.max():.3f}, {outside} of {ratio.size} outside (allowed {allowed}), "
+        f"rms(ref) = {np.sqrt(np.mean(want ** 2)):.4g}")
+    assert outside <= allowed, f"{what}: {outside} of {ratio.size} outside the bound (allowed {allowed})"
+    assert ratio.max() <= 5.0, f"{what}: an output misses the bound {ratio.max():.2f} times over"
     return float(ratio.max())
 
 
@@ -189,9 +200,9 @@ def test_fp8_layer_moved_codes_are_rare_and_mistakes_are_caught():
                              np.concatenate([inp.w1_scale[:, N // 128:], inp.w1_scale[:, :N // 128]], axis=1),
                              inp.w2_codes, inp.w2_scale, cfg.dtype)
     for name, wrong in (("neighbouring W2 block scale", wrong_scale), ("gate/up swapped", wrong_gate)):
-        miss = float((np.abs(got - wrong) / layer_bound(wrong)).max())
-        say(f"  planted mistake '{name}': max err / bound = {miss:.1f}")
-        assert miss > 5.0
+        r = np.abs(got - wrong) / layer_bound(wrong)
+        say(f"  planted mistake '{name}': max err / bound = {r.max():.1f}, outside the bound: {np.mean(r > 1):.1%}")
+        assert r.max() > 5.0 and np.mean(r > 1) > 0.1
 
 
 def test_fp8_layer_invalid_ids_permutation_and_errors():
