@@ -26,6 +26,7 @@ namespace moe {
 
 constexpr int kAlignWaves = 16;
 constexpr int kAlignThreads = 64 * kAlignWaves;
+constexpr int kAlignBatch = 8;      // tiles of 64 slot ids a wave fetches before it processes them
 
 // The bucketing proper; every thread of the (single) workgroup calls it.  `topk_ids` is not
 // restrict-qualified: in the fused kernel the same workgroup wrote it just before.
@@ -48,12 +49,18 @@ align_body(const int32_t* topk_ids, int S, int E, int block_m, int capacity, int
   const int begin = wave * per_wave;
   const int end = begin + per_wave < S ? begin + per_wave : S;
 
-  for (int s0 = begin; s0 < end; s0 += 64) {
-    const int s = s0 + lane;
-    if (s < end) {
-      const int e = topk_ids[s];
-      if (e >= 0 && e < E) atomicAdd(&hist[wave * E + e], 1);
+  // (both walks fetch kAlignBatch tiles of 64 ids ahead of using them: with one load per trip the
+  // walk of a large batch is a chain of memory latencies)
+  for (int s0 = begin; s0 < end; s0 += 64 * kAlignBatch) {
+    int ev[kAlignBatch];
+#pragma unroll
+    for (int u = 0; u < kAlignBatch; ++u) {
+      const int s = s0 + 64 * u + lane;
+      ev[u] = s < end ? topk_ids[s] : -1;
     }
+#pragma unroll
+    for (int u = 0; u < kAlignBatch; ++u)
+      if (ev[u] >= 0 && ev[u] < E) atomicAdd(&hist[wave * E + ev[u]], 1);
   }
   __syncthreads();
 
@@ -94,27 +101,34 @@ align_body(const int32_t* topk_ids, int S, int E, int block_m, int capacity, int
   __syncthreads();
 
   // scatter in slot order
-  for (int s0 = begin; s0 < end; s0 += 64) {
-    const int s = s0 + lane;
-    int e = -1;
-    if (s < end) {
-      e = topk_ids[s];
+  for (int s0 = begin; s0 < end; s0 += 64 * kAlignBatch) {
+    int ev[kAlignBatch];
+#pragma unroll
+    for (int u = 0; u < kAlignBatch; ++u) {
+      const int s = s0 + 64 * u + lane;
+      ev[u] = s < end ? topk_ids[s] : -1;
+    }
+#pragma unroll
+    for (int u = 0; u < kAlignBatch; ++u) {      // tiles in slot order
+      if (s0 + 64 * u >= end) break;             // (wave-uniform)
+      const int s = s0 + 64 * u + lane;
+      int e = ev[u];
       if (e < 0 || e >= E) e = -1;
-    }
-    const bool valid = e >= 0;
-    unsigned long long same = __ballot(valid);
-    for (int b = 0; b < id_bits; ++b) {
-      const bool bit = (e >> b) & 1;
-      const unsigned long long m = __ballot(valid && bit);
-      same &= bit ? m : ~m;
-    }
-    if (valid) {
-      const unsigned long long below = same & ((1ull << lane) - 1ull);
-      const int rank = __popcll(below);
-      int* ctr = &hist[wave * E + e];
-      const int base = *ctr;
-      sorted_slot_ids[base + rank] = s;
-      if (rank == 0) *ctr = base + __popcll(same);   // after every lane of the group has read it
+      const bool valid = e >= 0;
+      unsigned long long same = __ballot(valid);
+      for (int b = 0; b < id_bits; ++b) {
+        const bool bit = (e >> b) & 1;
+        const unsigned long long m = __ballot(valid && bit);
+        same &= bit ? m : ~m;
+      }
+      if (valid) {
+        const unsigned long long below = same & ((1ull << lane) - 1ull);
+        const int rank = __popcll(below);
+        int* ctr = &hist[wave * E + e];
+        const int base = *ctr;
+        sorted_slot_ids[base + rank] = s;
+        if (rank == 0) *ctr = base + __popcll(same);   // after every lane of the group has read it
+      }
     }
   }
 
