@@ -275,3 +275,20 @@ def test_fp8_layer_full_size_prefill_sampled_tokens():
     say(f"fp8 layer full size: oracle for tokens {tokens} ({len(seen)} distinct experts)")
     want = oracle_fp8_layer(inp, tokens=tokens)
     assert_layer_close(got[tokens], want, "fp8_moe_prefill sampled tokens")
+
+
+def test_fp8_layer_on_random_shapes():
+    """Thirty seeded random shapes (1 to 900 tokens, 1 to 32 experts, K up to 1536, N up to 1024,
+    both 16-bit types), whole output against the oracle with the bound of this module."""
+    rng = np.random.default_rng(21)
+    for case in range(30):
+        K = 128 * int(rng.integers(1, 13))
+        N = 128 * int(rng.integers(1, 9))
+        E = int(rng.integers(1, 33))
+        topk = int(rng.integers(1, min(E, 8) + 1))
+        T = int(rng.choice([1, 3, 16, 40, 130, 300, 900]))
+        dt = "bf16" if rng.random() < 0.6 else "f16"
+        cfg = Fp8MoEConfig(f"fp8_random{case}", T=T, K=K, N=N, E=E, topk=topk, dtype=dt, seed=500 + case)
+        say(f"fp8 layer random shape {case}: {cfg}")
+        inp = make_fp8_moe_inputs(cfg)
+        assert_layer_close(run_fp8_layer(inp), oracle_fp8_layer(inp), cfg.name)
