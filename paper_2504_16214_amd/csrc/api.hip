@@ -1,6 +1,7 @@
 // Host side of the C ABI declared in include/moe_w4a16.h: argument validation, tile choice,
 // workspace carving and kernel launches.  No allocation, no synchronisation, caller's stream.
 #include <hip/hip_runtime.h>
+#include <algorithm>
 #include <stdarg.h>
 #include <stdint.h>
 #include <stdio.h>
@@ -279,17 +280,19 @@ static int run_gemm(const GemmArgs& a, hipStream_t stream) {
   return MOE_OK;
 }
 
-static int pick_block_m(long long S, int E, bool wide_ok = false) {
+// wide_shape: the layer's shapes admit the eight-wave tile; wide_tile: it will be used (not with
+// operand-order weights, which only the four-wave tiles read)
+static int pick_block_m(long long S, int E, bool wide_shape = false, bool wide_tile = false) {
   const long long avg = S / (E > 0 ? E : 1);
   if (avg <= 8) return 16;
-  if (avg <= (wide_ok ? 28 : 24)) return 32;
+  if (avg <= (wide_shape ? 28 : 24)) return 32;
   // 128-slot blocks only for the eight-wave tile (every unpacked weight feeds up to eight matrix
   // instructions and its main loop skips the block's empty 16-row sub-tiles, so a block that is a
   // quarter full costs a quarter of the matrix work); the four-wave 128-slot tiles run one
   // workgroup per CU and lose to 64-slot ones.  Measured on the 256-expert layer shape: 32 rows per
   // expert 1.73 against 1.88 ms, 48 rows a tie, 64 rows 2.40 against 2.90 ms; up to 28 rows the
   // 32-slot tile wins (28 rows: 1.65 ms for both, 64-slot blocks 1.86).
-  if (wide_ok) return 128;
+  if (wide_tile) return 128;
   return 64;
 }
 
@@ -328,7 +331,8 @@ static Workspace carve(long long T, int K, int N, int E, int topk) {
   w.blocks = o;      o += round_up((align_capacity(S, E, 16) / 16 + 1) * 4, 256);
   w.act = o;         o += round_up((size_t)S * N * 2, 256);
   // float32 (combined unrounded); one plane per reduction split (at most 8, small batches only)
-  w.Y = o;           o += round_up((size_t)S * K * 4 * pick_k_splits(S, E, K, N, pick_block_m(S, E)), 256);
+  w.Y = o;           o += round_up((size_t)S * K * 4 * std::max(pick_k_splits(S, E, K, N, pick_block_m(S, E)),
+                                                            pick_k_splits(S, E, K, N, pick_block_m(S, E, true))), 256);
   w.total = o;
   return w;
 }
@@ -514,7 +518,7 @@ int moe_layer_block_m(int T, int E, int topk) {
 int moe_layer_block_m_for(int T, int K, int N, int E, int topk, int group_size) {
   if (T < 0 || K < 1 || N < 1 || E < 1 || topk < 1 || group_size < 1) return 0;
   if (g_force_block_m > 0) return g_force_block_m;
-  return pick_block_m((long long)T * topk, E, layer_wide_ok(K, N, group_size));
+  return pick_block_m((long long)T * topk, E, layer_wide_ok(K, N, group_size), layer_wide_ok(K, N, group_size));
 }
 
 }  // extern "C"
@@ -589,7 +593,7 @@ static int layer_impl(const void* X, const int32_t* topk_ids, const float* topk_
   // a forced bucketing block wins; a forced token tile (tuning hook) also fixes the block
   const int block_m = g_force_block_m > 0 ? g_force_block_m
                       : (g_force_mt == 1 || g_force_mt == 2 || g_force_mt == 4 || g_force_mt == 8)
-                          ? 16 * g_force_mt : pick_block_m(S, E, !pre && layer_wide_ok(K, N, group_size));
+                          ? 16 * g_force_mt : pick_block_m(S, E, layer_wide_ok(K, N, group_size), !pre && layer_wide_ok(K, N, group_size));
   const bool ev = g_nevents == 5;
 
   if (ev) (void)hipEventRecord((hipEvent_t)g_events[0], stream);
