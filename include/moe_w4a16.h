@@ -48,7 +48,14 @@ typedef enum {
   MOE_HIP_ERROR = 4
 } moe_status;
 
-typedef enum { MOE_F16 = 0, MOE_BF16 = 1 } moe_dtype;
+/* Any int may arrive here from a C caller (the entry points answer MOE_INVALID_ARGUMENT to values
+ * other than these two); for a C++ translation unit the enumeration therefore has int as its fixed
+ * underlying type, so that reading such a value is defined. */
+#ifdef __cplusplus
+typedef enum moe_dtype : int { MOE_F16 = 0, MOE_BF16 = 1 } moe_dtype;
+#else
+typedef enum moe_dtype { MOE_F16 = 0, MOE_BF16 = 1 } moe_dtype;
+#endif
 
 /* Message for the last non-OK status returned on this thread ("" if none). */
 const char* moe_last_error(void);

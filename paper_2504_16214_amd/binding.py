@@ -36,7 +36,9 @@ class MoEError(RuntimeError):
 
 
 def library_path() -> str:
-    return os.path.join(_HERE, "libmoe_w4a16.so")
+    """The in-tree library, or the file MOE_W4A16_LIBRARY names (e.g. the build with the sanitized
+    host layer); there is no search and no fallback."""
+    return os.environ.get("MOE_W4A16_LIBRARY") or os.path.join(_HERE, "libmoe_w4a16.so")
 
 
 def load_library() -> ctypes.CDLL:

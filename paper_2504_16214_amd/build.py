@@ -1,6 +1,7 @@
 """Builds libmoe_w4a16.so (HIP, gfx950 only) in-tree with hipcc.
 
-    python -m paper_2504_16214_amd.build
+    python -m paper_2504_16214_amd.build                 # the library
+    python -m paper_2504_16214_amd.build --host-ubsan    # plus a copy with a sanitized host layer
 
 Objects go to paper_2504_16214_amd/_build/, the library next to this file.
 """
@@ -65,5 +66,32 @@ def build(jobs: int | None = None, verbose: bool = True) -> str:
     return LIB
 
 
+def build_host_ubsan(verbose: bool = True) -> str:
+    """A second library, libmoe_w4a16_hostubsan.so, whose HOST code of the C ABI layer (api.hip:
+    argument checks, tile and workspace arithmetic, launches) is compiled with the undefined-
+    behaviour sanitizer in trapping mode (no runtime library: undefined behaviour executes a trap
+    instruction); device code and the other objects are those of build().  Point the binding at it
+    with MOE_W4A16_LIBRARY=<path> and run the tests: a trap ends the process with SIGILL."""
+    lib = build(verbose=False)
+    obj = os.path.join(BUILD, "api_hostubsan.o")
+    cmd = [HIPCC, *[f for f in FLAGS if f != "-O3"], "-O1", "-g",
+           "-Xarch_host", "-fsanitize=undefined", "-Xarch_host", "-fsanitize-trap=all",
+           "-c", os.path.join(CSRC, "api.hip"), "-o", obj]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError(f"hipcc failed for the sanitized api.hip:\n{r.stderr}")
+    objs = [obj if u[1] == "api.o" else os.path.join(BUILD, u[1]) for u in _units()]
+    out = os.path.join(HERE, "libmoe_w4a16_hostubsan.so")
+    r = subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", out, *objs], capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError(f"link failed:\n{r.stderr}")
+    if verbose:
+        print(f"built {lib} and {out}")
+    return out
+
+
 if __name__ == "__main__":
-    build()
+    if "--host-ubsan" in sys.argv[1:]:
+        build_host_ubsan()
+    else:
+        build()
